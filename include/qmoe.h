@@ -1,0 +1,241 @@
+/*
+ * qmoe.h -- C ABI of the compressed-MoE inference hot path for AMD MI355X (gfx950).
+ *
+ * The library implements the inference side of QMoE (arxiv 2310.16795,
+ * Section 4.3): expert weight matrices are ternary ({-s, 0, +s} with one
+ * scale per output row), stored as a stream of 16-bit codewords that index a
+ * static dictionary of variable-length ternary runs, and are multiplied with
+ * the tokens routed to the expert while being decoded on the fly.
+ *
+ * Conventions
+ *  - A matrix is [rows = output features][cols = input features]; every row is
+ *    an independent codeword stream (Section 4.3.1), rows are packed back to
+ *    back, row_off[r] is the index (in codewords) of row r's first codeword and
+ *    row_off[rows] the total (Section 4.3.3 "Encoding").
+ *  - Ternary symbols: 0 -> 0, 1 -> -s_r (the paper's w_min), 2 -> +s_r (w_max).
+ *  - "host" / "device" after a pointer says where the memory must live.  The
+ *    library never allocates or frees device memory and never synchronises:
+ *    device work is enqueued on the caller's stream (a hipStream_t passed as
+ *    void*, NULL = the default stream) and the call returns at once.
+ *  - Every function returns QMOE_OK or a negative qmoe_status.  Argument
+ *    errors are found before anything is enqueued.  The contents of device
+ *    buffers are trusted: a corrupt codeword stream is not detected on the
+ *    device (run qmoe_validate_host on the host copy first); the kernels clamp
+ *    every index they derive from it, so such a stream gives wrong numbers,
+ *    never an out-of-bounds access.
+ *  - Nothing crosses the boundary but plain pointers, sizes and the opaque
+ *    qmoe_dict handle.  The only global state is the last HIP error code.
+ */
+#ifndef QMOE_H
+#define QMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int qmoe_status;
+#define QMOE_OK 0
+#define QMOE_E_INVALID_ARG (-1)      /* NULL pointer, non-positive size, odd cols, ... */
+#define QMOE_E_BUFFER_TOO_SMALL (-2) /* output capacity too small; the needed size is reported */
+#define QMOE_E_BAD_SYMBOL (-3)       /* ternary input outside {-1,0,+1}, or symbol value 3 in a table */
+#define QMOE_E_CORRUPT_STREAM (-4)   /* a row does not decode to exactly cols values, bad offsets */
+#define QMOE_E_WORKSPACE (-5)        /* workspace missing, misaligned or too small */
+#define QMOE_E_HIP (-6)              /* a HIP call failed; see qmoe_last_hip_error() */
+#define QMOE_E_UNENCODABLE (-7)      /* the dictionary lacks a phrase needed for this input */
+#define QMOE_E_NOMEM (-8)            /* host allocation failed */
+#define QMOE_E_NO_DEVICE_DICT (-9)   /* device call before qmoe_dict_upload */
+#define QMOE_E_LIMIT (-10)           /* size beyond what the kernels support (see each call) */
+
+const char *qmoe_strerror(qmoe_status s);
+/* hipError_t of the most recent failed HIP call made by this library (0 = none). */
+int qmoe_last_hip_error(void);
+
+/* ------------------------------------------------------------------------- */
+/* Dictionary (Section 4.3.2, Algorithm 1)                                    */
+/* ------------------------------------------------------------------------- */
+
+typedef struct qmoe_dict qmoe_dict; /* host object; immutable after upload; caller destroys */
+
+/*
+ * Generate the static dictionary: the n_entries most probable sequences of
+ * 1..max_pairs pairs of ternary symbols under P(0)=p0, P(1)=P(2)=(1-p0)/2
+ * (Eq. 2), in order of decreasing probability; equally probable sequences in
+ * ascending order of the symbol string read as a base-3 number.  The paper's
+ * table is p0 = 0.885, max_pairs = 14, n_entries = 65536.
+ * Errors: INVALID_ARG unless 0<p0<1, 1<=max_pairs<=14, 1<=n_entries<=65536.
+ * Fewer than n_entries are produced when fewer sequences exist.
+ */
+qmoe_status qmoe_dict_create(double p0, int max_pairs, int n_entries, qmoe_dict **out);
+
+/*
+ * Adopt a table in the interchange layout (host, copied): words[2k], words[2k+1]
+ * describe entry k; in each 32-bit word bits 0..3 hold the entry's pair count
+ * (the same in both words) and bits 4+2j..5+2j the j-th symbol of that half
+ * (7 pairs = 14 symbols per word, first half in word 0), unused slots 0
+ * (Section 4.3.2; bit positions as the paper's kernel listing reads them).
+ * Errors: INVALID_ARG, BAD_SYMBOL (a symbol value 3, a non-zero unused slot,
+ * count nibbles that differ or are 0 or > 14).
+ */
+qmoe_status qmoe_dict_from_words(const uint32_t *words /*host [n_entries][2]*/, int n_entries,
+                                 qmoe_dict **out);
+
+/* Borrow the interchange-layout table (valid until qmoe_dict_destroy). */
+qmoe_status qmoe_dict_words(const qmoe_dict *d, const uint32_t **words, int *n_entries);
+
+/* Largest number of non-zero symbols in any entry (3 for the paper's table). */
+int qmoe_dict_max_nonzeros(const qmoe_dict *d);
+
+/* Bytes of device memory qmoe_dict_upload needs (independent of the table's contents). */
+size_t qmoe_dict_device_bytes(void);
+
+/*
+ * Copy the device form of the table into dev_buf (device, >= qmoe_dict_device_bytes(),
+ * 256-byte aligned, owned by the caller, must outlive every device call that uses d)
+ * and bind it to d.  The copy is enqueued on `stream` from memory owned by d.
+ * Errors: INVALID_ARG, BUFFER_TOO_SMALL, HIP.
+ */
+qmoe_status qmoe_dict_upload(qmoe_dict *d, void *dev_buf /*device*/, size_t dev_bytes, void *stream);
+
+void qmoe_dict_destroy(qmoe_dict *d);
+
+/* ------------------------------------------------------------------------- */
+/* Host codec (Section 4.3.3 "Encoding")                                      */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Encode a row-major ternary matrix (host int8 in {-1,0,+1}) by longest-prefix
+ * match against the dictionary, row by row.  row_off (host, [rows+1]) is always
+ * written; codes (host) may be NULL to only size the output.  *n_codes receives
+ * the number of codewords needed.  Rows are encoded on several host threads.
+ * Errors: INVALID_ARG (NULL, rows<1, cols<2 or odd), BAD_SYMBOL,
+ * BUFFER_TOO_SMALL (codes_cap < needed; *n_codes still set), UNENCODABLE,
+ * LIMIT (more than 2^32-1 codewords).
+ */
+qmoe_status qmoe_encode_host(const qmoe_dict *d, const int8_t *tern /*host [rows][cols]*/, int rows,
+                             int cols, uint16_t *codes /*host or NULL*/, size_t codes_cap,
+                             uint32_t *row_off /*host [rows+1]*/, size_t *n_codes);
+
+/*
+ * Check a compressed matrix on the host: offsets start at 0 and never decrease,
+ * every codeword names an entry, every row decodes to exactly cols values.
+ * Errors: INVALID_ARG, CORRUPT_STREAM.
+ */
+qmoe_status qmoe_validate_host(const qmoe_dict *d, const uint16_t *codes /*host*/,
+                               const uint32_t *row_off /*host [rows+1]*/, int rows, int cols);
+
+/* ------------------------------------------------------------------------- */
+/* Device kernels (Section 4.3.3 "GPU Kernel")                                */
+/* ------------------------------------------------------------------------- */
+
+/* One compressed matrix.  All pointers are device memory owned by the caller. */
+typedef struct qmoe_matrix {
+    const uint16_t *codes;     /* [n_codes] codewords, rows back to back               */
+    const uint32_t *row_off;   /* [rows+1] first codeword of each row                   */
+    const uint16_t *scale_f16; /* [rows] IEEE binary16 scale s_r of each output row     */
+    int32_t rows, cols;        /* cols even                                             */
+    uint32_t n_codes;          /* = row_off[rows]; offsets beyond it are clamped        */
+    uint32_t reserved;         /* 0                                                     */
+} qmoe_matrix;
+
+/*
+ * Fused decode + product (the paper's kernel, extended by an inner loop over
+ * tokens as its Section 5.3 suggests):
+ *   y[b][r] = s_r * sum_c T[r][c] * x[b][c],  b < batch
+ * W: host struct holding device pointers.  x: device bf16 [batch][cols].
+ * y: device fp32 [batch][rows], overwritten.  fp32 accumulation.
+ * Errors: INVALID_ARG (NULL, batch<1, odd cols), NO_DEVICE_DICT, LIMIT
+ * (cols > 32768), HIP.
+ */
+qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
+                               const uint16_t *x_bf16 /*device*/, int batch, float *y /*device*/,
+                               void *stream);
+
+/*
+ * Pure decompression (Section 4.3.3 mentions it as a variant): out is device
+ * int8 [rows][cols] in {-1,0,+1} and equals the encoder's input bit for bit.
+ * `path` selects the table the kernel reads: 0 = the one the product kernels
+ * use for this dictionary, 1 = always the interchange layout.
+ * Errors: as qmoe_decode_matvec.
+ */
+qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/, int8_t *out /*device*/,
+                              int path, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* One MoE feed-forward layer (Section 2.1; Section 5.1 on skipping experts)  */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Where things live inside the layer workspace (byte offsets), for callers and
+ * tests that want to look at the dispatch result:
+ *   tok_off  int32 [n_experts+1]  expert e owns slots tok_off[e]..tok_off[e+1]
+ *   perm     int32 [n_tokens]     slot -> token index, ascending inside an expert
+ *   counters int32 [8]            [0] tokens kept, [1] tokens dropped (expert index
+ *                                 outside [0,n_experts)), [2] experts with tokens,
+ *                                 [3] work items of the first product, [4] of the second
+ *   hidden   bf16  [n_tokens][d_ff]  by slot
+ */
+typedef struct qmoe_ws_layout {
+    size_t tok_off, perm, counters, items_wi, items_wo, hidden, total;
+} qmoe_ws_layout;
+
+qmoe_status qmoe_moe_layer_ws_layout(int n_experts, int d_model, int d_ff, int n_tokens,
+                                     qmoe_ws_layout *out);
+/* = layout.total; 0 on bad arguments */
+size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_tokens);
+
+/*
+ * y[t] = gate[t] * Wo[e] . bf16( relu( Wi[e] . x[t] ) ),  e = expert_idx[t]
+ *
+ * wi, wo: device arrays [n_experts] of qmoe_matrix (wi[e]: d_ff x d_model,
+ * wo[e]: d_model x d_ff).  x: device bf16 [n_tokens][d_model].  expert_idx:
+ * device int32 [n_tokens].  gate: device fp32 [n_tokens] or NULL (= 1).
+ * y: device fp32 [n_tokens][d_model], overwritten; a token whose expert index
+ * is outside [0, n_experts) gets a zero row.  workspace: device, 256-byte
+ * aligned, >= qmoe_moe_layer_workspace(...) bytes, contents need not be
+ * initialised.  Experts without tokens are never touched (their qmoe_matrix
+ * may hold anything).  Enqueues a dispatch kernel and the two product kernels.
+ * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
+ * n_tokens > 2^20, d_model or d_ff > 32768), HIP.
+ */
+qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*device*/,
+                                   const qmoe_matrix *wo /*device*/, int n_experts, int d_model,
+                                   int d_ff, const uint16_t *x_bf16 /*device*/,
+                                   const int32_t *expert_idx /*device*/, const float *gate /*device*/,
+                                   int n_tokens, float *y /*device*/, void *workspace /*device*/,
+                                   size_t workspace_bytes, void *stream);
+
+/* Only the dispatch step of the layer (fills tok_off, perm, counters, work items). */
+qmoe_status qmoe_moe_dispatch(const int32_t *expert_idx /*device*/, int n_tokens, int n_experts,
+                              int d_model, int d_ff, void *workspace /*device*/,
+                              size_t workspace_bytes, void *stream);
+
+/*
+ * The same layer on uncompressed weights, for the "uncompressed bf16
+ * execution" the paper compares against (Section 5.3): wi_dense[e] / wo_dense[e]
+ * are device pointers to row-major bf16 matrices that already include the row
+ * scales (NULL allowed for experts without tokens).  Same dispatch, same
+ * workspace, same outputs.
+ */
+qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_experts]*/,
+                                    const uint16_t *const *wo_dense /*device [n_experts]*/,
+                                    int n_experts, int d_model, int d_ff,
+                                    const uint16_t *x_bf16 /*device*/,
+                                    const int32_t *expert_idx /*device*/, const float *gate /*device*/,
+                                    int n_tokens, float *y /*device*/, void *workspace /*device*/,
+                                    size_t workspace_bytes, void *stream);
+
+/*
+ * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
+ * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
+ * "grid_per_cu", "host_threads" (encoder threads).  value 0 restores the built-in
+ * heuristic; lds_dict_entries = -1 keeps the whole table in L2.  Unknown key: INVALID_ARG.
+ */
+qmoe_status qmoe_set_tuning(const char *key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QMOE_H */

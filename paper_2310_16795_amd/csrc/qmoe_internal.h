@@ -1,0 +1,54 @@
+// Internal declarations shared by the host codec and the HIP launch code.
+// Not part of the C ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "qmoe.h"
+
+namespace qmoe {
+
+constexpr int kMaxSyms = 28;          // 14 pairs, two ternary symbols each
+constexpr int kTableEntries = 65536;  // device tables always span every uint16 codeword
+
+// Compact device entry ("run entry") for tables whose entries hold at most three
+// non-zero symbols, which is the case for the paper's table: a codeword is then
+// a run length plus at most three signed positions.
+//   bits 0..4          number of ternary values the entry decodes to (2..28; 0 = no entry)
+//   bits 5+7j..9+7j    position of the j-th non-zero inside the run (j = 0,1,2)
+//   bits 10+7j..11+7j  its weight as a 2-bit signed integer: +1, -1, or 0 = slot unused
+constexpr int kRunLenBits = 5;
+constexpr int kRunFieldBits = 7;
+constexpr int kRunMaxNonzeros = 3;
+
+// Device blob written by qmoe_dict_upload: run entries first, then the
+// interchange-layout words, both for all 65536 codewords (absent entries are 0).
+constexpr size_t kDevRunOffset = 0;
+constexpr size_t kDevWordsOffset = sizeof(uint32_t) * kTableEntries;
+constexpr size_t kDevDictBytes = kDevWordsOffset + 2 * sizeof(uint32_t) * kTableEntries;
+
+struct Tuning {
+    int threads = 0;
+    int rows_per_item = 0;
+    int token_tile = 0;
+    int lds_dict_entries = 0;  // 0 = heuristic, -1 = keep the table in L2 only
+    int grid_per_cu = 0;
+    int host_threads = 0;
+};
+Tuning &tuning();
+
+}  // namespace qmoe
+
+struct qmoe_dict {
+    int n_entries = 0;
+    int max_pairs = 0;
+    int max_nonzeros = 0;
+    std::vector<uint32_t> words;  // [kTableEntries][2], interchange layout, zero beyond n_entries
+    std::vector<uint32_t> run;    // [kTableEntries], valid when max_nonzeros <= kRunMaxNonzeros
+    // trie over the entries: child[node * 9 + pair] (-1 = none), code[node] (-1 = no entry ends here)
+    std::vector<int32_t> child;
+    std::vector<int32_t> code;
+    const void *dev = nullptr;  // bound by qmoe_dict_upload
+};

@@ -1,0 +1,122 @@
+"""Plumbing between host arrays and device memory (torch tensors).  No arithmetic."""
+from __future__ import annotations
+
+import ctypes
+
+import numpy as np
+import torch
+
+from . import _binding as B
+
+
+class DeviceDict:
+    """A dictionary handle together with the device buffer it is bound to."""
+
+    def __init__(self, handle: int | None = None, device="cuda:0"):
+        self.handle = B.qmoe_dict_create() if handle is None else handle
+        self.buf = torch.empty(B.qmoe_dict_device_bytes(), dtype=torch.uint8, device=device)
+        B.qmoe_dict_upload(self.handle, self.buf)
+        torch.cuda.current_stream().synchronize()
+
+    def close(self):
+        if self.handle:
+            B.qmoe_dict_destroy(self.handle)
+            self.handle = 0
+
+
+def _pad_to(a: np.ndarray, multiple: int) -> np.ndarray:
+    extra = (-a.size) % multiple
+    return a if extra == 0 else np.concatenate([a, np.zeros(extra, dtype=a.dtype)])
+
+
+class DeviceMatrix:
+    """One compressed matrix in device memory and its qmoe_matrix descriptor."""
+
+    def __init__(self, codes: np.ndarray, row_off: np.ndarray, scale_f16: np.ndarray, rows: int, cols: int,
+                 device="cuda:0"):
+        assert row_off.shape == (rows + 1,) and scale_f16.shape == (rows,)
+        self.codes = torch.from_numpy(_pad_to(codes.view(np.int16), 8).copy()).to(device)
+        self.row_off = torch.from_numpy(row_off.astype(np.uint32).view(np.int32).copy()).to(device)
+        self.scale = torch.from_numpy(scale_f16.view(np.int16).copy()).to(device)
+        self.desc = B.qmoe_matrix(self.codes.data_ptr(), self.row_off.data_ptr(), self.scale.data_ptr(), rows,
+                                  cols, int(codes.size), 0)
+
+
+class DeviceLayer:
+    """All experts of one MoE layer: three big device buffers per projection and
+    a device array of qmoe_matrix descriptors pointing into them."""
+
+    def __init__(self, n_experts: int, d_model: int, d_ff: int, device="cuda:0"):
+        self.n_experts, self.d_model, self.d_ff, self.device = n_experts, d_model, d_ff, device
+        self._host = {"wi": [None] * n_experts, "wo": [None] * n_experts}
+        self.compressed_bytes = 0
+        self.n_codes = {"wi": np.zeros(n_experts, dtype=np.int64), "wo": np.zeros(n_experts, dtype=np.int64)}
+
+    def set_expert(self, e: int, which: str, codes: np.ndarray, row_off: np.ndarray, scale_f16: np.ndarray):
+        rows = self.d_ff if which == "wi" else self.d_model
+        assert row_off.shape == (rows + 1,) and scale_f16.shape == (rows,) and row_off[-1] == codes.size
+        self._host[which][e] = (codes, row_off.astype(np.uint32), scale_f16)
+        self.n_codes[which][e] = codes.size
+
+    def finalize(self):
+        self.bufs, self.desc_dev, self.desc_host = {}, {}, {}
+        for which in ("wi", "wo"):
+            rows = self.d_ff if which == "wi" else self.d_model
+            cols = self.d_model if which == "wi" else self.d_ff
+            parts = self._host[which]
+            code_off, total = [], 0
+            for p in parts:
+                code_off.append(total)
+                if p is not None:
+                    total += (p[0].size + 7) // 8 * 8  # 16-byte aligned start for every matrix
+            codes = np.zeros(max(total, 8), dtype=np.uint16)
+            row_off = np.zeros((self.n_experts, rows + 1), dtype=np.uint32)
+            scale = np.zeros((self.n_experts, rows), dtype=np.uint16)
+            for e, p in enumerate(parts):
+                if p is None:
+                    continue
+                codes[code_off[e]: code_off[e] + p[0].size] = p[0]
+                row_off[e] = p[1]
+                scale[e] = p[2]
+            d_codes = torch.from_numpy(codes.view(np.int16)).to(self.device)
+            d_row = torch.from_numpy(row_off.view(np.int32)).to(self.device)
+            d_scale = torch.from_numpy(scale.view(np.int16)).to(self.device)
+            descs = (B.qmoe_matrix * self.n_experts)()
+            for e, p in enumerate(parts):
+                if p is None:
+                    continue  # stays all-zero: never touched unless a token is routed there
+                descs[e] = B.qmoe_matrix(d_codes.data_ptr() + 2 * code_off[e],
+                                         d_row.data_ptr() + 4 * e * (rows + 1),
+                                         d_scale.data_ptr() + 2 * e * rows, rows, cols, int(p[0].size), 0)
+            raw = np.frombuffer(bytes(descs), dtype=np.uint8).copy()
+            self.bufs[which] = (d_codes, d_row, d_scale)
+            self.desc_host[which] = descs
+            self.desc_dev[which] = torch.from_numpy(raw).to(self.device)
+            self.compressed_bytes += sum(2 * p[0].size + 6 * rows for p in parts if p is not None)
+        self._host = None
+        return self
+
+    def workspace(self, n_tokens: int) -> torch.Tensor:
+        n = B.qmoe_moe_layer_workspace(self.n_experts, self.d_model, self.d_ff, n_tokens)
+        return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+    def forward(self, dd: DeviceDict, x_bf16: torch.Tensor, expert_idx: torch.Tensor, y: torch.Tensor,
+                workspace: torch.Tensor, gate: torch.Tensor | None = None, stream=None):
+        B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.n_experts,
+                                 self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, workspace, stream)
+
+
+def read_workspace(workspace: torch.Tensor, n_experts: int, d_model: int, d_ff: int, n_tokens: int):
+    """Copy the dispatch results out of a layer workspace (synchronises)."""
+    l = B.qmoe_moe_layer_ws_layout(n_experts, d_model, d_ff, n_tokens)
+    host = workspace.cpu().numpy()
+    def view(off, n, dt):
+        return host[off: off + n * np.dtype(dt).itemsize].view(dt).copy()
+    return {
+        "tok_off": view(l.tok_off, n_experts + 1, np.int32),
+        "perm": view(l.perm, n_tokens, np.int32),
+        "counters": view(l.counters, 8, np.int32),
+        "items_wi": view(l.items_wi, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
+        "items_wo": view(l.items_wo, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
+        "hidden": view(l.hidden, n_tokens * d_ff, np.uint16).reshape(n_tokens, d_ff),
+    }
