@@ -44,6 +44,7 @@ constexpr int kMaxTokenTile = 8;
 constexpr int kMaxCols = 32768;
 constexpr int kMaxExperts = 16384;
 constexpr int kMaxTokens = 1 << 20;
+constexpr uint32_t kMaxCodes = 0xFFFFFF00u;  // keeps `kb += 16` from wrapping
 
 struct Item {  // one (expert, token tile) unit of work; row blocks are enumerated on the fly
     int expert, slot0, ntok, pad;
@@ -166,7 +167,7 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     // previous step's total sits in lane 15 of the row; lane 0 takes it in
     const int carry = __builtin_amdgcn_update_dpp(0, incl, kRowRor1, 0xf, 0xf, false);
     incl = row_scan16(s.len + (l16 == 0 ? carry : 0));
-    s.start = min(incl - s.len, a.cols);
+    s.start = (int)min((uint32_t)(incl - s.len), (uint32_t)a.cols);  // also catches a wrapped index
     return s;
 }
 
@@ -211,7 +212,7 @@ __device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_ma
 {
     const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
     for (int r = r0 + grp; r < r1; r += ngrp) {
-        const uint32_t kend = min(M.row_off[r + 1], M.n_codes);
+        const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
         const uint32_t kbeg = min(M.row_off[r], kend);
         float acc[TBI];
 #pragma unroll
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(256) void k_decode_dense(const ProductArgs a, int8_
     const qmoe_matrix M = a.single;
     const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
     for (int r = blockIdx.x * ngrp + grp; r < a.rows; r += gridDim.x * ngrp) {
-        const uint32_t kend = min(M.row_off[r + 1], M.n_codes);
+        const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
         const uint32_t kbeg = min(M.row_off[r], kend);
         int8_t *orow = out + (size_t)r * a.cols;
         int incl = 0;
