@@ -230,10 +230,21 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
 /*
  * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
  * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
- * "grid_per_cu", "host_threads" (encoder threads).  value 0 restores the built-in
- * heuristic; lds_dict_entries = -1 keeps the whole table in L2.  Unknown key: INVALID_ARG.
+ * "grid_per_cu", "host_threads" (encoder threads), "phases" (bit mask of the layer's
+ * kernels to enqueue: 1 dispatch, 2 first product, 4 second product -- lets a
+ * benchmark time one kernel on a workspace a full call has filled).  value 0 restores
+ * the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2.
+ * Unknown key: INVALID_ARG.
  */
 qmoe_status qmoe_set_tuning(const char *key, int value);
+
+/*
+ * Plain device-to-device copy kernel (16 bytes per lane, grid-stride): the
+ * yardstick for what a pure streaming kernel reaches on this GPU and the
+ * calibration of the profiler's HBM byte counters.  dst, src: device, 16-byte
+ * aligned, bytes a multiple of 16.  Errors: INVALID_ARG, HIP.
+ */
+qmoe_status qmoe_stream_copy(void *dst /*device*/, const void *src /*device*/, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -41,7 +41,7 @@ EXPORTS = [
     "qmoe_dict_max_nonzeros", "qmoe_dict_device_bytes", "qmoe_dict_upload", "qmoe_dict_destroy",
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
-    "qmoe_bf16_layer_forward", "qmoe_set_tuning",
+    "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy",
 ]
 
 
@@ -72,6 +72,7 @@ def lib():
         L.qmoe_moe_dispatch.argtypes = [vp, i, i, i, i, vp, sz, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
+        L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -233,3 +234,10 @@ def qmoe_bf16_layer_forward(wi_ptrs, wo_ptrs, n_experts: int, d_model: int, d_ff
 
 def qmoe_set_tuning(key: str, value: int) -> None:
     _check(lib().qmoe_set_tuning(key.encode(), int(value)), "qmoe_set_tuning")
+
+
+def qmoe_stream_copy(dst, src, stream=None) -> None:
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < n:
+        raise ValueError("destination too small")
+    _check(lib().qmoe_stream_copy(_dev_ptr(dst), _dev_ptr(src), n, _stream_ptr(stream)), "qmoe_stream_copy")

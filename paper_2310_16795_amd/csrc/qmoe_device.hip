@@ -205,7 +205,7 @@ __device__ __forceinline__ void accumulate_step(const Step &s, const float *xs, 
     }
 }
 
-template <int TBI, bool RUN>
+template <int TBI, bool RUN, int EPI>
 __device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_matrix &M, int ntok,
                                              int slot0, int r0, int r1, const float *xs,
                                              const int *tok_ids, const uint32_t *lds_run)
@@ -230,7 +230,7 @@ __device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_ma
             for (int t = 0; t < TBI; t++) {
                 if (t < ntok) {
                     const float v = acc[t] * scale;
-                    if (a.epilogue == 0) {
+                    if constexpr (EPI == 0) {
                         const int tok = tok_ids[t];
                         const float g = a.gate ? a.gate[tok] : 1.0f;
                         reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + r] = g * v;
@@ -247,7 +247,9 @@ __device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_ma
 
 // ---------------------------------------------------------------- fused decode + product
 
-template <bool RUN>
+// EPI 0: fp32 out[token][r] = gate * s_r * acc      (second product, and the plain matvec)
+// EPI 1: bf16 out[slot][r]  = relu(s_r * acc)        (first product, writes the hidden vector)
+template <bool RUN, int EPI>
 __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -314,10 +316,10 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         const int r0 = blk * a.rows_per_item;
         const int r1 = min(a.rows, r0 + a.rows_per_item);
         switch (tbi) {
-        case 1: product_rows<1, RUN>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        case 2: product_rows<2, RUN>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        case 4: product_rows<4, RUN>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        default: product_rows<8, RUN>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
+        case 1: product_rows<1, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
+        case 2: product_rows<2, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
+        case 4: product_rows<4, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
+        default: product_rows<8, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
         }
     }
 }
@@ -615,6 +617,16 @@ __global__ __launch_bounds__(1024) void k_dense_bf16(const DenseArgs a)
     }
 }
 
+// ---------------------------------------------------------------- plain streaming copy
+
+// 16 bytes per lane per iteration, grid-stride; the yardstick for what a kernel
+// that only moves bytes reaches on this GPU, and the calibration of the HBM counters.
+__global__ __launch_bounds__(256) void k_stream_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------- launch helpers
 
 struct DeviceInfo {
@@ -700,18 +712,20 @@ qmoe_status allow_lds(K kernel, size_t smem)
     return QMOE_OK;
 }
 
-qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
+template <bool RUN, int EPI>
+qmoe_status launch_product_as(const ProductArgs &a, const ProductPlan &p, hipStream_t s)
 {
-    qmoe_status st;
-    if (run) {
-        if ((st = allow_lds(k_product<true>, p.smem)) != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_product<true>, dim3(p.grid), dim3(p.threads), p.smem, s, a);
-    } else {
-        if ((st = allow_lds(k_product<false>, p.smem)) != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_product<false>, dim3(p.grid), dim3(p.threads), p.smem, s, a);
-    }
+    const qmoe_status st = allow_lds(k_product<RUN, EPI>, p.smem);
+    if (st != QMOE_OK) return st;
+    hipLaunchKernelGGL((k_product<RUN, EPI>), dim3(p.grid), dim3(p.threads), p.smem, s, a);
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
+}
+
+qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
+{
+    if (run) return a.epilogue ? launch_product_as<true, 1>(a, p, s) : launch_product_as<true, 0>(a, p, s);
+    return a.epilogue ? launch_product_as<false, 1>(a, p, s) : launch_product_as<false, 0>(a, p, s);
 }
 
 qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
@@ -923,9 +937,11 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo)) != QMOE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
-    if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
-        QMOE_OK)
-        return st;
+    const int phases = tuning().phases > 0 ? tuning().phases : 7;
+    if (phases & 1)
+        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
+            QMOE_OK)
+            return st;
 
     ProductArgs a{};
     fill_tables(d, &a);
@@ -949,7 +965,8 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwi.blocks_per_pass;
     a.tb_max = pwi.tb_max;
     a.lds_dict_entries = pwi.lds_dict_entries;
-    if ((st = launch_product(a, pwi, run, s)) != QMOE_OK) return st;
+    if (phases & 2)
+        if ((st = launch_product(a, pwi, run, s)) != QMOE_OK) return st;
     // second product: y[token] = gate * Wo hidden[slot]
     a.mats = wo;
     a.items = lp.items_wo;
@@ -967,7 +984,8 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwo.blocks_per_pass;
     a.tb_max = pwo.tb_max;
     a.lds_dict_entries = pwo.lds_dict_entries;
-    return launch_product(a, pwo, run, s);
+    if (phases & 4) return launch_product(a, pwo, run, s);
+    return QMOE_OK;
 }
 
 qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint16_t *const *wo_dense,
@@ -987,9 +1005,11 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     if ((st = plan_product(d_model, d_ff, false, n_tokens, &pwo)) != QMOE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
-    if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
-        QMOE_OK)
-        return st;
+    const int phases = tuning().phases > 0 ? tuning().phases : 7;
+    if (phases & 1)
+        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
+            QMOE_OK)
+            return st;
     DenseArgs a{};
     a.n_experts = n_experts;
     a.max_items = n_tokens;
@@ -1009,9 +1029,11 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     a.rows_per_item = pwi.rows_per_item;
     a.blocks_per_pass = pwi.blocks_per_pass;
     a.tb_max = pwi.tb_max;
-    if ((st = allow_lds(k_dense_bf16, pwi.smem)) != QMOE_OK) return st;
-    hipLaunchKernelGGL(k_dense_bf16, dim3(pwi.grid), dim3(pwi.threads), pwi.smem, s, a);
-    QMOE_HIP_TRY(hipGetLastError());
+    if (phases & 2) {
+        if ((st = allow_lds(k_dense_bf16, pwi.smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_dense_bf16, dim3(pwi.grid), dim3(pwi.threads), pwi.smem, s, a);
+        QMOE_HIP_TRY(hipGetLastError());
+    }
     a.mats = wo_dense;
     a.items = lp.items_wo;
     a.n_items_dev = lp.counters + 4;
@@ -1027,8 +1049,26 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     a.rows_per_item = pwo.rows_per_item;
     a.blocks_per_pass = pwo.blocks_per_pass;
     a.tb_max = pwo.tb_max;
-    if ((st = allow_lds(k_dense_bf16, pwo.smem)) != QMOE_OK) return st;
-    hipLaunchKernelGGL(k_dense_bf16, dim3(pwo.grid), dim3(pwo.threads), pwo.smem, s, a);
+    if (phases & 4) {
+        if ((st = allow_lds(k_dense_bf16, pwo.smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_dense_bf16, dim3(pwo.grid), dim3(pwo.threads), pwo.smem, s, a);
+        QMOE_HIP_TRY(hipGetLastError());
+    }
+    return QMOE_OK;
+}
+
+qmoe_status qmoe_stream_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || bytes == 0 || (bytes % 16) || reinterpret_cast<uintptr_t>(dst) % 16 ||
+        reinterpret_cast<uintptr_t>(src) % 16)
+        return QMOE_E_INVALID_ARG;
+    DeviceInfo di;
+    const qmoe_status st = device_info(&di);
+    if (st != QMOE_OK) return st;
+    const size_t n16 = bytes / 16;
+    const int grid = (int)std::min<size_t>((n16 + 255) / 256, (size_t)di.cus * 32);
+    hipLaunchKernelGGL(k_stream_copy, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }

@@ -340,6 +340,7 @@ qmoe_status qmoe_set_tuning(const char *key, int value)
     else if (!std::strcmp(key, "lds_dict_entries")) t.lds_dict_entries = value;
     else if (!std::strcmp(key, "grid_per_cu")) t.grid_per_cu = value;
     else if (!std::strcmp(key, "host_threads")) t.host_threads = value;
+    else if (!std::strcmp(key, "phases")) t.phases = value;
     else return QMOE_E_INVALID_ARG;
     return QMOE_OK;
 }

@@ -36,6 +36,7 @@ struct Tuning {
     int lds_dict_entries = 0;  // 0 = heuristic, -1 = keep the table in L2 only
     int grid_per_cu = 0;
     int host_threads = 0;
+    int phases = 0;  // bit 0 dispatch, bit 1 first product, bit 2 second product; 0 = all
 };
 Tuning &tuning();
 
