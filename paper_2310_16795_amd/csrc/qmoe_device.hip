@@ -2,17 +2,19 @@
 //
 // Work decomposition of the fused decode + product kernel (Section 4.3.3 of the
 // paper defines what is computed; the mapping below is this library's own):
-//  - a 16-lane DPP row ("group") owns one matrix row at a time; each lane takes
-//    one codeword per step, so a step covers 16 consecutive codewords = 32
-//    contiguous bytes of the stream, four rows per wavefront;
+//  - a 16-lane DPP row ("group") owns a contiguous range of matrix rows and with
+//    it one contiguous piece of the codeword stream; each lane takes one codeword
+//    per step, so a step covers 16 consecutive codewords = 32 contiguous bytes,
+//    four groups per wavefront, codewords fetched two steps ahead of their use;
 //  - the running column index of the paper's sequential decoder becomes an
 //    inclusive prefix sum of the run lengths inside the group (four DPP row
-//    shifts), with the previous step's total carried in through lane 0;
+//    shifts), with the previous step's total carried in through lane 0; a row is
+//    complete when the sum reaches `cols`, and the group then reduces and writes it;
 //  - a codeword is looked up in a compact "run entry" table (length plus up to
 //    three signed non-zero positions), so the arithmetic per codeword is three
 //    gathers from the activations in LDS, not 28 multiply-adds;
-//  - the activations of up to eight tokens sit interleaved in LDS as fp32, so
-//    one decoded weight is applied to all tokens of the tile with one LDS read;
+//  - the activations of up to eight tokens sit interleaved in LDS as bf16, so one
+//    decoded weight is applied to all tokens of the tile with one LDS read;
 //  - workgroups are persistent and walk a list of (expert, token tile, row
 //    block) items that the dispatch kernel wrote; experts without tokens never
 //    appear in it.
@@ -44,6 +46,7 @@ constexpr int kMaxTokenTile = 8;
 constexpr int kMaxCols = 32768;
 constexpr int kMaxExperts = 16384;
 constexpr int kMaxTokens = 1 << 20;
+constexpr int kMaxRowsPerItem = 1024;
 constexpr uint32_t kMaxCodes = 0xFFFFFF00u;  // keeps `kb += 16` from wrapping
 
 struct Item {  // one (expert, token tile) unit of work; row blocks are enumerated on the fly
@@ -72,6 +75,7 @@ struct ProductArgs {
     int rows_per_item, blocks_per_pass;
     int tb_max;
     int lds_dict_entries;     // leading run entries copied to LDS (0 = none)
+    int *work_counter;        // device counter (zeroed by the dispatch kernel) for handing out items, or nullptr
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -147,17 +151,14 @@ struct Step {
 
 template <bool RUN>
 __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t *codes, uint32_t k,
-                                            uint32_t kend, int l16, int &incl, const uint32_t *lds_run)
+                                            uint32_t kend, int l16, int &incl)
 {
     Step s;
     s.e0 = 0; s.e1 = 0;
     if (k < kend) {
         const uint32_t code = codes[k];
         if constexpr (RUN) {
-            if (lds_run != nullptr && (int)code < a.lds_dict_entries)
-                s.e0 = lds_run[code];
-            else
-                s.e0 = a.run[code];
+            s.e0 = a.run[code];
         } else {
             const uint2 w = reinterpret_cast<const uint2 *>(a.words)[code];
             s.e0 = w.x; s.e1 = w.y;
@@ -171,25 +172,113 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     return s;
 }
 
-template <int TBI, bool RUN>
-__device__ __forceinline__ void accumulate_step(const Step &s, const float *xs, float (&acc)[TBI])
+// Global-memory pointers with their address space spelled out: pointers that reach
+// a kernel through memory would otherwise be generic and cost flat loads.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using gp_u16 = const __attribute__((address_space(1))) uint16_t *;
+using gp_u32 = const __attribute__((address_space(1))) uint32_t *;
+using gp_u64 = const __attribute__((address_space(1))) unsigned long long *;
+using gp_u32x4 = const __attribute__((address_space(1))) u32x4 *;
+using lp_u32 = const __attribute__((address_space(3))) uint32_t *;
+using lp_u16 = const __attribute__((address_space(3))) uint16_t *;
+
+enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2 };
+
+struct Entry {
+    uint32_t e0, e1;  // run entry (e0), or the two interchange words (e0, e1)
+};
+
+template <int DICT>
+__device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t code, lp_u32 lds_run)
 {
-    if constexpr (RUN) {
+    Entry e{0u, 0u};
+    if constexpr (DICT == kDictRun) {
+        e.e0 = ((gp_u32)a.run)[code];
+    } else if constexpr (DICT == kDictRunLds) {
+        if ((int)code < a.lds_dict_entries)
+            e.e0 = lds_run[code];
+        else
+            e.e0 = ((gp_u32)a.run)[code];
+    } else {
+        const unsigned long long w = ((gp_u64)a.words)[code];
+        e.e0 = (uint32_t)w; e.e1 = (uint32_t)(w >> 32);
+    }
+    return e;
+}
+
+template <int DICT>
+__device__ __forceinline__ int entry_len(const Entry &e)
+{
+    return DICT == kDictWords ? 2 * (int)(e.e0 & 15u) : (int)(e.e0 & 31u);
+}
+
+// activations of one column for the TBI (>= 2) tokens of the tile: packed bf16 in LDS -> fp32
+template <int TBI>
+__device__ __forceinline__ void lds_load_x(lp_u16 xs, int col, float (&v)[TBI])
+{
+    typedef const __attribute__((address_space(3))) uint32_t *p32;
+    if constexpr (TBI == 1) {
+        v[0] = __uint_as_float((uint32_t)xs[4 * col + 1] << 16);  // the +x slot of the record
+    } else if constexpr (TBI == 2) {
+        const uint32_t u = ((p32)xs)[col];
+        v[0] = __uint_as_float(u << 16); v[1] = __uint_as_float(u & 0xFFFF0000u);
+    } else if constexpr (TBI == 4) {
+        const uint32_t u0 = ((p32)xs)[2 * col], u1 = ((p32)xs)[2 * col + 1];
+        v[0] = __uint_as_float(u0 << 16); v[1] = __uint_as_float(u0 & 0xFFFF0000u);
+        v[2] = __uint_as_float(u1 << 16); v[3] = __uint_as_float(u1 & 0xFFFF0000u);
+    } else {
+        const uint32_t u0 = ((p32)xs)[4 * col], u1 = ((p32)xs)[4 * col + 1];
+        const uint32_t u2 = ((p32)xs)[4 * col + 2], u3 = ((p32)xs)[4 * col + 3];
+        v[0] = __uint_as_float(u0 << 16); v[1] = __uint_as_float(u0 & 0xFFFF0000u);
+        v[2] = __uint_as_float(u1 << 16); v[3] = __uint_as_float(u1 & 0xFFFF0000u);
+        v[4] = __uint_as_float(u2 << 16); v[5] = __uint_as_float(u2 & 0xFFFF0000u);
+        v[6] = __uint_as_float(u3 << 16); v[7] = __uint_as_float(u3 & 0xFFFF0000u);
+    }
+}
+
+// acc[t] += sum over the entry's non-zeros of weight * x[t][col + position]
+//
+// One token (TBI == 1) with a run table: the activations sit in LDS as one 8-byte
+// record {0, +x, 0, -x} (bf16) per column, and a run-entry field is the byte offset
+// of the wanted slot inside the record at `col + position` -- unused fields hit a
+// zero slot.  The 16-bit value is loaded straight into the upper half of a register
+// whose lower half stays zero, which makes it the fp32 value: three adds per
+// codeword, no unpacking, no sign handling.
+template <int TBI, int DICT>
+__device__ __forceinline__ void accumulate(const Entry &e, lp_u16 xs, uint32_t xs_addr, int col,
+                                           float (&acc)[TBI], float (&xr)[3])
+{
+    if constexpr (DICT != kDictWords && TBI == 1) {
+        const uint32_t rec = xs_addr + ((uint32_t)col << 3);
+        const uint32_t a0 = rec + ((e.e0 >> kRunLenBits) & 0xFFu);
+        const uint32_t a1 = rec + ((e.e0 >> (kRunLenBits + 8)) & 0xFFu);
+        const uint32_t a2 = rec + ((e.e0 >> (kRunLenBits + 16)) & 0xFFu);
+        asm volatile("ds_read_u16_d16_hi %0, %3\n\t"
+                     "ds_read_u16_d16_hi %1, %4\n\t"
+                     "ds_read_u16_d16_hi %2, %5\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "+v"(xr[0]), "+v"(xr[1]), "+v"(xr[2])
+                     : "v"(a0), "v"(a1), "v"(a2)
+                     : "memory");
+        acc[0] += xr[0];
+        acc[0] += xr[1];
+        acc[0] += xr[2];
+    } else if constexpr (DICT != kDictWords) {
 #pragma unroll
         for (int j = 0; j < kRunMaxNonzeros; j++) {
             const int sh = kRunLenBits + kRunFieldBits * j;
-            const int pos = (int)((s.e0 >> sh) & 31u);
-            const int wi = ((int)(s.e0 << (32 - (sh + 7)))) >> 30;  // signed 2-bit weight
+            const int pos = (int)((e.e0 >> (sh + 3)) & 31u);
+            const int wi = ((int)(e.e0 << (32 - (sh + 3)))) >> 30;  // signed 2-bit weight
             const float w = (float)wi;
             float xv[TBI];
-            lds_load_tile<TBI>(xs, s.start + pos, xv);
+            lds_load_x<TBI>(xs, col + pos, xv);
 #pragma unroll
             for (int t = 0; t < TBI; t++) acc[t] = fmaf(w, xv[t], acc[t]);
         }
     } else {
 #pragma unroll
         for (int h = 0; h < 2; h++) {
-            const uint32_t w = h ? s.e1 : s.e0;
+            const uint32_t w = h ? e.e1 : e.e0;
             uint32_t m = ((w >> 4) | (w >> 5)) & 0x05555555u;  // bit 2j set <=> symbol j non-zero
             while (m) {
                 const int b = __ffs((int)m) - 1;
@@ -197,7 +286,7 @@ __device__ __forceinline__ void accumulate_step(const Step &s, const float *xs, 
                 const int sym = (int)((w >> (4 + b)) & 3u);
                 const float wt = sym == 2 ? 1.0f : (sym == 1 ? -1.0f : 0.0f);
                 float xv[TBI];
-                lds_load_tile<TBI>(xs, s.start + 14 * h + (b >> 1), xv);
+                lds_load_x<TBI>(xs, col + 14 * h + (b >> 1), xv);
 #pragma unroll
                 for (int t = 0; t < TBI; t++) acc[t] = fmaf(wt, xv[t], acc[t]);
             }
@@ -205,43 +294,151 @@ __device__ __forceinline__ void accumulate_step(const Step &s, const float *xs, 
     }
 }
 
-template <int TBI, bool RUN, int EPI>
-__device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_matrix &M, int ntok,
-                                             int slot0, int r0, int r1, const float *xs,
-                                             const int *tok_ids, const uint32_t *lds_run)
+// Per-lane decoder state for one item.
+template <int TBI>
+struct LaneState {
+    float acc[TBI];
+    float xr[3];       // upper halves receive the gathered bf16 values, lower halves stay 0
+    int idx;           // column reached in the current row
+    int row, rb;       // current row, end of this lane's rows
+    float scale, scale_next;
+};
+
+// One decoded entry of one lane: apply its non-zeros, advance, close the row when it is full.
+template <int TBI, int DICT, int EPI>
+__device__ __forceinline__ void consume(const ProductArgs &a, const qmoe_matrix &M, LaneState<TBI> &st,
+                                        const Entry &e, int ntok, int slot0, lp_u16 xs, uint32_t xs_addr,
+                                        const int *tok_ids)
 {
-    const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
-    for (int r = r0 + grp; r < r1; r += ngrp) {
-        const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
-        const uint32_t kbeg = min(M.row_off[r], kend);
-        float acc[TBI];
+    accumulate<TBI, DICT>(e, xs, xs_addr, st.idx, st.acc, st.xr);
+    st.idx += entry_len<DICT>(e);
+    if (__any(st.idx >= a.cols)) {
+        if (st.idx >= a.cols) {
+            if (st.row < st.rb) {
 #pragma unroll
-        for (int t = 0; t < TBI; t++) acc[t] = 0.0f;
-        int incl = 0;
-        for (uint32_t kb = kbeg; kb < kend; kb += 16) {
-            const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl, lds_run);
-            accumulate_step<TBI, RUN>(s, xs, acc);
-        }
-#pragma unroll
-        for (int t = 0; t < TBI; t++) acc[t] = row_sum16_to_last(acc[t]);
-        if (l16 == 15) {
-            const float scale = half_bits_to_float(M.scale_f16[r]);
-#pragma unroll
-            for (int t = 0; t < TBI; t++) {
-                if (t < ntok) {
-                    const float v = acc[t] * scale;
-                    if constexpr (EPI == 0) {
-                        const int tok = tok_ids[t];
-                        const float g = a.gate ? a.gate[tok] : 1.0f;
-                        reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + r] = g * v;
-                    } else {
-                        const float h = v > 0.0f ? v : 0.0f;
-                        reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] =
-                            float_to_bf16_bits(h);
+                for (int t = 0; t < TBI; t++) {
+                    if (t < ntok) {
+                        const float v = st.acc[t] * st.scale;
+                        if constexpr (EPI == 0) {
+                            const int tok = tok_ids[t];
+                            const float g = a.gate ? a.gate[tok] : 1.0f;
+                            reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = g * v;
+                        } else {
+                            const float h = v > 0.0f ? v : 0.0f;
+                            reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + st.row] =
+                                float_to_bf16_bits(h);
+                        }
                     }
                 }
             }
+#pragma unroll
+            for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
+            st.idx -= a.cols;
+            st.row += 1;
+            st.scale = st.scale_next;
+            st.scale_next = st.row + 1 < st.rb ? half_bits_to_float(((gp_u16)M.scale_f16)[st.row + 1]) : 0.0f;
         }
+    }
+}
+
+// table entries of the eight codewords held in one 16-byte piece of the stream
+template <int DICT>
+__device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp_u32 lds_run, Entry (&e)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        e[2 * j] = lookup_entry<DICT>(a, v[j] & 0xFFFFu, lds_run);
+        e[2 * j + 1] = lookup_entry<DICT>(a, v[j] >> 16, lds_run);
+    }
+}
+
+// One block of one (expert, token tile) item: every lane decodes its own rows.
+//
+// The rows of the matrix are dealt out evenly over all lanes of the workgroups that
+// share the item; a lane's rows are consecutive, so its codewords are one contiguous
+// piece of the stream, which it reads in aligned 64-byte chunks (32 codewords, the
+// next chunk in flight while the current one is decoded) and decodes sequentially:
+// no prefix sum across lanes, no reduction -- the running column index is a scalar
+// per lane, exactly the paper's sequential decoder, 64 of them per wavefront.  Table
+// entries are fetched eight codewords ahead of their use.
+template <int TBI, int DICT, int EPI>
+__device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_matrix &M, int ntok,
+                                              int slot0, int blk, lp_u16 xs, uint32_t xs_addr,
+                                              const int *tok_ids, lp_u32 lds_run)
+{
+    const int nlanes = (int)blockDim.x * a.blocks_per_pass;
+    const int gl = blk * (int)blockDim.x + (int)threadIdx.x;
+    const int base_rows = a.rows / nlanes, extra = a.rows - base_rows * nlanes;
+    const int ra = gl * base_rows + min(gl, extra);
+    const int rb = ra + base_rows + (gl < extra ? 1 : 0);
+    gp_u32 row_off = (gp_u32)M.row_off;
+    uint32_t K0 = 0, K1 = 0;
+    if (ra < rb) {
+        const uint32_t cap = min(M.n_codes, kMaxCodes);
+        K1 = min(row_off[rb], cap);
+        K0 = min(row_off[ra], K1);
+    }
+    const uint32_t n = K1 - K0;  // codewords of this lane
+    // 64-byte chunks by address; `rel` is the stream index (relative to K0) of the chunk's first slot
+    const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + 2 * (uintptr_t)K0;
+    const uint32_t lead = (uint32_t)(first_byte & 63u);
+    uintptr_t chunk = first_byte - lead;
+    int rel = -(int)(lead >> 1);
+    const int my_chunks = n ? (int)((lead + 2u * n + 63u) >> 6) : 0;
+    const uintptr_t last_chunk = chunk + 64u * (uintptr_t)max(my_chunks - 1, 0);
+    int nchunks = my_chunks;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) nchunks = max(nchunks, __shfl_xor(nchunks, d, 64));
+
+    LaneState<TBI> st;
+#pragma unroll
+    for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
+    st.xr[0] = st.xr[1] = st.xr[2] = 0.0f;
+    st.idx = 0;
+    st.row = ra;
+    st.rb = rb;
+    st.scale = ra < rb ? half_bits_to_float(((gp_u16)M.scale_f16)[ra]) : 0.0f;
+    st.scale_next = ra + 1 < rb ? half_bits_to_float(((gp_u16)M.scale_f16)[ra + 1]) : 0.0f;
+
+    u32x4 q[4], qn[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) q[i] = ((gp_u32x4)chunk)[i];
+    Entry ecur[8], enxt[8];
+    lookup8<DICT>(a, q[0], lds_run, ecur);
+    for (int c = 0; c < nchunks; c++) {
+        const uintptr_t next = min(chunk + 64u, last_chunk);  // lanes past their end re-read their last chunk
+#pragma unroll
+        for (int i = 0; i < 4; i++) qn[i] = ((gp_u32x4)next)[i];
+        // is every slot of this chunk a codeword of its lane, in every lane of the wavefront?
+        const bool whole = rel >= 0 && (uint32_t)rel + 32u <= n;
+        if (__all(whole)) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                lookup8<DICT>(a, i < 3 ? q[i + 1] : qn[0], lds_run, enxt);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    consume<TBI, DICT, EPI>(a, M, st, ecur[j], ntok, slot0, xs, xs_addr, tok_ids);
+#pragma unroll
+                for (int j = 0; j < 8; j++) ecur[j] = enxt[j];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                lookup8<DICT>(a, i < 3 ? q[i + 1] : qn[0], lds_run, enxt);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    Entry e = ecur[j];
+                    if ((uint32_t)(rel + 8 * i + j) >= n) { e.e0 = 0u; e.e1 = 0u; }  // not this lane's codeword
+                    consume<TBI, DICT, EPI>(a, M, st, e, ntok, slot0, xs, xs_addr, tok_ids);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; j++) ecur[j] = enxt[j];
+            }
+        }
+        chunk = next;
+        rel += 32;
+#pragma unroll
+        for (int i = 0; i < 4; i++) q[i] = qn[i];
     }
 }
 
@@ -249,15 +446,21 @@ __device__ __forceinline__ void product_rows(const ProductArgs &a, const qmoe_ma
 
 // EPI 0: fp32 out[token][r] = gate * s_r * acc      (second product, and the plain matvec)
 // EPI 1: bf16 out[slot][r]  = relu(s_r * acc)        (first product, writes the hidden vector)
-template <bool RUN, int EPI>
+// LDS: activations | token ids | leading run entries.  Activations are bf16, for one
+// token as 8-byte records {0, +x, 0, -x} per column, for 2/4/8 tokens packed per column.
+template <int DICT, int EPI>
 __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    float *xs = reinterpret_cast<float *>(smem);
-    const size_t xs_bytes = (size_t)(a.cols + kPadCols) * a.tb_max * sizeof(float);
+    uint16_t *xs_w = reinterpret_cast<uint16_t *>(smem);
+    const size_t xs_bytes = (size_t)(a.cols + kPadCols) * max(a.tb_max, 4) * sizeof(uint16_t);
     int *tok_ids = reinterpret_cast<int *>(smem + xs_bytes);            // [kMaxTokenTile] output token
     int *x_rows = tok_ids + kMaxTokenTile;                              // [kMaxTokenTile] input row
-    uint32_t *lds_run = a.lds_dict_entries > 0 ? reinterpret_cast<uint32_t *>(smem + xs_bytes + 64) : nullptr;
+    int *next_item = x_rows + kMaxTokenTile;                            // [1]
+    uint32_t *lds_run_w = reinterpret_cast<uint32_t *>(smem + xs_bytes + 128);
+    lp_u16 xs = (lp_u16)xs_w;
+    lp_u32 lds_run = (lp_u32)lds_run_w;
+    const uint32_t xs_addr = (uint32_t)(uintptr_t)xs;  // LDS byte address of the activations
 
     int n_pass;
     if (a.items) {
@@ -265,22 +468,39 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     } else {
         n_pass = (a.batch + a.tb_max - 1) / a.tb_max;
     }
-    const long long total = (long long)n_pass * a.blocks_per_pass;
-    const long long per = (total + gridDim.x - 1) / gridDim.x;
-    const long long g0 = per * blockIdx.x;
-    const long long g1 = min(total, g0 + per);
-    if (g0 >= g1) return;
+    const int total = (int)min((long long)n_pass * a.blocks_per_pass, 0x7FFFFFFFLL);
+    // Items are handed out one at a time from a device counter when there is one (uneven
+    // experts balance themselves), otherwise each workgroup takes an equal contiguous share.
+    const int per = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    int g_static = per * (int)blockIdx.x;
+    const int g_static_end = min(total, g_static + per);
+    if (!a.work_counter && g_static >= g_static_end) return;
 
-    if (lds_run) {
-        for (int i = threadIdx.x; i < a.lds_dict_entries; i += blockDim.x) lds_run[i] = a.run[i];
+    if constexpr (DICT == kDictRunLds) {
+        for (int i = threadIdx.x; i < a.lds_dict_entries; i += blockDim.x) lds_run_w[i] = ((gp_u32)a.run)[i];
     }
 
+    gp_u16 xg = (gp_u16)a.x;
     int cur_pass = -1, ntok = 0, slot0 = 0, expert = 0, tbi = 1;
-    for (long long g = g0; g < g1; g++) {
-        const int pass = (int)(g / a.blocks_per_pass);
-        const int blk = (int)(g - (long long)pass * a.blocks_per_pass);
+    for (;;) {
+        __syncthreads();  // everyone is done with the previous item (activations, token ids, next_item)
+        if (threadIdx.x == 0) {
+            int g;
+            if (a.work_counter) {
+                g = atomicAdd(a.work_counter, 1);
+                if (g >= total) g = -1;
+            } else {
+                g = g_static < g_static_end ? g_static : -1;
+            }
+            *next_item = g;
+        }
+        g_static++;
+        __syncthreads();
+        const int g = *next_item;
+        if (g < 0) break;
+        const int pass = g / a.blocks_per_pass;
+        const int blk = g - pass * a.blocks_per_pass;
         if (pass != cur_pass) {
-            __syncthreads();  // everyone is done with the previous tile's activations
             if (a.items) {
                 const Item it = a.items[pass];
                 expert = it.expert; slot0 = it.slot0; ntok = it.ntok;
@@ -301,11 +521,21 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
                 x_rows[t] = xr;
             }
             __syncthreads();
-            for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
-                for (int t = 0; t < tbi; t++) {
-                    float v = 0.0f;
-                    if (c < a.cols && t < ntok) v = bf16_bits_to_float(a.x[(size_t)x_rows[t] * a.ldx + c]);
-                    xs[(size_t)c * tbi + t] = v;
+            if (tbi == 1) {
+                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
+                    uint32_t v = 0;
+                    if (c < a.cols && ntok > 0) v = xg[(size_t)x_rows[0] * a.ldx + c];
+                    // {0, +x, 0, -x}; past the last column and for a missing token all four are 0
+                    const uint32_t neg = (c < a.cols && ntok > 0) ? (v ^ 0x8000u) : 0u;
+                    reinterpret_cast<uint2 *>(xs_w)[c] = make_uint2(v << 16, neg << 16);
+                }
+            } else {
+                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
+                    for (int t = 0; t < tbi; t++) {
+                        uint16_t v = 0;
+                        if (c < a.cols && t < ntok) v = xg[(size_t)x_rows[t] * a.ldx + c];
+                        xs_w[(size_t)c * tbi + t] = v;
+                    }
                 }
             }
             __syncthreads();
@@ -313,13 +543,11 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         }
         if (ntok == 0) continue;
         const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
-        const int r0 = blk * a.rows_per_item;
-        const int r1 = min(a.rows, r0 + a.rows_per_item);
         switch (tbi) {
-        case 1: product_rows<1, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        case 2: product_rows<2, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        case 4: product_rows<4, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
-        default: product_rows<8, RUN, EPI>(a, M, ntok, slot0, r0, r1, xs, tok_ids, lds_run); break;
+        case 1: product_block<1, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
+        case 2: product_block<2, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
+        case 4: product_block<4, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
+        default: product_block<8, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
         }
     }
 }
@@ -337,15 +565,15 @@ __global__ __launch_bounds__(256) void k_decode_dense(const ProductArgs a, int8_
         int8_t *orow = out + (size_t)r * a.cols;
         int incl = 0;
         for (uint32_t kb = kbeg; kb < kend; kb += 16) {
-            const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl, nullptr);
+            const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl);
             for (int j = 0; j < s.len; j++) {
                 int v = 0;
                 if constexpr (RUN) {
 #pragma unroll
                     for (int z = 0; z < kRunMaxNonzeros; z++) {
                         const int sh = kRunLenBits + kRunFieldBits * z;
-                        const int pos = (int)((s.e0 >> sh) & 31u);
-                        const int wi = ((int)(s.e0 << (32 - (sh + 7)))) >> 30;
+                        const int pos = (int)((s.e0 >> (sh + 3)) & 31u);
+                        const int wi = ((int)(s.e0 << (32 - (sh + 3)))) >> 30;
                         if (pos == j) v += wi;
                     }
                 } else {
@@ -660,43 +888,103 @@ struct ProductPlan {
     size_t smem;
 };
 
-// Pick the token tile, workgroup size and grid for a product over rows x cols matrices.
+// Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
+// matrices with the lane-per-row kernel (compressed path).
 qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
     if (st != QMOE_OK) return st;
     const Tuning &tu = tuning();
-    const size_t col_bytes = (size_t)(cols + kPadCols) * sizeof(float);
-    // activations of one tile should leave room for a second workgroup on the CU
-    size_t budget = (size_t)di.max_lds / 2 - 256;
+    const size_t max_lds = (size_t)di.max_lds;
+    const size_t fixed = 128;  // token ids, item hand-out
+    // activations: bf16, 8 bytes per column for up to four tokens (one token uses the
+    // {0,+x,0,-x} record), 16 bytes for eight
+    auto xs_bytes = [&](int tb) { return (size_t)(cols + kPadCols) * 2 * (size_t)std::max(tb, 4); };
+    if (xs_bytes(1) + fixed > max_lds) return QMOE_E_LIMIT;
+
+    // Keep the leading run entries in LDS when the launch is long enough to pay for staging
+    // them (one copy per workgroup): table reads that go to L2 cost a cycle per lane.
+    const double codes_per_row = std::max(1.0, cols / 22.0);
+    const double est_codes = (double)max_passes_hint * rows * codes_per_row;
+    const bool lds_table = run_table && tu.lds_dict_entries >= 0 && max_lds >= 128 * 1024 &&
+                           (tu.lds_dict_entries > 0 || est_codes / di.cus >= 1.0e6);
     int tb = kMaxTokenTile;
-    while (tb > 1 && col_bytes * tb > budget) tb >>= 1;
+    if (lds_table) {
+        while (tb > 4 && xs_bytes(tb) > 36 * 1024) tb >>= 1;
+    } else {
+        while (tb > 4 && xs_bytes(tb) + fixed > max_lds / 2) tb >>= 1;
+    }
     if (tu.token_tile > 0) {
         tb = 1;
         while (tb * 2 <= tu.token_tile && tb < kMaxTokenTile) tb <<= 1;
     }
-    if (col_bytes * tb + 256 > (size_t)di.max_lds) return QMOE_E_LIMIT;
+    while (tb > 4 && xs_bytes(tb) + fixed > max_lds) tb >>= 1;
     int lds_dict = 0;
-    if (run_table && tu.lds_dict_entries > 0) {
-        lds_dict = std::min(tu.lds_dict_entries, kTableEntries);
-        while (tb > 1 && col_bytes * tb + 64 + 4 * (size_t)lds_dict > (size_t)di.max_lds) tb >>= 1;
-        if (col_bytes * tb + 64 + 4 * (size_t)lds_dict > (size_t)di.max_lds)
-            lds_dict = (int)(((size_t)di.max_lds - col_bytes * tb - 64) / 4);
+    if (lds_table) {
+        const size_t room = (max_lds - xs_bytes(tb) - fixed) / 4;
+        lds_dict = (int)std::min<size_t>(room, kTableEntries);
+        if (tu.lds_dict_entries > 0) lds_dict = std::min(lds_dict, tu.lds_dict_entries);
+        if (lds_dict < 4096) lds_dict = 0;
     }
     p->tb_max = tb;
     p->lds_dict_entries = lds_dict;
-    p->smem = col_bytes * tb + 64 + 4 * (size_t)lds_dict;
-    int threads = tu.threads > 0 ? tu.threads : (p->smem * 2 > (size_t)di.max_lds ? 1024 : 512);
-    threads = std::max(64, std::min(1024, threads / 64 * 64));
-    p->threads = threads;
-    int rpi = tu.rows_per_item > 0 ? tu.rows_per_item : 4 * (threads / 16);
-    rpi = std::max(1, std::min(rpi, rows));
-    p->rows_per_item = rpi;
-    p->blocks_per_pass = (rows + rpi - 1) / rpi;
-    const int wg_per_cu = tu.grid_per_cu > 0 ? tu.grid_per_cu
-                                             : std::max(1, std::min((int)((size_t)di.max_lds / p->smem), 2048 / threads));
+    p->smem = xs_bytes(tb) + fixed + 4 * (size_t)lds_dict;
+    const int fit = (int)std::max<size_t>(1, max_lds / p->smem);
+
+    // Lanes per matrix: a lane should own at least ~256 codewords (eight 64-byte chunks), and
+    // rows / lanes should round up with little waste since a wavefront is as slow as its
+    // lane with the most rows.  Search workgroup sizes and block counts for the best fill.
+    const int want_rpl = std::max(1, (int)std::ceil(256.0 / codes_per_row));
+    const int max_threads = fit >= 4 ? 256 : (fit >= 2 ? 512 : 1024);
+    int best_t = 64, best_b = 1;
+    double best_score = -1.0;
+    for (int b = 1; b <= 64; b++) {
+        for (int t = 64; t <= max_threads; t += 64) {
+            const long long nl = (long long)b * t;
+            const int rpl = (int)((rows + nl - 1) / nl);
+            if (rpl < want_rpl && !(b == 1 && t == 64)) continue;
+            const double fill = (double)rows / ((double)nl * rpl);
+            // prefer full workgroups (occupancy) and few blocks (less restaging)
+            const double score = fill * std::min(1.0, (double)t / (0.625 * max_threads)) - 0.002 * b;
+            if (score > best_score) { best_score = score; best_t = t; best_b = b; }
+        }
+    }
+    if (tu.threads > 0) {
+        best_t = std::max(64, std::min(1024, tu.threads / 64 * 64));
+        const int rpl = tu.rows_per_item > 0 ? tu.rows_per_item : want_rpl;
+        best_b = std::max(1, (int)((rows + (long long)best_t * rpl - 1) / ((long long)best_t * rpl)));
+    }
+    p->threads = best_t;
+    p->blocks_per_pass = best_b;
+    p->rows_per_item = (rows + best_b - 1) / best_b;
+    const int wg_per_cu = tu.grid_per_cu > 0 ? tu.grid_per_cu : std::max(1, std::min(fit, 2048 / best_t));
     long long grid = (long long)di.cus * wg_per_cu;
+    const long long items = max_passes_hint * p->blocks_per_pass;
+    if (items < grid) grid = std::max(1LL, items);
+    p->grid = (int)grid;
+    return QMOE_OK;
+}
+
+// The dense bf16 comparator keeps its own simple plan: fp32 activations in LDS, wavefront per row.
+qmoe_status plan_dense(int rows, int cols, long long max_passes_hint, ProductPlan *p)
+{
+    DeviceInfo di;
+    const qmoe_status st = device_info(&di);
+    if (st != QMOE_OK) return st;
+    const size_t max_lds = (size_t)di.max_lds;
+    const size_t col_bytes = (size_t)(cols + kPadCols) * sizeof(float);
+    int tb = kMaxTokenTile;
+    while (tb > 1 && col_bytes * tb + 64 > max_lds / 2) tb >>= 1;
+    if (col_bytes * tb + 64 > max_lds) return QMOE_E_LIMIT;
+    p->tb_max = tb;
+    p->lds_dict_entries = 0;
+    p->smem = col_bytes * tb + 64;
+    p->threads = 512;
+    p->rows_per_item = std::min(rows, 128);
+    p->blocks_per_pass = (rows + p->rows_per_item - 1) / p->rows_per_item;
+    const int fit = (int)std::max<size_t>(1, max_lds / p->smem);
+    long long grid = (long long)di.cus * std::max(1, std::min(fit, 4));
     const long long items = max_passes_hint * p->blocks_per_pass;
     if (items < grid) grid = std::max(1LL, items);
     p->grid = (int)grid;
@@ -712,20 +1000,22 @@ qmoe_status allow_lds(K kernel, size_t smem)
     return QMOE_OK;
 }
 
-template <bool RUN, int EPI>
+template <int DICT, int EPI>
 qmoe_status launch_product_as(const ProductArgs &a, const ProductPlan &p, hipStream_t s)
 {
-    const qmoe_status st = allow_lds(k_product<RUN, EPI>, p.smem);
+    const qmoe_status st = allow_lds(k_product<DICT, EPI>, p.smem);
     if (st != QMOE_OK) return st;
-    hipLaunchKernelGGL((k_product<RUN, EPI>), dim3(p.grid), dim3(p.threads), p.smem, s, a);
+    hipLaunchKernelGGL((k_product<DICT, EPI>), dim3(p.grid), dim3(p.threads), p.smem, s, a);
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }
 
 qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
 {
-    if (run) return a.epilogue ? launch_product_as<true, 1>(a, p, s) : launch_product_as<true, 0>(a, p, s);
-    return a.epilogue ? launch_product_as<false, 1>(a, p, s) : launch_product_as<false, 0>(a, p, s);
+    if (!run) return a.epilogue ? launch_product_as<kDictWords, 1>(a, p, s) : launch_product_as<kDictWords, 0>(a, p, s);
+    if (p.lds_dict_entries > 0)
+        return a.epilogue ? launch_product_as<kDictRunLds, 1>(a, p, s) : launch_product_as<kDictRunLds, 0>(a, p, s);
+    return a.epilogue ? launch_product_as<kDictRun, 1>(a, p, s) : launch_product_as<kDictRun, 0>(a, p, s);
 }
 
 qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
@@ -965,6 +1255,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwi.blocks_per_pass;
     a.tb_max = pwi.tb_max;
     a.lds_dict_entries = pwi.lds_dict_entries;
+    a.work_counter = lp.counters + 5;
     if (phases & 2)
         if ((st = launch_product(a, pwi, run, s)) != QMOE_OK) return st;
     // second product: y[token] = gate * Wo hidden[slot]
@@ -984,6 +1275,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwo.blocks_per_pass;
     a.tb_max = pwo.tb_max;
     a.lds_dict_entries = pwo.lds_dict_entries;
+    a.work_counter = lp.counters + 6;
     if (phases & 4) return launch_product(a, pwo, run, s);
     return QMOE_OK;
 }
@@ -1001,8 +1293,8 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
     ProductPlan pwi, pwo;
-    if ((st = plan_product(d_ff, d_model, false, n_tokens, &pwi)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, false, n_tokens, &pwo)) != QMOE_OK) return st;
+    if ((st = plan_dense(d_ff, d_model, n_tokens, &pwi)) != QMOE_OK) return st;
+    if ((st = plan_dense(d_model, d_ff, n_tokens, &pwo)) != QMOE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
     const int phases = tuning().phases > 0 ? tuning().phases : 7;

@@ -71,7 +71,7 @@ qmoe_status finish_dict(qmoe_dict *d)
             if (s != 0) {
                 if (nnz < kRunMaxNonzeros) {
                     const uint32_t weight = (s == 2) ? 1u : 3u;  // 2-bit signed: +1 / -1
-                    run |= ((uint32_t)j | (weight << 5)) << (kRunLenBits + kRunFieldBits * nnz);
+                    run |= (((uint32_t)j << 3) | (weight << 1)) << (kRunLenBits + kRunFieldBits * nnz);
                 }
                 nnz++;
             }
