@@ -164,7 +164,7 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
             s.e0 = w.x; s.e1 = w.y;
         }
     }
-    s.len = RUN ? (int)(s.e0 & 31u) : 2 * (int)(s.e0 & 15u);
+    s.len = RUN ? (int)((s.e0 & 0xFFu) >> 3) : 2 * (int)(s.e0 & 15u);
     // previous step's total sits in lane 15 of the row; lane 0 takes it in
     const int carry = __builtin_amdgcn_update_dpp(0, incl, kRowRor1, 0xf, 0xf, false);
     incl = row_scan16(s.len + (l16 == 0 ? carry : 0));
@@ -188,6 +188,9 @@ struct Entry {
     uint32_t e0, e1;  // run entry (e0), or the two interchange words (e0, e1)
 };
 
+// Table look-up without branches, so that the compiler can keep many of them in flight:
+// with the head of the run table in LDS, every lane reads LDS and global memory, each
+// from entry 0 when the codeword lives in the other one.
 template <int DICT>
 __device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t code, lp_u32 lds_run)
 {
@@ -195,10 +198,10 @@ __device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t cod
     if constexpr (DICT == kDictRun) {
         e.e0 = ((gp_u32)a.run)[code];
     } else if constexpr (DICT == kDictRunLds) {
-        if ((int)code < a.lds_dict_entries)
-            e.e0 = lds_run[code];
-        else
-            e.e0 = ((gp_u32)a.run)[code];
+        const bool in_lds = (int)code < a.lds_dict_entries;
+        const uint32_t from_lds = lds_run[in_lds ? code : 0u];
+        const uint32_t from_l2 = ((gp_u32)a.run)[in_lds ? 0u : code];
+        e.e0 = in_lds ? from_lds : from_l2;
     } else {
         const unsigned long long w = ((gp_u64)a.words)[code];
         e.e0 = (uint32_t)w; e.e1 = (uint32_t)(w >> 32);
@@ -209,26 +212,29 @@ __device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t cod
 template <int DICT>
 __device__ __forceinline__ int entry_len(const Entry &e)
 {
-    return DICT == kDictWords ? 2 * (int)(e.e0 & 15u) : (int)(e.e0 & 31u);
+    return DICT == kDictWords ? 2 * (int)(e.e0 & 15u) : (int)((e.e0 & 0xFFu) >> 3);
 }
 
-// activations of one column for the TBI (>= 2) tokens of the tile: packed bf16 in LDS -> fp32
+// activations of one column for the tokens of the tile: bf16 in LDS -> fp32.
+// `rec8` is 8 * column.  One token: 8-byte records, +x in the second 16-bit slot;
+// 2 / 4 / 8 tokens: packed, 4 / 8 / 16 bytes per column.
 template <int TBI>
-__device__ __forceinline__ void lds_load_x(lp_u16 xs, int col, float (&v)[TBI])
+__device__ __forceinline__ void lds_load_x(uint32_t xs_addr, uint32_t rec8, float (&v)[TBI])
 {
     typedef const __attribute__((address_space(3))) uint32_t *p32;
     if constexpr (TBI == 1) {
-        v[0] = __uint_as_float((uint32_t)xs[4 * col + 1] << 16);  // the +x slot of the record
+        v[0] = __uint_as_float((uint32_t)(*(lp_u16)(uintptr_t)(xs_addr + rec8 + 2u)) << 16);
     } else if constexpr (TBI == 2) {
-        const uint32_t u = ((p32)xs)[col];
+        const uint32_t u = *(p32)(uintptr_t)(xs_addr + (rec8 >> 1));
         v[0] = __uint_as_float(u << 16); v[1] = __uint_as_float(u & 0xFFFF0000u);
     } else if constexpr (TBI == 4) {
-        const uint32_t u0 = ((p32)xs)[2 * col], u1 = ((p32)xs)[2 * col + 1];
+        p32 p = (p32)(uintptr_t)(xs_addr + rec8);
+        const uint32_t u0 = p[0], u1 = p[1];
         v[0] = __uint_as_float(u0 << 16); v[1] = __uint_as_float(u0 & 0xFFFF0000u);
         v[2] = __uint_as_float(u1 << 16); v[3] = __uint_as_float(u1 & 0xFFFF0000u);
     } else {
-        const uint32_t u0 = ((p32)xs)[4 * col], u1 = ((p32)xs)[4 * col + 1];
-        const uint32_t u2 = ((p32)xs)[4 * col + 2], u3 = ((p32)xs)[4 * col + 3];
+        p32 p = (p32)(uintptr_t)(xs_addr + (rec8 << 1));
+        const uint32_t u0 = p[0], u1 = p[1], u2 = p[2], u3 = p[3];
         v[0] = __uint_as_float(u0 << 16); v[1] = __uint_as_float(u0 & 0xFFFF0000u);
         v[2] = __uint_as_float(u1 << 16); v[3] = __uint_as_float(u1 & 0xFFFF0000u);
         v[4] = __uint_as_float(u2 << 16); v[5] = __uint_as_float(u2 & 0xFFFF0000u);
@@ -236,42 +242,20 @@ __device__ __forceinline__ void lds_load_x(lp_u16 xs, int col, float (&v)[TBI])
     }
 }
 
-// acc[t] += sum over the entry's non-zeros of weight * x[t][col + position]
-//
-// One token (TBI == 1) with a run table: the activations sit in LDS as one 8-byte
-// record {0, +x, 0, -x} (bf16) per column, and a run-entry field is the byte offset
-// of the wanted slot inside the record at `col + position` -- unused fields hit a
-// zero slot.  The 16-bit value is loaded straight into the upper half of a register
-// whose lower half stays zero, which makes it the fp32 value: three adds per
-// codeword, no unpacking, no sign handling.
+// acc[t] += sum over the entry's non-zeros of weight * x[t][column + position], the
+// column given as pos8 = 8 * column.  (The one-token run-table case has its own code
+// in consume8_one; this is the form every other case uses.)
 template <int TBI, int DICT>
-__device__ __forceinline__ void accumulate(const Entry &e, lp_u16 xs, uint32_t xs_addr, int col,
-                                           float (&acc)[TBI], float (&xr)[3])
+__device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uint32_t pos8, float (&acc)[TBI])
 {
-    if constexpr (DICT != kDictWords && TBI == 1) {
-        const uint32_t rec = xs_addr + ((uint32_t)col << 3);
-        const uint32_t a0 = rec + ((e.e0 >> kRunLenBits) & 0xFFu);
-        const uint32_t a1 = rec + ((e.e0 >> (kRunLenBits + 8)) & 0xFFu);
-        const uint32_t a2 = rec + ((e.e0 >> (kRunLenBits + 16)) & 0xFFu);
-        asm volatile("ds_read_u16_d16_hi %0, %3\n\t"
-                     "ds_read_u16_d16_hi %1, %4\n\t"
-                     "ds_read_u16_d16_hi %2, %5\n\t"
-                     "s_waitcnt lgkmcnt(0)"
-                     : "+v"(xr[0]), "+v"(xr[1]), "+v"(xr[2])
-                     : "v"(a0), "v"(a1), "v"(a2)
-                     : "memory");
-        acc[0] += xr[0];
-        acc[0] += xr[1];
-        acc[0] += xr[2];
-    } else if constexpr (DICT != kDictWords) {
+    if constexpr (DICT != kDictWords) {
 #pragma unroll
         for (int j = 0; j < kRunMaxNonzeros; j++) {
-            const int sh = kRunLenBits + kRunFieldBits * j;
-            const int pos = (int)((e.e0 >> (sh + 3)) & 31u);
-            const int wi = ((int)(e.e0 << (32 - (sh + 3)))) >> 30;  // signed 2-bit weight
+            const uint32_t field = (e.e0 >> (8 + 8 * j)) & 0xFFu;
+            const int wi = ((int)(e.e0 << (32 - (8 + 8 * j + 3)))) >> 30;  // signed 2-bit weight
             const float w = (float)wi;
             float xv[TBI];
-            lds_load_x<TBI>(xs, col + pos, xv);
+            lds_load_x<TBI>(xs_addr, pos8 + (field & 0xF8u), xv);
 #pragma unroll
             for (int t = 0; t < TBI; t++) acc[t] = fmaf(w, xv[t], acc[t]);
         }
@@ -286,7 +270,7 @@ __device__ __forceinline__ void accumulate(const Entry &e, lp_u16 xs, uint32_t x
                 const int sym = (int)((w >> (4 + b)) & 3u);
                 const float wt = sym == 2 ? 1.0f : (sym == 1 ? -1.0f : 0.0f);
                 float xv[TBI];
-                lds_load_x<TBI>(xs, col + 14 * h + (b >> 1), xv);
+                lds_load_x<TBI>(xs_addr, pos8 + 8u * (uint32_t)(14 * h + (b >> 1)), xv);
 #pragma unroll
                 for (int t = 0; t < TBI; t++) acc[t] = fmaf(wt, xv[t], acc[t]);
             }
@@ -297,46 +281,123 @@ __device__ __forceinline__ void accumulate(const Entry &e, lp_u16 xs, uint32_t x
 // Per-lane decoder state for one item.
 template <int TBI>
 struct LaneState {
-    float acc[TBI];
-    float xr[3];       // upper halves receive the gathered bf16 values, lower halves stay 0
-    int idx;           // column reached in the current row
+    float acc[TBI];    // running sum since the last row that was written
+    uint32_t pos8;     // 8 * (column reached in the current row)
     int row, rb;       // current row, end of this lane's rows
-    float scale, scale_next;
 };
 
-// One decoded entry of one lane: apply its non-zeros, advance, close the row when it is full.
-template <int TBI, int DICT, int EPI>
-__device__ __forceinline__ void consume(const ProductArgs &a, const qmoe_matrix &M, LaneState<TBI> &st,
-                                        const Entry &e, int ntok, int slot0, lp_u16 xs, uint32_t xs_addr,
-                                        const int *tok_ids)
+// What a lane needs to write a finished row; everything it reads sits in LDS, so
+// that closing a row never waits on global memory (which would also wait for the
+// stream and table prefetches in flight).
+struct RowSink {
+    lp_u16 scale_s;   // binary16 scales of the block's rows
+    int r0;           // first row of the block
+    const __attribute__((address_space(3))) int *tok_ids;   // output token of each tile slot
+    const __attribute__((address_space(3))) float *gate_s;  // gate of each tile slot
+    int ntok, slot0;
+};
+
+template <int TBI, int EPI>
+__device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<TBI> &st, const float (&sum)[TBI],
+                                          const RowSink &rs)
 {
-    accumulate<TBI, DICT>(e, xs, xs_addr, st.idx, st.acc, st.xr);
-    st.idx += entry_len<DICT>(e);
-    if (__any(st.idx >= a.cols)) {
-        if (st.idx >= a.cols) {
-            if (st.row < st.rb) {
+    const float scale = half_bits_to_float(rs.scale_s[st.row - rs.r0]);
 #pragma unroll
-                for (int t = 0; t < TBI; t++) {
-                    if (t < ntok) {
-                        const float v = st.acc[t] * st.scale;
-                        if constexpr (EPI == 0) {
-                            const int tok = tok_ids[t];
-                            const float g = a.gate ? a.gate[tok] : 1.0f;
-                            reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = g * v;
-                        } else {
-                            const float h = v > 0.0f ? v : 0.0f;
-                            reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + st.row] =
-                                float_to_bf16_bits(h);
-                        }
-                    }
-                }
+    for (int t = 0; t < TBI; t++) {
+        if (t < rs.ntok) {
+            const float v = sum[t] * scale;
+            if constexpr (EPI == 0) {
+                const int tok = rs.tok_ids[t];
+                reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = rs.gate_s[t] * v;
+            } else {
+                const float h = v > 0.0f ? v : 0.0f;
+                reinterpret_cast<uint16_t *>(a.out)[(size_t)(rs.slot0 + t) * a.ld_out + st.row] =
+                    float_to_bf16_bits(h);
             }
+        }
+    }
+}
+
+// General form: one decoded entry at a time, the row closed as soon as it is full.
+// Works for any width and any table; used for narrow matrices (several row ends may
+// fall into eight codewords) and for tables without run entries.
+template <int TBI, int DICT, int EPI>
+__device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI> &st, const Entry &e,
+                                         uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
+{
+    accumulate<TBI, DICT>(e, xs_addr, st.pos8, st.acc);
+    st.pos8 += 8u * (uint32_t)entry_len<DICT>(e);
+    if (__any(st.pos8 >= cols8)) {
+        if (st.pos8 >= cols8) {
+            if (st.row < st.rb) write_row<TBI, EPI>(a, st, st.acc, rs);
 #pragma unroll
             for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
-            st.idx -= a.cols;
+            st.pos8 -= cols8;
             st.row += 1;
-            st.scale = st.scale_next;
-            st.scale_next = st.row + 1 < st.rb ? half_bits_to_float(((gp_u16)M.scale_f16)[st.row + 1]) : 0.0f;
+        }
+    }
+}
+
+// Fast form for run tables and rows of at least 224 values (at most one row end per
+// eight codewords): the eight entries are applied without a branch in between, so
+// their LDS gathers overlap; the running sum is never reset inside, a row end only
+// records the sum reached (`snap`), and the row is written once after the eight.
+// One token: the activations are 8-byte records {0, +x, 0, -x} and an entry's field
+// is the byte offset of the wanted 16-bit slot from the record of the run's first
+// column (unused fields land on a zero), so a non-zero costs one add.
+template <int TBI, int DICT, int EPI>
+__device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &st, const Entry (&e)[8],
+                                         uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
+{
+    uint32_t pos[8];
+    bool wrap[8];
+    uint32_t p = st.pos8;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        pos[j] = p;
+        p += e[j].e0 & 0xFFu;
+        wrap[j] = p >= cols8;
+        p = wrap[j] ? p - cols8 : p;
+    }
+    st.pos8 = p;
+    float snap[TBI];
+    bool wrapped = false;
+#pragma unroll
+    for (int t = 0; t < TBI; t++) snap[t] = 0.0f;
+    if constexpr (TBI == 1) {
+        float x[24];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t rec = xs_addr + pos[j];
+#pragma unroll
+            for (int z = 0; z < 3; z++) {
+                const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
+                x[3 * j + z] = __uint_as_float((uint32_t)(*(lp_u16)(uintptr_t)addr) << 16);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            st.acc[0] += x[3 * j];
+            st.acc[0] += x[3 * j + 1];
+            st.acc[0] += x[3 * j + 2];
+            snap[0] = wrap[j] ? st.acc[0] : snap[0];
+            wrapped = wrapped || wrap[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            accumulate<TBI, DICT>(e[j], xs_addr, pos[j], st.acc);
+#pragma unroll
+            for (int t = 0; t < TBI; t++) snap[t] = wrap[j] ? st.acc[t] : snap[t];
+            wrapped = wrapped || wrap[j];
+        }
+    }
+    if (__any(wrapped)) {
+        if (wrapped) {
+            if (st.row < st.rb) write_row<TBI, EPI>(a, st, snap, rs);
+#pragma unroll
+            for (int t = 0; t < TBI; t++) st.acc[t] -= snap[t];
+            st.row += 1;
         }
     }
 }
@@ -362,9 +423,8 @@ __device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp
 // per lane, exactly the paper's sequential decoder, 64 of them per wavefront.  Table
 // entries are fetched eight codewords ahead of their use.
 template <int TBI, int DICT, int EPI>
-__device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_matrix &M, int ntok,
-                                              int slot0, int blk, lp_u16 xs, uint32_t xs_addr,
-                                              const int *tok_ids, lp_u32 lds_run)
+__device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_matrix &M, int blk,
+                                              uint32_t xs_addr, const RowSink &rs, lp_u32 lds_run)
 {
     const int nlanes = (int)blockDim.x * a.blocks_per_pass;
     const int gl = blk * (int)blockDim.x + (int)threadIdx.x;
@@ -390,55 +450,47 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) nchunks = max(nchunks, __shfl_xor(nchunks, d, 64));
 
+    const uint32_t cols8 = 8u * (uint32_t)a.cols;
     LaneState<TBI> st;
 #pragma unroll
     for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
-    st.xr[0] = st.xr[1] = st.xr[2] = 0.0f;
-    st.idx = 0;
+    st.pos8 = 0;
     st.row = ra;
     st.rb = rb;
-    st.scale = ra < rb ? half_bits_to_float(((gp_u16)M.scale_f16)[ra]) : 0.0f;
-    st.scale_next = ra + 1 < rb ? half_bits_to_float(((gp_u16)M.scale_f16)[ra + 1]) : 0.0f;
 
-    u32x4 q[4], qn[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) q[i] = ((gp_u32x4)chunk)[i];
-    Entry ecur[8], enxt[8];
-    lookup8<DICT>(a, q[0], lds_run, ecur);
-    for (int c = 0; c < nchunks; c++) {
-        const uintptr_t next = min(chunk + 64u, last_chunk);  // lanes past their end re-read their last chunk
-#pragma unroll
-        for (int i = 0; i < 4; i++) qn[i] = ((gp_u32x4)next)[i];
-        // is every slot of this chunk a codeword of its lane, in every lane of the wavefront?
-        const bool whole = rel >= 0 && (uint32_t)rel + 32u <= n;
-        if (__all(whole)) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                lookup8<DICT>(a, i < 3 ? q[i + 1] : qn[0], lds_run, enxt);
-#pragma unroll
-                for (int j = 0; j < 8; j++)
-                    consume<TBI, DICT, EPI>(a, M, st, ecur[j], ntok, slot0, xs, xs_addr, tok_ids);
-#pragma unroll
-                for (int j = 0; j < 8; j++) ecur[j] = enxt[j];
-            }
+    // The stream is walked in 16-byte pieces (eight codewords): piece p + 2 is being
+    // loaded and the entries of piece p + 1 looked up while piece p is applied.
+    const int npieces = 4 * nchunks;
+    const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(4 * my_chunks - 1, 0);
+    const bool fast = DICT != kDictWords && a.cols >= 224;
+    auto load_piece = [&](int p) -> u32x4 {
+        // lanes past their own end re-read their last piece (its slots are masked out below)
+        return *(gp_u32x4)min(chunk + 16u * (uintptr_t)p, last_piece);
+    };
+    auto apply = [&](const Entry (&e)[8], int r) {
+        // r: stream index (relative to K0) of the piece's first slot
+        const bool whole = r >= 0 && (uint32_t)r + 8u <= n;  // all eight are this lane's codewords
+        if (fast && __all(whole)) {
+            consume8<TBI, DICT, EPI>(a, st, e, cols8, xs_addr, rs);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                lookup8<DICT>(a, i < 3 ? q[i + 1] : qn[0], lds_run, enxt);
-#pragma unroll
-                for (int j = 0; j < 8; j++) {
-                    Entry e = ecur[j];
-                    if ((uint32_t)(rel + 8 * i + j) >= n) { e.e0 = 0u; e.e1 = 0u; }  // not this lane's codeword
-                    consume<TBI, DICT, EPI>(a, M, st, e, ntok, slot0, xs, xs_addr, tok_ids);
-                }
-#pragma unroll
-                for (int j = 0; j < 8; j++) ecur[j] = enxt[j];
+            for (int j = 0; j < 8; j++) {
+                Entry ej = e[j];
+                if ((uint32_t)(r + j) >= n) { ej.e0 = 0u; ej.e1 = 0u; }  // not this lane's codeword
+                consume1<TBI, DICT, EPI>(a, st, ej, cols8, xs_addr, rs);
             }
         }
-        chunk = next;
-        rel += 32;
-#pragma unroll
-        for (int i = 0; i < 4; i++) q[i] = qn[i];
+    };
+    Entry ea[8], eb[8];
+    u32x4 cb = load_piece(1);
+    lookup8<DICT>(a, load_piece(0), lds_run, ea);
+    for (int p = 0; p < npieces; p += 2) {
+        const u32x4 cc = load_piece(p + 2);
+        lookup8<DICT>(a, cb, lds_run, eb);
+        apply(ea, rel + 8 * p);
+        cb = load_piece(p + 3);
+        lookup8<DICT>(a, cc, lds_run, ea);
+        apply(eb, rel + 8 * p + 8);
     }
 }
 
@@ -456,8 +508,11 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     const size_t xs_bytes = (size_t)(a.cols + kPadCols) * max(a.tb_max, 4) * sizeof(uint16_t);
     int *tok_ids = reinterpret_cast<int *>(smem + xs_bytes);            // [kMaxTokenTile] output token
     int *x_rows = tok_ids + kMaxTokenTile;                              // [kMaxTokenTile] input row
-    int *next_item = x_rows + kMaxTokenTile;                            // [1]
-    uint32_t *lds_run_w = reinterpret_cast<uint32_t *>(smem + xs_bytes + 128);
+    float *gate_s = reinterpret_cast<float *>(x_rows + kMaxTokenTile);  // [kMaxTokenTile] gate
+    int *next_item = reinterpret_cast<int *>(gate_s + kMaxTokenTile);   // [1]
+    uint16_t *scale_w = reinterpret_cast<uint16_t *>(smem + xs_bytes + 128);  // [rows_per_item] row scales
+    const size_t scale_bytes = ((size_t)a.rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
+    uint32_t *lds_run_w = reinterpret_cast<uint32_t *>(smem + xs_bytes + 128 + scale_bytes);
     lp_u16 xs = (lp_u16)xs_w;
     lp_u32 lds_run = (lp_u32)lds_run_w;
     const uint32_t xs_addr = (uint32_t)(uintptr_t)xs;  // LDS byte address of the activations
@@ -519,6 +574,7 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
                 }
                 tok_ids[t] = tok;
                 x_rows[t] = xr;
+                gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
             }
             __syncthreads();
             if (tbi == 1) {
@@ -543,11 +599,26 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         }
         if (ntok == 0) continue;
         const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
+        // the block's rows: lanes blk*T .. blk*T+T-1 of the even split (see product_block)
+        const int nlanes = (int)blockDim.x * a.blocks_per_pass;
+        const int base_rows = a.rows / nlanes, extra = a.rows - base_rows * nlanes;
+        const int gl0 = blk * (int)blockDim.x, gl1 = gl0 + (int)blockDim.x;
+        const int r0 = gl0 * base_rows + min(gl0, extra);
+        const int r1 = min(gl1 * base_rows + min(gl1, extra), r0 + a.rows_per_item);
+        for (int i = threadIdx.x; i < r1 - r0; i += blockDim.x) scale_w[i] = ((gp_u16)M.scale_f16)[r0 + i];
+        __syncthreads();
+        RowSink rs;
+        rs.scale_s = (lp_u16)scale_w;
+        rs.r0 = r0;
+        rs.tok_ids = (const __attribute__((address_space(3))) int *)tok_ids;
+        rs.gate_s = (const __attribute__((address_space(3))) float *)gate_s;
+        rs.ntok = ntok;
+        rs.slot0 = slot0;
         switch (tbi) {
-        case 1: product_block<1, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
-        case 2: product_block<2, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
-        case 4: product_block<4, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
-        default: product_block<8, DICT, EPI>(a, M, ntok, slot0, blk, xs, xs_addr, tok_ids, lds_run); break;
+        case 1: product_block<1, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
+        case 2: product_block<2, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
+        case 4: product_block<4, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
+        default: product_block<8, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         }
     }
 }
@@ -571,7 +642,7 @@ __global__ __launch_bounds__(256) void k_decode_dense(const ProductArgs a, int8_
                 if constexpr (RUN) {
 #pragma unroll
                     for (int z = 0; z < kRunMaxNonzeros; z++) {
-                        const int sh = kRunLenBits + kRunFieldBits * z;
+                        const int sh = 8 + 8 * z;
                         const int pos = (int)((s.e0 >> (sh + 3)) & 31u);
                         const int wi = ((int)(s.e0 << (32 - (sh + 3)))) >> 30;
                         if (pos == j) v += wi;
@@ -928,9 +999,7 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
         if (lds_dict < 4096) lds_dict = 0;
     }
     p->tb_max = tb;
-    p->lds_dict_entries = lds_dict;
-    p->smem = xs_bytes(tb) + fixed + 4 * (size_t)lds_dict;
-    const int fit = (int)std::max<size_t>(1, max_lds / p->smem);
+    const int fit = (int)std::max<size_t>(1, max_lds / (xs_bytes(tb) + fixed + 4 * (size_t)lds_dict));
 
     // Lanes per matrix: a lane should own at least ~256 codewords (eight 64-byte chunks), and
     // rows / lanes should round up with little waste since a wavefront is as slow as its
@@ -957,7 +1026,19 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     }
     p->threads = best_t;
     p->blocks_per_pass = best_b;
-    p->rows_per_item = (rows + best_b - 1) / best_b;
+    // most rows a block can own under the even split of rows over lanes
+    const long long all_lanes = (long long)best_b * best_t;
+    p->rows_per_item = (int)std::min<long long>(rows, (long long)best_t * (rows / all_lanes + 1));
+    const size_t scale_bytes = ((size_t)p->rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
+    if (lds_dict > 0) {
+        // the row scales take their share of LDS from the table
+        const size_t room = max_lds - xs_bytes(tb) - fixed - scale_bytes;
+        lds_dict = (int)std::min<size_t>((size_t)lds_dict, room / 4);
+        if (lds_dict < 4096) lds_dict = 0;
+    }
+    p->lds_dict_entries = lds_dict;
+    p->smem = xs_bytes(tb) + fixed + scale_bytes + 4 * (size_t)lds_dict;
+    if (p->smem > max_lds) return QMOE_E_LIMIT;
     const int wg_per_cu = tu.grid_per_cu > 0 ? tu.grid_per_cu : std::max(1, std::min(fit, 2048 / best_t));
     long long grid = (long long)di.cus * wg_per_cu;
     const long long items = max_passes_hint * p->blocks_per_pass;

@@ -61,7 +61,7 @@ qmoe_status finish_dict(qmoe_dict *d)
         const int np = (int)(w0 & 15u);
         if (np < 1 || np > 14 || (int)(w1 & 15u) != np) return QMOE_E_BAD_SYMBOL;
         d->max_pairs = std::max(d->max_pairs, np);
-        uint32_t run = (uint32_t)(2 * np);
+        uint32_t run = (uint32_t)(8 * 2 * np);
         int nnz = 0;
         for (int j = 0; j < kMaxSyms; j++) {
             const uint32_t w = j < 14 ? w0 : w1;
@@ -71,7 +71,7 @@ qmoe_status finish_dict(qmoe_dict *d)
             if (s != 0) {
                 if (nnz < kRunMaxNonzeros) {
                     const uint32_t weight = (s == 2) ? 1u : 3u;  // 2-bit signed: +1 / -1
-                    run |= (((uint32_t)j << 3) | (weight << 1)) << (kRunLenBits + kRunFieldBits * nnz);
+                    run |= (((uint32_t)j << 3) | (weight << 1)) << (8 + 8 * nnz);
                 }
                 nnz++;
             }

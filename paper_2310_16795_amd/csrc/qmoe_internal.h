@@ -15,16 +15,16 @@ constexpr int kTableEntries = 65536;  // device tables always span every uint16 
 
 // Compact device entry ("run entry") for tables whose entries hold at most three
 // non-zero symbols, which is the case for the paper's table: a codeword is then
-// a run length plus at most three signed positions.
-//   bits 0..4        number of ternary values the entry decodes to (2..28; 0 = no entry)
-//   bits 5+8j..12+8j field of the j-th non-zero (j = 0,1,2), all zero = slot unused:
-//                      bit 0      always 0
-//                      bits 1..2  its weight as a 2-bit signed integer: +1 (01) or -1 (11)
-//                      bits 3..7  its position inside the run
-// Read as a whole, a field is the byte offset of the wanted value in an activation
-// record of four 16-bit slots {0, +x, 0, -x} per column (see the product kernel).
-constexpr int kRunLenBits = 5;
-constexpr int kRunFieldBits = 8;
+// a run length plus at most three signed positions.  Four bytes:
+//   byte 0        8 * (number of ternary values the entry decodes to), 16..224; 0 = no entry
+//   byte 1+j      field of the j-th non-zero (j = 0,1,2), 0 = slot unused:
+//                   bit 0      always 0
+//                   bits 1..2  its weight as a 2-bit signed integer: +1 (01) or -1 (11)
+//                   bits 3..7  its position inside the run
+// The product kernel keeps one token's activations as 8-byte records {0, +x, 0, -x}
+// (bf16) per column: byte 0 is then the distance in bytes the decoder advances, and a
+// field is the byte offset, from the record of the run's first column, of the value
+// to add -- unused fields land on a zero.
 constexpr int kRunMaxNonzeros = 3;
 
 // Device blob written by qmoe_dict_upload: run entries first, then the
