@@ -32,7 +32,7 @@ def log(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def build_layer(w, dd, gpu, workers):
+def build_layer(w, dd, gpu, workers, interchange_order=False):
     """Generate and encode every expert (host threads), upload once."""
     import paper_2310_16795_amd as q
     from paper_2310_16795_amd import device as dev
@@ -57,7 +57,7 @@ def build_layer(w, dd, gpu, workers):
             if done % 256 == 0:
                 log(f"encoded {done}/{w.n_experts} experts ({time.time() - t0:.0f} s)")
     q.qmoe_set_tuning("host_threads", 0)
-    layer.finalize()
+    layer.finalize(device_order_of=None if interchange_order else dd)
     return layer
 
 
@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--no-bf16", action="store_true", help="skip the uncompressed comparator")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--tune", action="append", default=[], help="key=value for qmoe_set_tuning")
+    ap.add_argument("--interchange-order", action="store_true",
+                    help="leave the codeword streams as encoded instead of renumbering them at load time")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -184,7 +186,7 @@ def main():
     dd = dev.DeviceDict(device=gpu)
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
-    layer = build_layer(w, dd, gpu, workers)
+    layer = build_layer(w, dd, gpu, workers, args.interchange_order)
     log(f"layer resident: {layer.compressed_bytes / 1e9:.3f} GB compressed, built in {time.time() - t0:.0f} s")
 
     x = torch.from_numpy(x_bits.view(np.int16).copy()).to(gpu)
@@ -228,7 +230,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_experts": w.n_experts, "d_model": w.d_model, "d_ff": w.d_ff,
                    "tokens": T, "experts_with_tokens": len(active), "routing": w.routing,
-                   "zero_fraction": "0.80-0.97 per row" if w.p0_spread else w.p0},
+                   "zero_fraction": "0.80-0.97 per row" if w.p0_spread else w.p0,
+                   "code_order": "interchange" if args.interchange_order else "device"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
                      "kernel_ms": dom[1], "algorithmic_bytes": dom[2]},

@@ -92,6 +92,27 @@ int qmoe_dict_max_nonzeros(const qmoe_dict *d);
 size_t qmoe_dict_device_bytes(void);
 
 /*
+ * The device numbering of the codewords ("device order"), for dictionaries whose
+ * entries hold at most three non-zeros.  The paper keeps its table in L2 and notes
+ * that look-ups are random accesses (Section 4.3.2); to hold the whole table in the
+ * 160 KB of LDS instead, this library renumbers the codewords so that the four sign
+ * combinations of the last two non-zeros of a run are four consecutive codes
+ * 4g..4g+3 sharing one table entry; runs without a complete group of four follow as
+ * single codes.  It is a bijection on the codes in use: stream length, bits per
+ * parameter and the set of runs are unchanged.
+ *   code_map [65536]   interchange code -> device code
+ *   table    [n_table] entry of group g at table[g] (both free signs positive), entry of
+ *                      single code 4*n_groups + i at table[n_groups + i]; each entry is
+ *                      byte 0 = 8 * run length, bytes 1..3 = one field per non-zero:
+ *                      (position << 3) | (weight as 2-bit signed integer << 1), 0 = unused
+ * Device code c < 4*n_groups decodes to table[c >> 2] with bit 2 of field 1 set if c & 1
+ * and bit 2 of field 2 set if c & 2 (which turns weight +1 into -1).
+ * code_map and table are NULL (n_table = 0) when the dictionary has no device order.
+ */
+qmoe_status qmoe_dict_device_order(const qmoe_dict *d, const uint16_t **code_map, const uint32_t **table,
+                                   int *n_groups, int *n_table);
+
+/*
  * Copy the device form of the table into dev_buf (device, >= qmoe_dict_device_bytes(),
  * 256-byte aligned, owned by the caller, must outlive every device call that uses d)
  * and bind it to d.  The copy is enqueued on `stream` from memory owned by d.
@@ -137,8 +158,20 @@ typedef struct qmoe_matrix {
     const uint16_t *scale_f16; /* [rows] IEEE binary16 scale s_r of each output row     */
     int32_t rows, cols;        /* cols even                                             */
     uint32_t n_codes;          /* = row_off[rows]; offsets beyond it are clamped        */
-    uint32_t reserved;         /* 0                                                     */
+    uint32_t code_order;       /* 0: interchange numbering (as encoded); 1: device
+                                  numbering (after qmoe_codes_to_device_order)          */
 } qmoe_matrix;
+
+/*
+ * Rewrite a codeword stream in device memory, in place, from the interchange numbering
+ * to the device numbering of d (see qmoe_dict_device_order): done once when a matrix is
+ * loaded, like any weight pre-packing; the product kernels then find the whole table in
+ * LDS.  Set code_order = 1 in the matrices that point into the rewritten stream.  Calling
+ * it twice on the same codes garbles them.
+ * Errors: INVALID_ARG, NO_DEVICE_DICT, LIMIT (the dictionary has no device order), HIP.
+ */
+qmoe_status qmoe_codes_to_device_order(const qmoe_dict *d, uint16_t *codes /*device*/, size_t n_codes,
+                                       void *stream);
 
 /*
  * Fused decode + product (the paper's kernel, extended by an inner loop over
@@ -196,13 +229,15 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * is outside [0, n_experts) gets a zero row.  workspace: device, 256-byte
  * aligned, >= qmoe_moe_layer_workspace(...) bytes, contents need not be
  * initialised.  Experts without tokens are never touched (their qmoe_matrix
- * may hold anything).  Enqueues a dispatch kernel and the two product kernels.
+ * may hold anything).  code_order: the numbering of every expert's stream (0 or 1, as
+ * in qmoe_matrix; the descriptors live in device memory, so the host is told).
+ * Enqueues a dispatch kernel and the two product kernels.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
- * n_tokens > 2^20, d_model or d_ff > 32768), HIP.
+ * n_tokens > 2^20, d_model or d_ff > 32768; code_order 1 without a device order), HIP.
  */
 qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*device*/,
-                                   const qmoe_matrix *wo /*device*/, int n_experts, int d_model,
-                                   int d_ff, const uint16_t *x_bf16 /*device*/,
+                                   const qmoe_matrix *wo /*device*/, int code_order, int n_experts,
+                                   int d_model, int d_ff, const uint16_t *x_bf16 /*device*/,
                                    const int32_t *expert_idx /*device*/, const float *gate /*device*/,
                                    int n_tokens, float *y /*device*/, void *workspace /*device*/,
                                    size_t workspace_bytes, void *stream);

@@ -29,7 +29,7 @@ class QmoeError(RuntimeError):
 
 class qmoe_matrix(Structure):
     _fields_ = [("codes", c_void_p), ("row_off", c_void_p), ("scale_f16", c_void_p),
-                ("rows", c_int32), ("cols", c_int32), ("n_codes", c_uint32), ("reserved", c_uint32)]
+                ("rows", c_int32), ("cols", c_int32), ("n_codes", c_uint32), ("code_order", c_uint32)]
 
 
 class qmoe_ws_layout(Structure):
@@ -41,7 +41,8 @@ EXPORTS = [
     "qmoe_dict_max_nonzeros", "qmoe_dict_device_bytes", "qmoe_dict_upload", "qmoe_dict_destroy",
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
-    "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy",
+    "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
+    "qmoe_codes_to_device_order",
 ]
 
 
@@ -68,7 +69,9 @@ def lib():
         L.qmoe_decode_dense.argtypes = [vp, POINTER(qmoe_matrix), vp, i, vp]
         L.qmoe_moe_layer_ws_layout.argtypes = [i, i, i, i, POINTER(qmoe_ws_layout)]
         L.qmoe_moe_layer_workspace.argtypes, L.qmoe_moe_layer_workspace.restype = [i, i, i, i], sz
-        L.qmoe_moe_layer_forward.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
+        L.qmoe_moe_layer_forward.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
+        L.qmoe_dict_device_order.argtypes = [vp, POINTER(vp), POINTER(vp), POINTER(i), POINTER(i)]
+        L.qmoe_codes_to_device_order.argtypes = [vp, vp, sz, vp]
         L.qmoe_moe_dispatch.argtypes = [vp, i, i, i, i, vp, sz, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
@@ -136,6 +139,25 @@ def qmoe_dict_device_bytes() -> int:
     return lib().qmoe_dict_device_bytes()
 
 
+def qmoe_dict_device_order(d: int):
+    """-> (code_map uint16 [65536], table uint32 [n_table], n_groups), or (None, None, 0)"""
+    m, t, g, n = c_void_p(), c_void_p(), c_int(), c_int()
+    _check(lib().qmoe_dict_device_order(d, byref(m), byref(t), byref(g), byref(n)), "qmoe_dict_device_order")
+    if not n.value:
+        return None, None, 0
+    cm = np.frombuffer((ctypes.c_uint16 * 65536).from_address(m.value), dtype=np.uint16).copy()
+    tb = np.frombuffer((c_uint32 * n.value).from_address(t.value), dtype=np.uint32).copy()
+    return cm, tb, g.value
+
+
+def qmoe_codes_to_device_order(d: int, codes_dev, stream=None) -> None:
+    """Renumber a device tensor of 16-bit codewords in place."""
+    if codes_dev.element_size() != 2:
+        raise ValueError("16-bit codewords expected")
+    _check(lib().qmoe_codes_to_device_order(d, _dev_ptr(codes_dev), codes_dev.numel(), _stream_ptr(stream)),
+           "qmoe_codes_to_device_order")
+
+
 def qmoe_dict_upload(d: int, dev_buf, stream=None) -> None:
     _check(lib().qmoe_dict_upload(d, _dev_ptr(dev_buf), dev_buf.numel() * dev_buf.element_size(),
                                   _stream_ptr(stream)), "qmoe_dict_upload")
@@ -199,8 +221,8 @@ def qmoe_moe_layer_workspace(n_experts: int, d_model: int, d_ff: int, n_tokens: 
     return lib().qmoe_moe_layer_workspace(n_experts, d_model, d_ff, n_tokens)
 
 
-def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, n_experts: int, d_model: int, d_ff: int, x_bf16,
-                           expert_idx, gate, y, workspace, stream=None) -> None:
+def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, code_order: int, n_experts: int, d_model: int, d_ff: int,
+                           x_bf16, expert_idx, gate, y, workspace, stream=None) -> None:
     """wi_dev / wo_dev: device byte tensors holding n_experts qmoe_matrix structs."""
     n_tokens = x_bf16.shape[0]
     if x_bf16.shape[1] != d_model or tuple(y.shape) != (n_tokens, d_model) or expert_idx.numel() != n_tokens:
@@ -208,7 +230,7 @@ def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, n_experts: int, d_model: int,
     need = ctypes.sizeof(qmoe_matrix) * n_experts
     if wi_dev.numel() * wi_dev.element_size() < need or wo_dev.numel() * wo_dev.element_size() < need:
         raise ValueError("expert descriptor arrays too small")
-    _check(lib().qmoe_moe_layer_forward(d, _dev_ptr(wi_dev), _dev_ptr(wo_dev), n_experts, d_model, d_ff,
+    _check(lib().qmoe_moe_layer_forward(d, _dev_ptr(wi_dev), _dev_ptr(wo_dev), code_order, n_experts, d_model, d_ff,
                                         _dev_ptr(x_bf16), _dev_ptr(expert_idx), _dev_ptr(gate), n_tokens,
                                         _dev_ptr(y), _dev_ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream_ptr(stream)),

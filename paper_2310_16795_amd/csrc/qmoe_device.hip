@@ -76,6 +76,9 @@ struct ProductArgs {
     int tb_max;
     int lds_dict_entries;     // leading run entries copied to LDS (0 = none)
     int *work_counter;        // device counter (zeroed by the dispatch kernel) for handing out items, or nullptr
+    const uint32_t *order_table;  // device-order table (n_order entries, the first n_groups are groups)
+    int n_groups, n_order;
+    int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -142,6 +145,29 @@ __device__ __forceinline__ void lds_load_tile(const float *xs, int col, float (&
     }
 }
 
+// Global-memory pointers with their address space spelled out: pointers that reach
+// a kernel through memory would otherwise be generic and cost flat loads.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using gp_u16 = const __attribute__((address_space(1))) uint16_t *;
+using gp_u32 = const __attribute__((address_space(1))) uint32_t *;
+using gp_u64 = const __attribute__((address_space(1))) unsigned long long *;
+using gp_u32x4 = const __attribute__((address_space(1))) u32x4 *;
+using lp_u32 = const __attribute__((address_space(3))) uint32_t *;
+using lp_u16 = const __attribute__((address_space(3))) uint16_t *;
+
+// Entry of a device-order code from the group/single table (see qmoe_internal.h):
+// codes below 4 * n_groups share table[code >> 2] and flip the signs of fields 1 and 2
+// with their two low bits; the rest are single entries.
+template <typename TablePtr>
+__device__ __forceinline__ uint32_t order_entry(TablePtr table, uint32_t code, uint32_t n_groups, uint32_t n_order)
+{
+    const bool grouped = code < 4u * n_groups;
+    const uint32_t u = grouped ? (code >> 2) : code - 3u * n_groups;
+    const uint32_t s = grouped ? (code & 3u) : 0u;
+    const uint32_t flips = (s * ((1u << 18) | (1u << 25))) & ((1u << 18) | (1u << 26));
+    return table[min(u, n_order - 1u)] | flips;
+}
+
 // Decode one step (one codeword per lane) and return this lane's run:
 // `len` values starting at column `start` (absolute, clamped to cols).
 struct Step {
@@ -158,7 +184,8 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     if (k < kend) {
         const uint32_t code = codes[k];
         if constexpr (RUN) {
-            s.e0 = a.run[code];
+            s.e0 = a.code_order ? order_entry((gp_u32)a.order_table, code, (uint32_t)a.n_groups, (uint32_t)a.n_order)
+                                : a.run[code];
         } else {
             const uint2 w = reinterpret_cast<const uint2 *>(a.words)[code];
             s.e0 = w.x; s.e1 = w.y;
@@ -172,17 +199,7 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     return s;
 }
 
-// Global-memory pointers with their address space spelled out: pointers that reach
-// a kernel through memory would otherwise be generic and cost flat loads.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-using gp_u16 = const __attribute__((address_space(1))) uint16_t *;
-using gp_u32 = const __attribute__((address_space(1))) uint32_t *;
-using gp_u64 = const __attribute__((address_space(1))) unsigned long long *;
-using gp_u32x4 = const __attribute__((address_space(1))) u32x4 *;
-using lp_u32 = const __attribute__((address_space(3))) uint32_t *;
-using lp_u16 = const __attribute__((address_space(3))) uint16_t *;
-
-enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2 };
+enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2, kDictOrder = 3 };
 
 struct Entry {
     uint32_t e0, e1;  // run entry (e0), or the two interchange words (e0, e1)
@@ -202,6 +219,8 @@ __device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t cod
         const uint32_t from_lds = lds_run[in_lds ? code : 0u];
         const uint32_t from_l2 = ((gp_u32)a.run)[in_lds ? 0u : code];
         e.e0 = in_lds ? from_lds : from_l2;
+    } else if constexpr (DICT == kDictOrder) {
+        e.e0 = order_entry(lds_run, code, (uint32_t)a.n_groups, (uint32_t)a.n_order);  // whole table in LDS
     } else {
         const unsigned long long w = ((gp_u64)a.words)[code];
         e.e0 = (uint32_t)w; e.e1 = (uint32_t)(w >> 32);
@@ -533,6 +552,8 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
 
     if constexpr (DICT == kDictRunLds) {
         for (int i = threadIdx.x; i < a.lds_dict_entries; i += blockDim.x) lds_run_w[i] = ((gp_u32)a.run)[i];
+    } else if constexpr (DICT == kDictOrder) {
+        for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) lds_run_w[i] = ((gp_u32)a.order_table)[i];
     }
 
     gp_u16 xg = (gp_u16)a.x;
@@ -926,6 +947,15 @@ __global__ __launch_bounds__(256) void k_stream_copy(const uint4 *__restrict__ s
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// ---------------------------------------------------------------- stream renumbering
+
+// codes[i] = map[codes[i]], in place (interchange numbering -> device numbering)
+__global__ __launch_bounds__(256) void k_renumber(uint16_t *codes, size_t n, const uint16_t *__restrict__ map)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) codes[i] = map[codes[i]];
+}
+
 // ---------------------------------------------------------------- launch helpers
 
 struct DeviceInfo {
@@ -961,7 +991,8 @@ struct ProductPlan {
 
 // Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
 // matrices with the lane-per-row kernel (compressed path).
-qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p)
+qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p,
+                         int n_order = 0)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
@@ -978,10 +1009,14 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     // them (one copy per workgroup): table reads that go to L2 cost a cycle per lane.
     const double codes_per_row = std::max(1.0, cols / 22.0);
     const double est_codes = (double)max_passes_hint * rows * codes_per_row;
-    const bool lds_table = run_table && tu.lds_dict_entries >= 0 && max_lds >= 128 * 1024 &&
+    const bool lds_table = n_order == 0 && run_table && tu.lds_dict_entries >= 0 && max_lds >= 128 * 1024 &&
                            (tu.lds_dict_entries > 0 || est_codes / di.cus >= 1.0e6);
     int tb = kMaxTokenTile;
-    if (lds_table) {
+    if (n_order > 0) {
+        // device-order streams: the whole table goes to LDS, the tile takes what is left
+        if (xs_bytes(1) + fixed + 4 * (size_t)n_order + 16384 > max_lds) return QMOE_E_LIMIT;
+        while (tb > 4 && xs_bytes(tb) + fixed + 4 * (size_t)n_order + 16384 > max_lds) tb >>= 1;
+    } else if (lds_table) {
         while (tb > 4 && xs_bytes(tb) > 36 * 1024) tb >>= 1;
     } else {
         while (tb > 4 && xs_bytes(tb) + fixed > max_lds / 2) tb >>= 1;
@@ -991,7 +1026,7 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
         while (tb * 2 <= tu.token_tile && tb < kMaxTokenTile) tb <<= 1;
     }
     while (tb > 4 && xs_bytes(tb) + fixed > max_lds) tb >>= 1;
-    int lds_dict = 0;
+    int lds_dict = n_order;
     if (lds_table) {
         const size_t room = (max_lds - xs_bytes(tb) - fixed) / 4;
         lds_dict = (int)std::min<size_t>(room, kTableEntries);
@@ -1030,7 +1065,7 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     const long long all_lanes = (long long)best_b * best_t;
     p->rows_per_item = (int)std::min<long long>(rows, (long long)best_t * (rows / all_lanes + 1));
     const size_t scale_bytes = ((size_t)p->rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
-    if (lds_dict > 0) {
+    if (lds_dict > 0 && n_order == 0) {
         // the row scales take their share of LDS from the table
         const size_t room = max_lds - xs_bytes(tb) - fixed - scale_bytes;
         lds_dict = (int)std::min<size_t>((size_t)lds_dict, room / 4);
@@ -1093,6 +1128,8 @@ qmoe_status launch_product_as(const ProductArgs &a, const ProductPlan &p, hipStr
 
 qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
 {
+    if (a.code_order)
+        return a.epilogue ? launch_product_as<kDictOrder, 1>(a, p, s) : launch_product_as<kDictOrder, 0>(a, p, s);
     if (!run) return a.epilogue ? launch_product_as<kDictWords, 1>(a, p, s) : launch_product_as<kDictWords, 0>(a, p, s);
     if (p.lds_dict_entries > 0)
         return a.epilogue ? launch_product_as<kDictRunLds, 1>(a, p, s) : launch_product_as<kDictRunLds, 0>(a, p, s);
@@ -1109,11 +1146,22 @@ qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
     return QMOE_OK;
 }
 
-void fill_tables(const qmoe_dict *d, ProductArgs *a)
+void fill_tables(const qmoe_dict *d, ProductArgs *a, int code_order)
 {
     const unsigned char *base = static_cast<const unsigned char *>(d->dev);
     a->run = reinterpret_cast<const uint32_t *>(base + kDevRunOffset);
     a->words = reinterpret_cast<const uint32_t *>(base + kDevWordsOffset);
+    a->order_table = reinterpret_cast<const uint32_t *>(base + kDevOrderTableOffset);
+    a->n_groups = d->n_groups;
+    a->n_order = (int)d->order_table.size();
+    a->code_order = code_order;
+}
+
+qmoe_status check_code_order(const qmoe_dict *d, int code_order)
+{
+    if (code_order != 0 && code_order != 1) return QMOE_E_INVALID_ARG;
+    if (code_order == 1 && d->order_table.empty()) return QMOE_E_LIMIT;
+    return QMOE_OK;
 }
 
 qmoe_status layer_limits(int n_experts, int d_model, int d_ff, int n_tokens)
@@ -1183,6 +1231,12 @@ qmoe_status qmoe_dict_upload(qmoe_dict *d, void *dev_buf, size_t dev_bytes, void
                                 hipMemcpyHostToDevice, s));
     QMOE_HIP_TRY(hipMemcpyAsync(b + kDevWordsOffset, d->words.data(), 2 * sizeof(uint32_t) * kTableEntries,
                                 hipMemcpyHostToDevice, s));
+    if (!d->order_table.empty()) {
+        QMOE_HIP_TRY(hipMemcpyAsync(b + kDevOrderTableOffset, d->order_table.data(),
+                                    sizeof(uint32_t) * d->order_table.size(), hipMemcpyHostToDevice, s));
+        QMOE_HIP_TRY(hipMemcpyAsync(b + kDevOrderMapOffset, d->order_map.data(), sizeof(uint16_t) * kTableEntries,
+                                    hipMemcpyHostToDevice, s));
+    }
     d->dev = dev_buf;
     return QMOE_OK;
 }
@@ -1193,9 +1247,13 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     qmoe_status st = check_matrix_args(d, W);
     if (st != QMOE_OK) return st;
     if (!x_bf16 || !y || batch < 1) return QMOE_E_INVALID_ARG;
+    const int code_order = (int)W->code_order;
+    if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     ProductPlan p;
-    if ((st = plan_product(W->rows, W->cols, run, ((long long)batch + 7) / 8 + 1, &p)) != QMOE_OK) return st;
+    if ((st = plan_product(W->rows, W->cols, run, ((long long)batch + 7) / 8 + 1, &p,
+                           code_order ? (int)d->order_table.size() : 0)) != QMOE_OK)
+        return st;
     // grid sized for the real number of tiles
     {
         const long long items = (long long)((batch + p.tb_max - 1) / p.tb_max) * p.blocks_per_pass;
@@ -1204,7 +1262,7 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     ProductArgs a{};
     a.mats = nullptr;
     a.single = *W;
-    fill_tables(d, &a);
+    fill_tables(d, &a, code_order);
     a.items = nullptr;
     a.n_items_dev = nullptr;
     a.max_items = 0;
@@ -1232,10 +1290,13 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W, int8_t *
     qmoe_status st = check_matrix_args(d, W);
     if (st != QMOE_OK) return st;
     if (!out || (path != 0 && path != 1)) return QMOE_E_INVALID_ARG;
+    const int code_order = (int)W->code_order;
+    if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
+    if (code_order && path == 1) return QMOE_E_INVALID_ARG;  // device-order codes do not index the interchange table
     const bool run = path == 0 && d->max_nonzeros <= kRunMaxNonzeros;
     ProductArgs a{};
     a.single = *W;
-    fill_tables(d, &a);
+    fill_tables(d, &a, code_order);
     a.rows = W->rows;
     a.cols = W->cols;
     a.lds_dict_entries = 0;
@@ -1291,7 +1352,7 @@ qmoe_status qmoe_moe_dispatch(const int32_t *expert_idx, int n_tokens, int n_exp
 }
 
 qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
-                                   int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
+                                   int code_order, int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
                                    const int32_t *expert_idx, const float *gate, int n_tokens, float *y,
                                    void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -1302,10 +1363,12 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
+    if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
+    const int n_order = code_order ? (int)d->order_table.size() : 0;
     ProductPlan pwi, pwo;
-    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo)) != QMOE_OK) return st;
+    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order)) != QMOE_OK) return st;
+    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order)) != QMOE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
     const int phases = tuning().phases > 0 ? tuning().phases : 7;
@@ -1315,7 +1378,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
             return st;
 
     ProductArgs a{};
-    fill_tables(d, &a);
+    fill_tables(d, &a, code_order);
     a.n_experts = n_experts;
     a.max_items = n_tokens;
     a.perm = lp.perm;
@@ -1427,6 +1490,22 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
         hipLaunchKernelGGL(k_dense_bf16, dim3(pwo.grid), dim3(pwo.threads), pwo.smem, s, a);
         QMOE_HIP_TRY(hipGetLastError());
     }
+    return QMOE_OK;
+}
+
+qmoe_status qmoe_codes_to_device_order(const qmoe_dict *d, uint16_t *codes, size_t n_codes, void *stream)
+{
+    if (!d || !codes || n_codes == 0) return QMOE_E_INVALID_ARG;
+    if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
+    if (d->order_table.empty()) return QMOE_E_LIMIT;
+    DeviceInfo di;
+    const qmoe_status st = device_info(&di);
+    if (st != QMOE_OK) return st;
+    const int grid = (int)std::min<size_t>((n_codes + 255) / 256, (size_t)di.cus * 32);
+    const uint16_t *map = reinterpret_cast<const uint16_t *>(static_cast<const unsigned char *>(d->dev) +
+                                                             kDevOrderMapOffset);
+    hipLaunchKernelGGL(k_renumber, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), codes, n_codes, map);
+    QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }
 

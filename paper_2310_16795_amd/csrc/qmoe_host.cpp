@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <map>
 #include <queue>
 #include <thread>
 
@@ -49,6 +50,69 @@ void pack_words(uint64_t syms, int npairs, uint32_t *w)
     w[1] = (uint32_t)npairs | (uint32_t)(((syms >> 28) & ((1ull << 28) - 1)) << 4);
 }
 
+// Device numbering of the codewords: group the sign variants of the last two non-zeros
+// of each run under one table entry (see qmoe_internal.h).
+void build_device_order(qmoe_dict *d)
+{
+    d->order_table.clear();
+    d->order_map.clear();
+    d->n_groups = 0;
+    if (d->max_nonzeros > kRunMaxNonzeros) return;
+    const int n = d->n_entries;
+    struct Nz { int pos; bool neg; };
+    // key: run length, positions, and the sign of the first non-zero when there are three
+    std::map<std::vector<int>, std::vector<int>> groups;  // key -> member code by free-sign bits, -1 = missing
+    std::vector<std::vector<Nz>> nz((size_t)n);
+    for (int k = 0; k < n; k++) {
+        const uint32_t e = d->run[k];
+        for (int j = 0; j < kRunMaxNonzeros; j++) {
+            const uint32_t f = (e >> (8 + 8 * j)) & 0xFFu;
+            if (f) nz[k].push_back(Nz{(int)(f >> 3), ((f >> 1) & 3u) == 3u});
+        }
+        const size_t c = nz[k].size();
+        if (c < 2) continue;
+        std::vector<int> key{(int)(e & 0xFFu)};
+        for (const Nz &z : nz[k]) key.push_back(z.pos);
+        if (c == 3) key.push_back(nz[k][0].neg ? 1 : 0);
+        const int bits = (nz[k][c - 2].neg ? 1 : 0) | (nz[k][c - 1].neg ? 2 : 0);
+        std::vector<int> &m = groups[key];
+        if (m.empty()) m.assign(4, -1);
+        if (m[bits] < 0) m[bits] = k;  // duplicates in a hand-made table stay single entries
+    }
+    std::vector<uint32_t> table;
+    std::vector<int> device_of((size_t)n, -1);
+    for (const auto &kv : groups) {
+        const std::vector<int> &m = kv.second;
+        if (m[0] < 0 || m[1] < 0 || m[2] < 0 || m[3] < 0) continue;
+        const int g = (int)table.size();
+        const int k = m[0];  // both free signs positive
+        const size_t c = nz[k].size();
+        uint32_t e = d->run[k] & 0xFFu;
+        if (c == 3) e |= (((uint32_t)nz[k][0].pos << 3) | ((nz[k][0].neg ? 3u : 1u) << 1)) << 8;
+        e |= (((uint32_t)nz[k][c - 2].pos << 3) | (1u << 1)) << 16;
+        e |= (((uint32_t)nz[k][c - 1].pos << 3) | (1u << 1)) << 24;
+        table.push_back(e);
+        for (int b = 0; b < 4; b++) device_of[m[b]] = 4 * g + b;
+    }
+    const int n_groups = (int)table.size();
+    int next = 4 * n_groups;
+    for (int k = 0; k < n; k++) {
+        if (device_of[k] >= 0) continue;
+        device_of[k] = next++;
+        table.push_back(d->run[k]);
+    }
+    int absent = -1;  // codes that name no entry all map to one empty single entry
+    if (n < kTableEntries) {
+        absent = next++;
+        table.push_back(0u);
+    }
+    if ((int)table.size() > kMaxOrderTable || next > kTableEntries) return;
+    d->order_map.assign(kTableEntries, (uint16_t)(absent >= 0 ? absent : 0));
+    for (int k = 0; k < n; k++) d->order_map[k] = (uint16_t)device_of[k];
+    d->order_table = std::move(table);
+    d->n_groups = n_groups;
+}
+
 // Derive everything the codec and the kernels need from the interchange words.
 qmoe_status finish_dict(qmoe_dict *d)
 {
@@ -79,6 +143,7 @@ qmoe_status finish_dict(qmoe_dict *d)
         d->max_nonzeros = std::max(d->max_nonzeros, nnz);
         d->run[k] = run;
     }
+    build_device_order(d);
     // trie: node 0 is the root; an entry's node is reached by its pairs in order
     d->child.assign(9, -1);
     d->code.assign(1, -1);
@@ -254,6 +319,17 @@ qmoe_status qmoe_dict_words(const qmoe_dict *d, const uint32_t **words, int *n_e
 int qmoe_dict_max_nonzeros(const qmoe_dict *d) { return d ? d->max_nonzeros : QMOE_E_INVALID_ARG; }
 
 size_t qmoe_dict_device_bytes(void) { return kDevDictBytes; }
+
+qmoe_status qmoe_dict_device_order(const qmoe_dict *d, const uint16_t **code_map, const uint32_t **table,
+                                   int *n_groups, int *n_table)
+{
+    if (!d || !code_map || !table || !n_groups || !n_table) return QMOE_E_INVALID_ARG;
+    *code_map = d->order_map.empty() ? nullptr : d->order_map.data();
+    *table = d->order_table.empty() ? nullptr : d->order_table.data();
+    *n_groups = d->n_groups;
+    *n_table = (int)d->order_table.size();
+    return QMOE_OK;
+}
 
 void qmoe_dict_destroy(qmoe_dict *d) { delete d; }
 

@@ -27,11 +27,26 @@ constexpr int kTableEntries = 65536;  // device tables always span every uint16 
 // to add -- unused fields land on a zero.
 constexpr int kRunMaxNonzeros = 3;
 
-// Device blob written by qmoe_dict_upload: run entries first, then the
-// interchange-layout words, both for all 65536 codewords (absent entries are 0).
+// Device numbering of the codewords ("device order").  The table is small enough to
+// sit in LDS whole when sign variants share an entry: codewords are renumbered so that
+// four consecutive device codes 4g..4g+3 are the four sign combinations of the last two
+// non-zeros of one run (its first non-zero, if it has three, keeps a fixed sign), and
+// their common entry is table[g] with those two signs positive; the two low code bits
+// then flip the sign bits of fields 1 and 2.  Entries that have no complete group of
+// four (at most one non-zero, or variants missing from the dictionary) follow as
+// "single" codes, device code = 4 * n_groups + i, entry table[n_groups + i].  A stream is
+// rewritten once, in place, when it is loaded; its length and the set of runs it can
+// express are unchanged.
+constexpr int kMaxOrderTable = 20480;  // entries (80 KiB); larger tables keep the interchange numbering
+
+// Device blob written by qmoe_dict_upload: run entries, then the interchange-layout
+// words, both for all 65536 codewords (absent entries are 0), then the device-order
+// table (kMaxOrderTable entries) and the interchange -> device code map (65536 x u16).
 constexpr size_t kDevRunOffset = 0;
 constexpr size_t kDevWordsOffset = sizeof(uint32_t) * kTableEntries;
-constexpr size_t kDevDictBytes = kDevWordsOffset + 2 * sizeof(uint32_t) * kTableEntries;
+constexpr size_t kDevOrderTableOffset = kDevWordsOffset + 2 * sizeof(uint32_t) * kTableEntries;
+constexpr size_t kDevOrderMapOffset = kDevOrderTableOffset + sizeof(uint32_t) * kMaxOrderTable;
+constexpr size_t kDevDictBytes = kDevOrderMapOffset + sizeof(uint16_t) * kTableEntries;
 
 struct Tuning {
     int threads = 0;
@@ -52,6 +67,10 @@ struct qmoe_dict {
     int max_nonzeros = 0;
     std::vector<uint32_t> words;  // [kTableEntries][2], interchange layout, zero beyond n_entries
     std::vector<uint32_t> run;    // [kTableEntries], valid when max_nonzeros <= kRunMaxNonzeros
+    // device order (empty when the dictionary does not qualify)
+    std::vector<uint32_t> order_table;  // n_groups group entries, then the single entries
+    std::vector<uint16_t> order_map;    // [kTableEntries] interchange code -> device code
+    int n_groups = 0;
     // trie over the entries: child[node * 9 + pair] (-1 = none), code[node] (-1 = no entry ends here)
     std::vector<int32_t> child;
     std::vector<int32_t> code;

@@ -33,13 +33,17 @@ class DeviceMatrix:
     """One compressed matrix in device memory and its qmoe_matrix descriptor."""
 
     def __init__(self, codes: np.ndarray, row_off: np.ndarray, scale_f16: np.ndarray, rows: int, cols: int,
-                 device="cuda:0"):
+                 device="cuda:0", device_order_of: "DeviceDict | None" = None):
         assert row_off.shape == (rows + 1,) and scale_f16.shape == (rows,)
         self.codes = torch.from_numpy(_pad_to(codes.view(np.int16), 8).copy()).to(device)
         self.row_off = torch.from_numpy(row_off.astype(np.uint32).view(np.int32).copy()).to(device)
         self.scale = torch.from_numpy(scale_f16.view(np.int16).copy()).to(device)
+        order = 0
+        if device_order_of is not None:  # renumber the stream for this dictionary, once
+            B.qmoe_codes_to_device_order(device_order_of.handle, self.codes)
+            order = 1
         self.desc = B.qmoe_matrix(self.codes.data_ptr(), self.row_off.data_ptr(), self.scale.data_ptr(), rows,
-                                  cols, int(codes.size), 0)
+                                  cols, int(codes.size), order)
 
 
 class DeviceLayer:
@@ -58,7 +62,9 @@ class DeviceLayer:
         self._host[which][e] = (codes, row_off.astype(np.uint32), scale_f16)
         self.n_codes[which][e] = codes.size
 
-    def finalize(self):
+    def finalize(self, device_order_of: "DeviceDict | None" = None):
+        """Upload everything; with device_order_of, renumber the streams for that dictionary."""
+        self.code_order = 0 if device_order_of is None else 1
         self.bufs, self.desc_dev, self.desc_host = {}, {}, {}
         for which in ("wi", "wo"):
             rows = self.d_ff if which == "wi" else self.d_model
@@ -79,6 +85,8 @@ class DeviceLayer:
                 row_off[e] = p[1]
                 scale[e] = p[2]
             d_codes = torch.from_numpy(codes.view(np.int16)).to(self.device)
+            if device_order_of is not None:
+                B.qmoe_codes_to_device_order(device_order_of.handle, d_codes)
             d_row = torch.from_numpy(row_off.view(np.int32)).to(self.device)
             d_scale = torch.from_numpy(scale.view(np.int16)).to(self.device)
             descs = (B.qmoe_matrix * self.n_experts)()
@@ -87,7 +95,7 @@ class DeviceLayer:
                     continue  # stays all-zero: never touched unless a token is routed there
                 descs[e] = B.qmoe_matrix(d_codes.data_ptr() + 2 * code_off[e],
                                          d_row.data_ptr() + 4 * e * (rows + 1),
-                                         d_scale.data_ptr() + 2 * e * rows, rows, cols, int(p[0].size), 0)
+                                         d_scale.data_ptr() + 2 * e * rows, rows, cols, int(p[0].size), self.code_order)
             raw = np.frombuffer(bytes(descs), dtype=np.uint8).copy()
             self.bufs[which] = (d_codes, d_row, d_scale)
             self.desc_host[which] = descs
@@ -102,7 +110,7 @@ class DeviceLayer:
 
     def forward(self, dd: DeviceDict, x_bf16: torch.Tensor, expert_idx: torch.Tensor, y: torch.Tensor,
                 workspace: torch.Tensor, gate: torch.Tensor | None = None, stream=None):
-        B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.n_experts,
+        B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.code_order, self.n_experts,
                                  self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, workspace, stream)
 
 

@@ -37,9 +37,10 @@ def ddict(gpu, oracle_dict):
     dd.close()
 
 
-def _upload(oracle_dict, tern, scale, gpu):
+def _upload(oracle_dict, tern, scale, gpu, order_of=None):
+    """order_of: renumber the stream to the device order of that dictionary (None: as encoded)."""
     codes, row_off = oracle.encode(oracle_dict, tern)
-    return dev.DeviceMatrix(codes, row_off, scale, *tern.shape, device=gpu)
+    return dev.DeviceMatrix(codes, row_off, scale, *tern.shape, device=gpu, device_order_of=order_of)
 
 
 def _to_dev16(bits, gpu):
@@ -69,11 +70,12 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("rows,cols,p0,seed", SHAPES)
-@pytest.mark.parametrize("path", [0, 1])
-def test_decode_dense_bit_exact(gpu, ddict, oracle_dict, rows, cols, p0, seed, path):
+@pytest.mark.parametrize("path,order", [(0, 0), (1, 0), (0, 1)])
+def test_decode_dense_bit_exact(gpu, ddict, oracle_dict, rows, cols, p0, seed, path, order):
+    """path 0/1: run-entry table / interchange words; order 1: stream renumbered to the device order."""
     tern = synth.ternary(seed, rows, cols, p0)
     scale = synth.uniform_f16(seed + 1000, (rows,), 0.01, 0.1)
-    M = _upload(oracle_dict, tern, scale, gpu)
+    M = _upload(oracle_dict, tern, scale, gpu, ddict if order else None)
     out = torch.full((rows, cols), 77, dtype=torch.int8, device=gpu)
     q.qmoe_decode_dense(ddict.handle, M.desc, out, path)
     torch.cuda.synchronize()
@@ -82,11 +84,12 @@ def test_decode_dense_bit_exact(gpu, ddict, oracle_dict, rows, cols, p0, seed, p
 
 @pytest.mark.parametrize("rows,cols,p0,seed", SHAPES)
 @pytest.mark.parametrize("batch", [1, 3, 8, 19])
-def test_decode_matvec_against_oracle(gpu, ddict, oracle_dict, rows, cols, p0, seed, batch):
+@pytest.mark.parametrize("order", [0, 1])
+def test_decode_matvec_against_oracle(gpu, ddict, oracle_dict, rows, cols, p0, seed, batch, order):
     tern = synth.ternary(seed, rows, cols, p0)
     scale = synth.uniform_f16(seed + 1000, (rows,), 0.01, 0.1)
     x = synth.normal_bf16(seed + 2000, (batch, cols))
-    M = _upload(oracle_dict, tern, scale, gpu)
+    M = _upload(oracle_dict, tern, scale, gpu, ddict if order else None)
     y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
     q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
     torch.cuda.synchronize()
@@ -101,7 +104,7 @@ def test_matvec_integer_inputs_are_exact(gpu, ddict, oracle_dict):
     one = np.full(rows, np.float16(1.0).view(np.uint16), dtype=np.uint16)
     xi = np.random.default_rng(1).integers(-4, 5, (5, cols)).astype(np.float32)
     x = torch.from_numpy(xi).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
-    M = _upload(oracle_dict, tern, one, gpu)
+    M = _upload(oracle_dict, tern, one, gpu, ddict)
     y = torch.empty((5, rows), dtype=torch.float32, device=gpu)
     q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
     torch.cuda.synchronize()
@@ -173,7 +176,7 @@ def test_dispatch_bit_exact(gpu, E, T, seed):
         assert np.all(covered == 1)
 
 
-def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None):
+def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None):
     layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu)
     for e in (range(w.n_experts) if experts is None else experts):
         for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_scale(e)), ("wo", w.wo_ternary(e), w.wo_scale(e))):
@@ -182,7 +185,7 @@ def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=N
             else:
                 codes, row_off = q.qmoe_encode_host(lib_dict, tern)
             layer.set_expert(e, which, codes, row_off, scale)
-    return layer.finalize()
+    return layer.finalize(device_order_of=order_of)
 
 
 def _run_layer(layer, ddict, x_bits, idx, gpu, gate=None):
@@ -210,12 +213,14 @@ def _check_layer(w, idx, x_bits, y_gpu, wsout, tokens, gate=None):
     assert flips <= max(2, total * 2e-3), f"{flips} of {total} hidden values rounded differently"
 
 
-def test_small_layer_every_token(gpu, ddict, oracle_dict):
-    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=12, d_model=96, d_ff=200, n_tokens=70)
+@pytest.mark.parametrize("d_model,d_ff,order", [(96, 200, 0), (96, 200, 1), (260, 300, 1), (450, 228, 0)])
+def test_small_layer_every_token(gpu, ddict, oracle_dict, d_model, d_ff, order):
+    """Widths on both sides of 224 (the row length from which eight codewords hold at most one row end)."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=12, d_model=d_model, d_ff=d_ff, n_tokens=70)
     idx, x = w.expert_idx(), w.tokens()
     idx[5:40] = 3      # one expert with many tokens (several tiles)
     idx[idx == 7] = 8  # at least one expert without tokens
-    layer = _build_layer(w, oracle_dict, gpu)
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict if order else None)
     gate = np.random.default_rng(7).uniform(0.2, 1.0, idx.size)
     y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
     _check_layer(w, idx, x, y, wsout, list(range(idx.size)), gate)
@@ -247,7 +252,7 @@ def test_switch_base128_layer_full_size(gpu, ddict, oracle_dict):
     """128 experts of 3072x768 / 768x3072, 128 tokens routed uniformly: every token checked."""
     w = synth.WORKLOADS["switch_base128"]
     idx, x = w.expert_idx(), w.tokens()
-    layer = _build_layer(w, oracle_dict, gpu, experts=sorted(set(idx.tolist())))
+    layer = _build_layer(w, oracle_dict, gpu, experts=sorted(set(idx.tolist())), order_of=ddict)
     y, wsout = _run_layer(layer, ddict, x, idx, gpu)
     assert np.isfinite(y).all()
     _check_layer(w, idx, x, y, wsout, list(range(idx.size)))
@@ -258,8 +263,21 @@ def test_switch_large128_layer_full_size(gpu, ddict, oracle_dict):
     w = synth.WORKLOADS["switch_large128"]
     idx, x = w.expert_idx(), w.tokens()
     lib_dict = q.qmoe_dict_create()
-    layer = _build_layer(w, oracle_dict, gpu, encoder="library", lib_dict=lib_dict)
+    layer = _build_layer(w, oracle_dict, gpu, encoder="library", lib_dict=lib_dict, order_of=ddict)
     q.qmoe_dict_destroy(lib_dict)
     y, wsout = _run_layer(layer, ddict, x, idx, gpu)
     assert np.isfinite(y).all()
     _check_layer(w, idx, x, y, wsout, list(range(0, idx.size, 8)))
+
+
+def test_switch_large128_interchange_numbering(gpu, ddict, oracle_dict):
+    """The same layer with the streams left as encoded (table head in LDS, the rest from L2)."""
+    w = synth.WORKLOADS["switch_large128"].scaled(n_experts=16, n_tokens=64)
+    idx, x = w.expert_idx(), w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu)
+    q.qmoe_set_tuning("lds_dict_entries", 20000)  # force the LDS head even for this small layer
+    try:
+        y, wsout = _run_layer(layer, ddict, x, idx, gpu)
+    finally:
+        q.qmoe_set_tuning("lds_dict_entries", 0)
+    _check_layer(w, idx, x, y, wsout, list(range(0, idx.size, 2)))

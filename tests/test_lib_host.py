@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
     assert ctypes.sizeof(q.qmoe_matrix) == 40
     assert L.qmoe_strerror(0) == b"ok" and L.qmoe_strerror(-4) == b"corrupt codeword stream"
-    assert q.qmoe_dict_device_bytes() == 65536 * 4 + 65536 * 8
+    assert q.qmoe_dict_device_bytes() == 65536 * 4 + 65536 * 8 + 20480 * 4 + 65536 * 2
 
 
 def test_dictionary_equals_oracle_table(lib_dict, oracle_dict):
@@ -192,8 +192,67 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     W = q.qmoe_matrix(256, 256, 256, 4, 8, 0, 0)
     assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -9     # not uploaded
     assert L.qmoe_decode_dense(lib_dict, ctypes.byref(W), 256, 0, None) == -9
-    assert L.qmoe_moe_layer_forward(lib_dict, 256, 256, 4, 8, 16, 256, 256, None, 4, 256, None, 0, None) == -9
+    assert L.qmoe_moe_layer_forward(lib_dict, 256, 256, 0, 4, 8, 16, 256, 256, None, 4, 256, None, 0, None) == -9
+    assert L.qmoe_codes_to_device_order(lib_dict, 256, 10, None) == -9
+    assert L.qmoe_codes_to_device_order(lib_dict, None, 10, None) == -1
     assert L.qmoe_dict_upload(lib_dict, None, 0, None) == -1
     assert L.qmoe_dict_upload(lib_dict, 256, 10, None) == -2
     assert L.qmoe_bf16_layer_forward(256, 256, 4, 12, 16, 256, 256, None, 4, 256, 256, 1 << 30, None) == -1
     assert L.qmoe_moe_dispatch(256, 4, 4, 8, 16, 256, 16, None) == -5                   # workspace too small
+
+
+def _decode_device_code(code, table, n_groups):
+    """Symbols of a device-order code, decoded the way include/qmoe.h describes it."""
+    if code < 4 * n_groups:
+        e = int(table[code >> 2])
+        if code & 1:
+            e |= 1 << 18
+        if code & 2:
+            e |= 1 << 26
+    else:
+        e = int(table[n_groups + code - 4 * n_groups])
+    length = (e & 0xFF) >> 3
+    syms = [0] * length
+    for j in range(3):
+        f = (e >> (8 + 8 * j)) & 0xFF
+        if f:
+            assert f & 1 == 0
+            w = (f >> 1) & 3
+            assert w in (1, 3)
+            assert syms[f >> 3] == 0
+            syms[f >> 3] = 2 if w == 1 else 1
+    return tuple(syms)
+
+
+def test_device_order_is_a_renumbering_of_the_same_runs(lib_dict, oracle_dict):
+    code_map, table, n_groups = q.qmoe_dict_device_order(lib_dict)
+    assert code_map is not None and table.size <= 20480 and 4 * n_groups + (table.size - n_groups) <= 65536
+    assert np.unique(code_map).size == 65536  # a bijection on the codes in use
+    seqs = oracle_dict.sequences()
+    for k in range(0, 65536, 7):
+        assert _decode_device_code(int(code_map[k]), table, n_groups) == seqs[k]
+    for k in list(range(40)) + [65535, 65534, 57401, 57402]:
+        assert _decode_device_code(int(code_map[k]), table, n_groups) == seqs[k]
+    # groups really are the four sign variants of the last two non-zeros
+    inv = np.argsort(code_map)
+    for g in (0, 1, n_groups // 2, n_groups - 1):
+        variants = [seqs[int(inv[4 * g + b])] for b in range(4)]
+        assert len({tuple(v != 0 for v in s) for s in variants}) == 1  # same positions
+        assert len(set(variants)) == 4
+
+
+def test_device_order_of_small_and_dense_dictionaries():
+    d = q.qmoe_dict_create(0.5, 3, 500)   # entries with up to 6 non-zeros -> no device order
+    assert q.qmoe_dict_max_nonzeros(d) > 3 and q.qmoe_dict_device_order(d)[0] is None
+    q.qmoe_dict_destroy(d)
+    d = q.qmoe_dict_create(0.95, 14, 3000)
+    od = oracle.Dictionary(p0=0.95, max_pairs=14, n_entries=3000)
+    assert q.qmoe_dict_max_nonzeros(d) <= 3
+    code_map, table, n_groups = q.qmoe_dict_device_order(d)
+    seqs = od.sequences()
+    for k in range(3000):
+        assert _decode_device_code(int(code_map[k]), table, n_groups) == seqs[k]
+    # codes that name no entry all land on one empty entry
+    assert len(set(code_map[3000:].tolist())) == 1
+    assert _decode_device_code(int(code_map[3000]), table, n_groups) == ()
+    q.qmoe_dict_destroy(d)
