@@ -830,29 +830,32 @@ struct DenseArgs {
     const float *gate;
     int epilogue;
     int rows, cols, rows_per_item, blocks_per_pass, tb_max;
+    int *work_counter;  // zeroed by the dispatch kernel
 };
 
+// One wavefront per row; a lane takes four consecutive columns at a time (8 bytes of
+// weights, coalesced to 512 bytes per wavefront) and the matching activations from
+// token-major fp32 planes in LDS (16 bytes per lane, consecutive lanes: conflict-free).
 template <int TBI>
 __device__ __forceinline__ void dense_rows(const DenseArgs &a, const uint16_t *W, int ntok, int slot0,
-                                           int r0, int r1, const float *xs, const int *tok_ids)
+                                           int r0, int r1, const float *xs, int plane, const int *tok_ids)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int nq = a.cols / 4;
     for (int r = r0 + wave; r < r1; r += nwaves) {
-        const uint4 *wrow = reinterpret_cast<const uint4 *>(W + (size_t)r * a.cols);
+        const uint2 *wrow = reinterpret_cast<const uint2 *>(W + (size_t)r * a.cols);
         float acc[TBI];
 #pragma unroll
         for (int t = 0; t < TBI; t++) acc[t] = 0.0f;
-        for (int c8 = lane; c8 < a.cols / 8; c8 += 64) {
-            const uint4 q = wrow[c8];
-            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll 4
+        for (int c4 = lane; c4 < nq; c4 += 64) {
+            const uint2 q = wrow[c4];
+            const float w0 = __uint_as_float(q.x << 16), w1 = __uint_as_float(q.x & 0xFFFF0000u);
+            const float w2 = __uint_as_float(q.y << 16), w3 = __uint_as_float(q.y & 0xFFFF0000u);
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const float w0 = __uint_as_float(u[i] << 16), w1 = __uint_as_float(u[i] & 0xFFFF0000u);
-                float x0[TBI], x1[TBI];
-                lds_load_tile<TBI>(xs, c8 * 8 + 2 * i, x0);
-                lds_load_tile<TBI>(xs, c8 * 8 + 2 * i + 1, x1);
-#pragma unroll
-                for (int t = 0; t < TBI; t++) acc[t] = fmaf(w1, x1[t], fmaf(w0, x0[t], acc[t]));
+            for (int t = 0; t < TBI; t++) {
+                const float4 x = reinterpret_cast<const float4 *>(xs + (size_t)t * plane)[c4];
+                acc[t] = fmaf(w3, x.w, fmaf(w2, x.z, fmaf(w1, x.y, fmaf(w0, x.x, acc[t]))));
             }
         }
 #pragma unroll
@@ -883,21 +886,27 @@ __global__ __launch_bounds__(1024) void k_dense_bf16(const DenseArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     float *xs = reinterpret_cast<float *>(smem);
-    const size_t xs_bytes = (size_t)(a.cols + kPadCols) * a.tb_max * sizeof(float);
+    const int plane = (a.cols + 3) / 4 * 4;  // one token's activations
+    const size_t xs_bytes = (size_t)plane * a.tb_max * sizeof(float);
     int *tok_ids = reinterpret_cast<int *>(smem + xs_bytes);
     int *x_rows = tok_ids + kMaxTokenTile;
+    int *next_item = x_rows + kMaxTokenTile;
 
     const int n_pass = min(*a.n_items_dev, a.max_items);
-    const long long total = (long long)n_pass * a.blocks_per_pass;
-    const long long per = (total + gridDim.x - 1) / gridDim.x;
-    const long long g0 = per * blockIdx.x;
-    const long long g1 = min(total, g0 + per);
+    const int total = (int)min((long long)n_pass * a.blocks_per_pass, 0x7FFFFFFFLL);
     int cur_pass = -1, ntok = 0, slot0 = 0, expert = 0, tbi = 1;
-    for (long long g = g0; g < g1; g++) {
-        const int pass = (int)(g / a.blocks_per_pass);
-        const int blk = (int)(g - (long long)pass * a.blocks_per_pass);
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int g = atomicAdd(a.work_counter, 1);
+            *next_item = g < total ? g : -1;
+        }
+        __syncthreads();
+        const int g = *next_item;
+        if (g < 0) break;
+        const int pass = g / a.blocks_per_pass;
+        const int blk = g - pass * a.blocks_per_pass;
         if (pass != cur_pass) {
-            __syncthreads();
             const Item it = a.items[pass];
             expert = it.expert; slot0 = it.slot0; ntok = it.ntok;
             if (expert < 0 || expert >= a.n_experts || ntok < 1) ntok = 0;
@@ -914,11 +923,11 @@ __global__ __launch_bounds__(1024) void k_dense_bf16(const DenseArgs a)
                 x_rows[t] = xr;
             }
             __syncthreads();
-            for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x)
-                for (int t = 0; t < tbi; t++) {
+            for (int t = 0; t < tbi; t++)
+                for (int c = threadIdx.x; c < plane; c += blockDim.x) {
                     float v = 0.0f;
                     if (c < a.cols && t < ntok) v = bf16_bits_to_float(a.x[(size_t)x_rows[t] * a.ldx + c]);
-                    xs[(size_t)c * tbi + t] = v;
+                    xs[(size_t)t * plane + c] = v;
                 }
             __syncthreads();
             cur_pass = pass;
@@ -929,10 +938,10 @@ __global__ __launch_bounds__(1024) void k_dense_bf16(const DenseArgs a)
         const int r0 = blk * a.rows_per_item;
         const int r1 = min(a.rows, r0 + a.rows_per_item);
         switch (tbi) {
-        case 1: dense_rows<1>(a, W, ntok, slot0, r0, r1, xs, tok_ids); break;
-        case 2: dense_rows<2>(a, W, ntok, slot0, r0, r1, xs, tok_ids); break;
-        case 4: dense_rows<4>(a, W, ntok, slot0, r0, r1, xs, tok_ids); break;
-        default: dense_rows<8>(a, W, ntok, slot0, r0, r1, xs, tok_ids); break;
+        case 1: dense_rows<1>(a, W, ntok, slot0, r0, r1, xs, plane, tok_ids); break;
+        case 2: dense_rows<2>(a, W, ntok, slot0, r0, r1, xs, plane, tok_ids); break;
+        case 4: dense_rows<4>(a, W, ntok, slot0, r0, r1, xs, plane, tok_ids); break;
+        default: dense_rows<8>(a, W, ntok, slot0, r0, r1, xs, plane, tok_ids); break;
         }
     }
 }
@@ -1011,7 +1020,9 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     const double est_codes = (double)max_passes_hint * rows * codes_per_row;
     const bool lds_table = n_order == 0 && run_table && tu.lds_dict_entries >= 0 && max_lds >= 128 * 1024 &&
                            (tu.lds_dict_entries > 0 || est_codes / di.cus >= 1.0e6);
-    int tb = kMaxTokenTile;
+    // tiles of eight tokens cost more per token than two tiles of four (16-byte LDS gathers,
+    // register pressure), so four is the default
+    int tb = 4;
     if (n_order > 0) {
         // device-order streams: the whole table goes to LDS, the tile takes what is left
         if (xs_bytes(1) + fixed + 4 * (size_t)n_order + 16384 > max_lds) return QMOE_E_LIMIT;
@@ -1082,25 +1093,26 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     return QMOE_OK;
 }
 
-// The dense bf16 comparator keeps its own simple plan: fp32 activations in LDS, wavefront per row.
+// The dense bf16 comparator keeps its own simple plan: token-major fp32 activations in
+// LDS, one wavefront per row.
 qmoe_status plan_dense(int rows, int cols, long long max_passes_hint, ProductPlan *p)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
     if (st != QMOE_OK) return st;
     const size_t max_lds = (size_t)di.max_lds;
-    const size_t col_bytes = (size_t)(cols + kPadCols) * sizeof(float);
+    const size_t plane_bytes = (size_t)((cols + 3) / 4 * 4) * sizeof(float);
     int tb = kMaxTokenTile;
-    while (tb > 1 && col_bytes * tb + 64 > max_lds / 2) tb >>= 1;
-    if (col_bytes * tb + 64 > max_lds) return QMOE_E_LIMIT;
+    while (tb > 1 && plane_bytes * tb + 128 > max_lds) tb >>= 1;
+    if (plane_bytes * tb + 128 > max_lds) return QMOE_E_LIMIT;
     p->tb_max = tb;
     p->lds_dict_entries = 0;
-    p->smem = col_bytes * tb + 64;
-    p->threads = 512;
-    p->rows_per_item = std::min(rows, 128);
-    p->blocks_per_pass = (rows + p->rows_per_item - 1) / p->rows_per_item;
+    p->smem = plane_bytes * tb + 128;
     const int fit = (int)std::max<size_t>(1, max_lds / p->smem);
-    long long grid = (long long)di.cus * std::max(1, std::min(fit, 4));
+    p->threads = fit >= 2 ? 512 : 1024;
+    p->rows_per_item = std::min(rows, 4 * (p->threads / 64));
+    p->blocks_per_pass = (rows + p->rows_per_item - 1) / p->rows_per_item;
+    long long grid = (long long)di.cus * std::max(1, std::min(fit, 2048 / p->threads));
     const long long items = max_passes_hint * p->blocks_per_pass;
     if (items < grid) grid = std::max(1LL, items);
     p->grid = (int)grid;
@@ -1465,6 +1477,7 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     a.rows_per_item = pwi.rows_per_item;
     a.blocks_per_pass = pwi.blocks_per_pass;
     a.tb_max = pwi.tb_max;
+    a.work_counter = lp.counters + 5;
     if (phases & 2) {
         if ((st = allow_lds(k_dense_bf16, pwi.smem)) != QMOE_OK) return st;
         hipLaunchKernelGGL(k_dense_bf16, dim3(pwi.grid), dim3(pwi.threads), pwi.smem, s, a);
@@ -1485,6 +1498,7 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     a.rows_per_item = pwo.rows_per_item;
     a.blocks_per_pass = pwo.blocks_per_pass;
     a.tb_max = pwo.tb_max;
+    a.work_counter = lp.counters + 6;
     if (phases & 4) {
         if ((st = allow_lds(k_dense_bf16, pwo.smem)) != QMOE_OK) return st;
         hipLaunchKernelGGL(k_dense_bf16, dim3(pwo.grid), dim3(pwo.threads), pwo.smem, s, a);

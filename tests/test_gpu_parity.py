@@ -281,3 +281,28 @@ def test_switch_large128_interchange_numbering(gpu, ddict, oracle_dict):
     finally:
         q.qmoe_set_tuning("lds_dict_entries", 0)
     _check_layer(w, idx, x, y, wsout, list(range(0, idx.size, 2)))
+
+
+def test_bf16_comparator_close_to_the_compressed_layer(gpu, ddict, oracle_dict):
+    """The uncompressed comparator multiplies bf16-rounded (scale * ternary) weights, so it can
+    only agree to bf16 precision; a wrong dispatch or a wrong row would show as an O(1) error."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=6, d_model=136, d_ff=264, n_tokens=40)
+    idx, x = w.expert_idx(), w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    y, _ = _run_layer(layer, ddict, x, idx, gpu)
+    wi_ptr, wo_ptr, keep = np.zeros(6, dtype=np.int64), np.zeros(6, dtype=np.int64), []
+    for e in range(6):
+        for which, tern, scale, arr in (("wi", w.wi_ternary(e), w.wi_scale(e), wi_ptr),
+                                        ("wo", w.wo_ternary(e), w.wo_scale(e), wo_ptr)):
+            dense = torch.from_numpy(tern.astype(np.float32) * synth.f16_to_f64(scale).astype(np.float32)[:, None])
+            dense = dense.to(torch.bfloat16).to(gpu).contiguous()
+            keep.append(dense)
+            arr[e] = dense.data_ptr()
+    y2 = torch.full((idx.size, w.d_model), float("nan"), dtype=torch.float32, device=gpu)
+    ws = layer.workspace(idx.size)
+    q.qmoe_bf16_layer_forward(torch.from_numpy(wi_ptr).to(gpu), torch.from_numpy(wo_ptr).to(gpu), 6, w.d_model,
+                              w.d_ff, _to_dev16(x, gpu), torch.from_numpy(idx).to(gpu), None, y2, ws)
+    torch.cuda.synchronize()
+    y2 = y2.cpu().numpy()
+    assert np.isfinite(y2).all()
+    assert np.linalg.norm(y2 - y) / np.linalg.norm(y) < 2e-2
