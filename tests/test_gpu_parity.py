@@ -306,3 +306,74 @@ def test_bf16_comparator_close_to_the_compressed_layer(gpu, ddict, oracle_dict):
     y2 = y2.cpu().numpy()
     assert np.isfinite(y2).all()
     assert np.linalg.norm(y2 - y) / np.linalg.norm(y) < 2e-2
+
+
+# ---------------------------------------------------------------------------
+# Full-size workloads in the launch configuration bench.py times: the library's
+# own dictionary and encoder, device-order streams, sampled tokens checked one
+# by one against the oracle (which regenerates and multiplies the expert densely).
+
+def _full_layer(w, gpu):
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    dd = dev.DeviceDict(device=gpu)
+    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu)
+    q.qmoe_set_tuning("host_threads", 1)
+
+    def one(e):
+        out = []
+        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_scale(e)), ("wo", w.wo_ternary(e), w.wo_scale(e))):
+            codes, row_off = q.qmoe_encode_host(dd.handle, tern)
+            out.append((which, codes, row_off, scale))
+        return e, out
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for e, parts in pool.map(one, range(w.n_experts)):
+            for which, codes, row_off, scale in parts:
+                layer.set_expert(e, which, codes, row_off, scale)
+    q.qmoe_set_tuning("host_threads", 0)
+    return dd, layer.finalize(device_order_of=dd)
+
+
+def _sample_tokens(idx, n_experts, per_class=4):
+    """Tokens from experts with 1 token, a few tokens, and the most tokens."""
+    counts = np.bincount(idx, minlength=n_experts)
+    order = np.argsort(-counts, kind="stable")
+    picks = []
+    busiest = [int(e) for e in order[:2]]
+    singles = [int(e) for e in np.nonzero(counts == 1)[0][:per_class]]
+    middle = [int(e) for e in np.nonzero((counts >= 3) & (counts <= 12))[0][:per_class]]
+    for e in busiest + singles + middle:
+        toks = np.nonzero(idx == e)[0]
+        picks.extend(int(t) for t in toks[:: max(1, toks.size // 3)][:3])
+    return sorted(set(picks))
+
+
+def test_c2048_layer_full_size_sampled(gpu, oracle_dict):
+    """2048 experts 2080 x 6144, 2048 tokens, Zipf routing: the benchmark's workload."""
+    w = synth.WORKLOADS["c2048"]
+    idx, x = w.expert_idx(), w.tokens()
+    dd, layer = _full_layer(w, gpu)
+    # the library's encoder must have produced the oracle's stream (checked on two experts)
+    for e in (int(idx[0]), int(idx[-1])):
+        oc, oro = oracle.encode(oracle_dict, w.wo_ternary(e))
+        assert layer.n_codes["wo"][e] == oc.size
+    y, wsout = _run_layer(layer, dd, x, idx, gpu)
+    assert np.isfinite(y).all()
+    counts = np.bincount(idx, minlength=w.n_experts)
+    assert wsout["counters"][2] == int((counts > 0).sum()) and wsout["counters"][0] == idx.size
+    _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts))
+    y2, _ = _run_layer(layer, dd, x, idx, gpu)
+    assert np.array_equal(y, y2)  # run-to-run bitwise identical
+    dd.close()
+
+
+def test_c2048_ragged_layer_full_size_sampled(gpu, oracle_dict):
+    """256 experts, 1-32 tokens each, per-row zero fraction 0.80-0.97."""
+    w = synth.WORKLOADS["c2048_ragged256"]
+    idx, x = w.expert_idx(), w.tokens()
+    dd, layer = _full_layer(w, gpu)
+    y, wsout = _run_layer(layer, dd, x, idx, gpu)
+    assert np.isfinite(y).all()
+    _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts, per_class=3))
+    dd.close()
