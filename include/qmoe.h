@@ -104,7 +104,9 @@ size_t qmoe_dict_device_bytes(void);
  *   table    [n_table] entry of group g at table[g] (both free signs positive), entry of
  *                      single code 4*n_groups + i at table[n_groups + i]; each entry is
  *                      byte 0 = 8 * run length, bytes 1..3 = one field per non-zero:
- *                      (position << 3) | (weight as 2-bit signed integer << 1), 0 = unused
+ *                      (position << 3) | (weight as 2-bit signed integer << 1), 0 = unused;
+ *                      the fields are right-aligned (k non-zeros fill bytes 4-k..3 in
+ *                      ascending position), so unused fields always come first
  * Device code c < 4*n_groups decodes to table[c >> 2] with bit 2 of field 1 set if c & 1
  * and bit 2 of field 2 set if c & 2 (which turns weight +1 into -1).
  * code_map and table are NULL (n_table = 0) when the dictionary has no device order.
@@ -153,7 +155,9 @@ qmoe_status qmoe_validate_host(const qmoe_dict *d, const uint16_t *codes /*host*
 
 /* One compressed matrix.  All pointers are device memory owned by the caller. */
 typedef struct qmoe_matrix {
-    const uint16_t *codes;     /* [n_codes] codewords, rows back to back               */
+    const uint16_t *codes;     /* [n_codes] codewords, rows back to back; 16-byte aligned,
+                                  readable (any contents) up to the next 16-byte
+                                  boundary after the last codeword                      */
     const uint32_t *row_off;   /* [rows+1] first codeword of each row                   */
     const uint16_t *scale_f16; /* [rows] IEEE binary16 scale s_r of each output row     */
     int32_t rows, cols;        /* cols even                                             */
@@ -205,13 +209,18 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
  * tests that want to look at the dispatch result:
  *   tok_off  int32 [n_experts+1]  expert e owns slots tok_off[e]..tok_off[e+1]
  *   perm     int32 [n_tokens]     slot -> token index, ascending inside an expert
- *   counters int32 [8]            [0] tokens kept, [1] tokens dropped (expert index
+ *   counters int32 [16]           [0] tokens kept, [1] tokens dropped (expert index
  *                                 outside [0,n_experts)), [2] experts with tokens,
- *                                 [3] work items of the first product, [4] of the second
+ *                                 [3] work items of the first product, [4] of the second,
+ *                                 [7] token tiles of crowded experts (items_mm, up to 64
+ *                                 tokens each, both products, matrix-core kernel)
+ *   items_*  int32 [n_tokens][4]  {expert, first slot, tokens, 0}; every kept token is in
+ *                                 exactly one item of items_wi or items_mm, and one of
+ *                                 items_wo or items_mm
  *   hidden   bf16  [n_tokens][d_ff]  by slot
  */
 typedef struct qmoe_ws_layout {
-    size_t tok_off, perm, counters, items_wi, items_wo, hidden, total;
+    size_t tok_off, perm, counters, items_wi, items_wo, items_mm, hidden, total;
 } qmoe_ws_layout;
 
 qmoe_status qmoe_moe_layer_ws_layout(int n_experts, int d_model, int d_ff, int n_tokens,
@@ -231,7 +240,10 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * initialised.  Experts without tokens are never touched (their qmoe_matrix
  * may hold anything).  code_order: the numbering of every expert's stream (0 or 1, as
  * in qmoe_matrix; the descriptors live in device memory, so the host is told).
- * Enqueues a dispatch kernel and the two product kernels.
+ * Enqueues a dispatch kernel and, per product, the scalar kernel for experts with few
+ * tokens and (device-order streams, widths divisible by 8, x 16-byte aligned) the
+ * matrix-core kernel for crowded ones: an expert's matrix is decoded once per tile of up
+ * to 64 tokens there, instead of once per 4.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
  * n_tokens > 2^20, d_model or d_ff > 32768; code_order 1 without a device order), HIP.
  */
@@ -242,10 +254,14 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*d
                                    int n_tokens, float *y /*device*/, void *workspace /*device*/,
                                    size_t workspace_bytes, void *stream);
 
-/* Only the dispatch step of the layer (fills tok_off, perm, counters, work items). */
-qmoe_status qmoe_moe_dispatch(const int32_t *expert_idx /*device*/, int n_tokens, int n_experts,
-                              int d_model, int d_ff, void *workspace /*device*/,
-                              size_t workspace_bytes, void *stream);
+/*
+ * Only the dispatch step of the layer (fills tok_off, perm, counters, work items), planned
+ * as qmoe_moe_layer_forward would for this dictionary and code order (and a 16-byte
+ * aligned x).
+ */
+qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t *expert_idx /*device*/,
+                              int n_tokens, int n_experts, int d_model, int d_ff,
+                              void *workspace /*device*/, size_t workspace_bytes, void *stream);
 
 /*
  * The same layer on uncompressed weights, for the "uncompressed bf16
@@ -265,7 +281,11 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
 /*
  * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
  * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
- * "grid_per_cu", "host_threads" (encoder threads), "phases" (bit mask of the layer's
+ * "grid_per_cu", "blocks_first" / "blocks_second" (workgroups that share one pass over a
+ * matrix in the first or only / the second product), "mfma_min_tokens" (experts with at
+ * least this many tokens use the matrix-core kernel; -1 = never), "host_threads" (encoder
+ * threads),
+ * "phases" (bit mask of the layer's
  * kernels to enqueue: 1 dispatch, 2 first product, 4 second product -- lets a
  * benchmark time one kernel on a workspace a full call has filled).  value 0 restores
  * the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2.

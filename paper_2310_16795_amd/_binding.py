@@ -33,7 +33,7 @@ class qmoe_matrix(Structure):
 
 
 class qmoe_ws_layout(Structure):
-    _fields_ = [(n, c_size_t) for n in ("tok_off", "perm", "counters", "items_wi", "items_wo", "hidden", "total")]
+    _fields_ = [(n, c_size_t) for n in ("tok_off", "perm", "counters", "items_wi", "items_wo", "items_mm", "hidden", "total")]
 
 
 EXPORTS = [
@@ -72,7 +72,7 @@ def lib():
         L.qmoe_moe_layer_forward.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_dict_device_order.argtypes = [vp, POINTER(vp), POINTER(vp), POINTER(i), POINTER(i)]
         L.qmoe_codes_to_device_order.argtypes = [vp, vp, sz, vp]
-        L.qmoe_moe_dispatch.argtypes = [vp, i, i, i, i, vp, sz, vp]
+        L.qmoe_moe_dispatch.argtypes = [vp, i, vp, i, i, i, i, vp, sz, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
         L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -237,8 +237,9 @@ def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, code_order: int, n_experts: i
            "qmoe_moe_layer_forward")
 
 
-def qmoe_moe_dispatch(expert_idx, n_experts: int, d_model: int, d_ff: int, workspace, stream=None) -> None:
-    _check(lib().qmoe_moe_dispatch(_dev_ptr(expert_idx), expert_idx.numel(), n_experts, d_model, d_ff,
+def qmoe_moe_dispatch(d, code_order: int, expert_idx, n_experts: int, d_model: int, d_ff: int, workspace,
+                      stream=None) -> None:
+    _check(lib().qmoe_moe_dispatch(d, code_order, _dev_ptr(expert_idx), expert_idx.numel(), n_experts, d_model, d_ff,
                                    _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream_ptr(stream)), "qmoe_moe_dispatch")
 

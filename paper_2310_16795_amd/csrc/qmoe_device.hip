@@ -48,6 +48,7 @@ constexpr int kMaxExperts = 16384;
 constexpr int kMaxTokens = 1 << 20;
 constexpr int kMaxRowsPerItem = 1024;
 constexpr uint32_t kMaxCodes = 0xFFFFFF00u;  // keeps `kb += 16` from wrapping
+constexpr int kLayerCounters = 16;
 
 struct Item {  // one (expert, token tile) unit of work; row blocks are enumerated on the fly
     int expert, slot0, ntok, pad;
@@ -79,6 +80,7 @@ struct ProductArgs {
     const uint32_t *order_table;  // device-order table (n_order entries, the first n_groups are groups)
     int n_groups, n_order;
     int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
+    int mm_row_blocks, mm_rows_per_block;  // matrix-core kernel: workgroups per matrix, rows each takes (<= 512)
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -436,8 +438,8 @@ __device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp
 //
 // The rows of the matrix are dealt out evenly over all lanes of the workgroups that
 // share the item; a lane's rows are consecutive, so its codewords are one contiguous
-// piece of the stream, which it reads in aligned 64-byte chunks (32 codewords, the
-// next chunk in flight while the current one is decoded) and decodes sequentially:
+// piece of the stream, which it reads in aligned 16-byte pieces (eight codewords, two
+// pieces in flight ahead of the one being applied) and decodes sequentially:
 // no prefix sum across lanes, no reduction -- the running column index is a scalar
 // per lane, exactly the paper's sequential decoder, 64 of them per wavefront.  Table
 // entries are fetched eight codewords ahead of their use.
@@ -458,16 +460,16 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
         K0 = min(row_off[ra], K1);
     }
     const uint32_t n = K1 - K0;  // codewords of this lane
-    // 64-byte chunks by address; `rel` is the stream index (relative to K0) of the chunk's first slot
+    // The stream is read in aligned 16-byte pieces (eight codewords); `rel` is the stream
+    // index (relative to K0) of the first slot of the lane's first piece.
     const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + 2 * (uintptr_t)K0;
-    const uint32_t lead = (uint32_t)(first_byte & 63u);
-    uintptr_t chunk = first_byte - lead;
-    int rel = -(int)(lead >> 1);
-    const int my_chunks = n ? (int)((lead + 2u * n + 63u) >> 6) : 0;
-    const uintptr_t last_chunk = chunk + 64u * (uintptr_t)max(my_chunks - 1, 0);
-    int nchunks = my_chunks;
+    const uint32_t lead = (uint32_t)(first_byte & 15u);
+    const uintptr_t chunk = first_byte - lead;
+    const int rel = -(int)(lead >> 1);
+    const int my_pieces = n ? (int)((lead + 2u * n + 15u) >> 4) : 0;
+    int npieces = my_pieces;
 #pragma unroll
-    for (int d = 32; d > 0; d >>= 1) nchunks = max(nchunks, __shfl_xor(nchunks, d, 64));
+    for (int d = 32; d > 0; d >>= 1) npieces = max(npieces, __shfl_xor(npieces, d, 64));
 
     const uint32_t cols8 = 8u * (uint32_t)a.cols;
     LaneState<TBI> st;
@@ -477,14 +479,14 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     st.row = ra;
     st.rb = rb;
 
-    // The stream is walked in 16-byte pieces (eight codewords): piece p + 2 is being
-    // loaded and the entries of piece p + 1 looked up while piece p is applied.
-    const int npieces = 4 * nchunks;
-    const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(4 * my_chunks - 1, 0);
+    // Piece p + 2 is being loaded and the entries of piece p + 1 looked up while piece p
+    // is applied.
+    const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(my_pieces - 1, 0);
     const bool fast = DICT != kDictWords && a.cols >= 224;
     auto load_piece = [&](int p) -> u32x4 {
         // lanes past their own end re-read their last piece (its slots are masked out below)
-        return *(gp_u32x4)min(chunk + 16u * (uintptr_t)p, last_piece);
+        const uintptr_t at = chunk + 16u * (uintptr_t)p;
+        return *(gp_u32x4)(at < last_piece ? at : last_piece);
     };
     auto apply = [&](const Entry (&e)[8], int r) {
         // r: stream index (relative to K0) of the piece's first slot
@@ -644,6 +646,288 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     }
 }
 
+// ---------------------------------------------------------------- matrix-core product for crowded experts
+//
+// An expert with many tokens is a dense contraction once its ternary weights are
+// in hand: y[token][row] = sum_k x[token][k] * W[row][k].  The scalar kernel above
+// would decode the matrix again for every few tokens; this one decodes it once per
+// tile of up to 64 tokens.  A workgroup owns up to 512 rows (one lane per row) and
+// walks the columns 64 at a time.  Every lane keeps a ring of 128 one-byte columns
+// of its row in LDS and decodes its codewords into it sequentially, as far ahead as
+// the ring allows (so the lanes of a wavefront, whose codewords end at different
+// columns, seldom wait for each other); then each wavefront multiplies the 64
+// columns that are complete, for the 64 rows its own lanes decoded, with the
+// tokens' activations (staged in LDS, shared by all wavefronts) on the matrix
+// cores: D[token][row] += X[token][k] * W^T[k][row], fp32 accumulators in
+// registers.  The ring holds the weights as the high byte of bf16 +-2.0 (0x40 /
+// 0xC0, low byte zero), expanded to bf16 by a byte permute when a fragment is
+// read; the factor 2 is taken out again, exactly, when a row is written.
+// Only device-order streams (whole table in LDS) take this path.
+
+constexpr int kMmThreads = 512;
+constexpr int kMmKc = 64;                      // columns per step
+constexpr int kMmRing = 2 * kMmKc;             // columns a lane's ring holds
+constexpr int kMmAhead = kMmRing - 28;         // a codeword may start this far past the step's first column
+constexpr int kMmWRowBytes = kMmRing + 8;      // 34 banks per row: 16 consecutive rows read 8 bytes each without conflict
+constexpr int kMmXRowBytes = 2 * kMmKc + 16;   // 36 banks per row: 8 consecutive rows read 16 bytes each without conflict
+constexpr int kMmTokens = 64;                  // tokens per tile
+constexpr int kMmMinTokensDefault = 8;         // experts with fewer tokens stay on the scalar kernel
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+inline size_t mm_lds_bytes(int n_order)
+{
+    return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes +
+           2 * (size_t)kMmTokens * kMmXRowBytes + 2 * sizeof(int) * kMmTokens + 16;
+}
+
+// eight ring bytes (high bytes of bf16) -> eight bf16
+__device__ __forceinline__ bf16x8 mm_expand(uint32_t d0, uint32_t d1)
+{
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(0u, d0, 0x010c000cu);
+    o.y = __builtin_amdgcn_perm(0u, d0, 0x030c020cu);
+    o.z = __builtin_amdgcn_perm(0u, d1, 0x010c000cu);
+    o.w = __builtin_amdgcn_perm(0u, d1, 0x030c020cu);
+    bf16x8 r;
+    __builtin_memcpy(&r, &o, 16);
+    return r;
+}
+
+using lw_u8 = __attribute__((address_space(3))) unsigned char *;
+using lw_u64 = __attribute__((address_space(3))) unsigned long long *;
+using lw_u32x4 = __attribute__((address_space(3))) u32x4 *;
+using lp_u64 = const __attribute__((address_space(3))) unsigned long long *;
+using lp_u32x4 = const __attribute__((address_space(3))) u32x4 *;
+using lp_i32 = const __attribute__((address_space(3))) int *;
+using lp_f32 = const __attribute__((address_space(3))) float *;
+
+// MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
+// rings and the two activation buffers.
+template <int MB, int EPI>
+__device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
+                                        lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // this thread's part of the activation tile: token tx, columns 8*seg .. 8*seg+7 of each step
+    const int tx = tid >> 3, seg = tid & 7;
+    const bool x_live = tx < ntok;
+    size_t xrow = 0;
+    if (x_live) {
+        const int tok = a.perm ? a.perm[slot0 + tx] : slot0 + tx;
+        xrow = a.x_by_slot ? (size_t)(slot0 + tx) : (size_t)tok;
+    }
+    const uintptr_t xsrc = reinterpret_cast<uintptr_t>(a.x) + 2 * (xrow * (size_t)a.ldx + 8 * (size_t)seg);
+    auto load_x = [&](int kc) -> u32x4 {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (x_live && kc + 8 * seg + 8 <= a.cols) v = *(gp_u32x4)(xsrc + 2 * (uintptr_t)kc);
+        return v;
+    };
+    const uint32_t x_slot = xt + (uint32_t)(tx * kMmXRowBytes + 16 * seg);  // in buffer 0
+
+    // this lane's row and its codewords
+    const int r0 = blk * a.mm_rows_per_block;
+    const int row = r0 + tid;
+    const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
+    uint32_t left = 0;
+    uintptr_t pp = reinterpret_cast<uintptr_t>(M.codes), last = pp;
+    uint32_t sub = 0;
+    if (row_live) {
+        gp_u32 row_off = (gp_u32)M.row_off;
+        const uint32_t cap = min(M.n_codes, kMaxCodes);
+        const uint32_t K1 = min(row_off[row + 1], cap);
+        const uint32_t K0 = min(row_off[row], K1);
+        left = K1 - K0;
+        const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + 2 * (uintptr_t)K0;
+        const uint32_t lead = (uint32_t)(first_byte & 15u);
+        pp = first_byte - lead;
+        sub = lead >> 1;
+        last = pp + 16u * (uintptr_t)(left ? ((lead + 2u * left + 15u) >> 4) - 1u : 0u);
+    }
+    // The stream in 16-byte pieces (eight codewords): `cur` and `nxt` are the window the
+    // decoder picks codewords from (index sub = 0..15), `fut` is in flight.  Pieces past the
+    // lane's last one re-read the last (never used: `left` runs out first).
+    auto piece = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
+    u32x4 cur = piece(pp), nxt = piece(pp + 16u), fut = piece(pp + 32u);
+    int pos = 0;  // column where the next codeword starts
+    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
+
+    f32x16 acc[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[mb][nb][v] = 0.0f;
+
+    // activations: step c is read from LDS buffer c & 1, step c + 1 is written there during
+    // step c, steps c + 2 and c + 3 are in registers / in flight
+    *(lw_u32x4)(uintptr_t)x_slot = load_x(0);
+    u32x4 xr0 = load_x(kMmKc), xr1 = load_x(2 * kMmKc);
+#pragma unroll
+    for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+    __syncthreads();  // token ids, gates and the first activation step are in place
+
+    const uint32_t wfrag = wt + (uint32_t)((64 * wave + l32) * kMmWRowBytes + 8 * lhi);
+    const uint32_t xfrag0 = xt + (uint32_t)(l32 * kMmXRowBytes + 16 * lhi);
+    const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+    for (int c = 0; c < nsteps; c++) {
+        const int kc = c * kMmKc, kend = kc + kMmKc;
+        const uint32_t other = (uint32_t)((c + 1) & 1);
+        // stage the next step's activations, fetch those three steps on
+        *(lw_u32x4)(uintptr_t)(x_slot + other * (uint32_t)(kMmTokens * kMmXRowBytes)) = xr0;
+        xr0 = xr1;
+        xr1 = load_x(kc + 3 * kMmKc);
+        // the half of the ring the previous step multiplied becomes columns kend .. kend+63
+#pragma unroll
+        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + other * kMmKc))[i] = 0ull;
+
+        // Decode until every lane has passed column kend; lanes that are there already keep
+        // going while their next codeword fits into the ring.  No branches inside: a lane
+        // that sits out decodes an empty entry into the spare bytes after its ring.
+        for (;;) {
+            if (sub >= 8u) {  // slide the window (seldom more than once per step)
+                sub -= 8u;
+                pp += 16u;
+                cur = nxt;
+                nxt = fut;
+                fut = piece(pp + 32u);
+            }
+            while (__any(left != 0u && pos < kend && sub < 16u)) {
+                const bool go = left != 0u && pos <= kc + kMmAhead && sub < 16u;
+                const bool hi8 = (sub & 8u) != 0u, hi4 = (sub & 4u) != 0u;
+                const uint32_t lo = hi8 ? (hi4 ? nxt.z : nxt.x) : (hi4 ? cur.z : cur.x);
+                const uint32_t hi = hi8 ? (hi4 ? nxt.w : nxt.y) : (hi4 ? cur.w : cur.y);
+                // bytes 2s, 2s+1 of {hi, lo}: selector 0x0c0c0100 + 0x0202 * s
+                const uint32_t code = __builtin_amdgcn_perm(hi, lo, 0x0c0c0100u + 0x0202u * (sub & 3u));
+                uint32_t ent = order_entry(table, code, (uint32_t)a.n_groups, (uint32_t)a.n_order);
+                ent = go ? ent : 0u;
+                const uint32_t base = go ? (uint32_t)pos : (uint32_t)kMmRing;
+                const uint32_t mask = go ? (uint32_t)(kMmRing - 1) : 0xFFu;
+                // fields are right-aligned in device-order entries: an unused one (0) comes
+                // first and writes a zero at the run's first column, before any real weight
+#pragma unroll
+                for (int z = 0; z < kRunMaxNonzeros; z++) {
+                    const uint32_t f = (ent >> (8 + 8 * z)) & 0xFFu;
+                    const uint32_t col = (base + (f >> 3)) & mask;
+                    *(lw_u8)(uintptr_t)(wrow + col) = (unsigned char)((f & 6u) << 5);  // 0, 0x40 (+2.0), 0xC0 (-2.0)
+                }
+                pos += (int)((ent & 0xFFu) >> 3);
+                left -= go ? 1u : 0u;
+                sub += go ? 1u : 0u;
+            }
+            if (!__any(left != 0u && pos < kend)) break;
+        }
+        // the rows this wavefront multiplies are the ones its own lanes wrote
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        const uint32_t xf = xfrag0 + (uint32_t)((c & 1) * kMmTokens * kMmXRowBytes);
+        const uint32_t wf = wfrag + (uint32_t)((c & 1) * kMmKc);
+#pragma unroll
+        for (int ks = 0; ks < kMmKc / 16; ks++) {
+            bf16x8 bw[2], ax[MB];
+#pragma unroll
+            for (int nb = 0; nb < 2; nb++) {
+                const unsigned long long d = *(lp_u64)(uintptr_t)(wf + (uint32_t)(nb * 32 * kMmWRowBytes + 16 * ks));
+                bw[nb] = mm_expand((uint32_t)d, (uint32_t)(d >> 32));
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++) {
+                const u32x4 t = *(lp_u32x4)(uintptr_t)(xf + (uint32_t)(mb * 32 * kMmXRowBytes + 32 * ks));
+                __builtin_memcpy(&ax[mb], &t, 16);
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+                for (int nb = 0; nb < 2; nb++)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[mb], bw[nb], acc[mb][nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __syncthreads();  // next step's activations visible; this step's reads of the other buffer are done
+    }
+
+    // accumulator v of lane l: token 32*mb + 8*(v/4) + 4*(l/32) + v%4, row 32*nb + l%32 of the wavefront's 64
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++) {
+        const int rl = 64 * wave + 32 * nb + l32;
+        const int r = r0 + rl;
+        if (rl < a.mm_rows_per_block && r < a.rows) {
+            const float scale = half_bits_to_float(((gp_u16)M.scale_f16)[r]);
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++) {
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int t = 32 * mb + 8 * (v / 4) + 4 * lhi + (v % 4);
+                    if (t < ntok) {
+                        const float val = (acc[mb][nb][v] * 0.5f) * scale;  // the weights were +-2
+                        if constexpr (EPI == 0) {
+                            reinterpret_cast<float *>(a.out)[(size_t)tok_ids[t] * a.ld_out + r] = gate_s[t] * val;
+                        } else {
+                            const float h = val > 0.0f ? val : 0.0f;
+                            reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] =
+                                float_to_bf16_bits(h);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
+    uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
+    unsigned char *wt = smem + table_bytes;                           // [512][kMmWRowBytes]
+    unsigned char *xt = wt + (size_t)kMmThreads * kMmWRowBytes;       // 2 x [64][kMmXRowBytes]
+    int *tok_ids = reinterpret_cast<int *>(xt + 2 * (size_t)kMmTokens * kMmXRowBytes);  // [64]
+    float *gate_s = reinterpret_cast<float *>(tok_ids + kMmTokens);   // [64]
+    int *next_item = reinterpret_cast<int *>(gate_s + kMmTokens);     // [1]
+
+    const int n_items = min(*a.n_items_dev, a.max_items);
+    const int total = (int)min((long long)n_items * a.mm_row_blocks, 0x7FFFFFFFLL);
+    if (total <= 0) return;
+    for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
+
+    for (;;) {
+        __syncthreads();  // everyone is done with the previous item
+        if (threadIdx.x == 0) {
+            const int g = atomicAdd(a.work_counter, 1);
+            *next_item = g < total ? g : -1;
+        }
+        __syncthreads();
+        const int g = *next_item;
+        if (g < 0) break;
+        const int idx = g / a.mm_row_blocks;
+        const int blk = g - idx * a.mm_row_blocks;
+        const Item it = a.items[idx];
+        const int expert = it.expert, slot0 = it.slot0;
+        const int ntok = min(it.ntok, kMmTokens);
+        if (expert < 0 || expert >= a.n_experts || ntok < 1) continue;
+        if (threadIdx.x < kMmTokens) {
+            const int t = threadIdx.x;
+            const int tok = t < ntok ? (a.perm ? a.perm[slot0 + t] : slot0 + t) : 0;
+            tok_ids[t] = tok;
+            gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
+        }
+        const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
+        const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, xt_addr = (uint32_t)(uintptr_t)(lw_u8)xt;
+        if (ntok <= 32)
+            mm_item<1, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+                            (lp_f32)gate_s);
+        else
+            mm_item<2, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+                            (lp_f32)gate_s);
+    }
+}
+
 // ---------------------------------------------------------------- pure decompression
 
 template <bool RUN>
@@ -687,8 +971,9 @@ struct DispatchArgs {
     int *tok_off;   // [E+1]
     int *perm;      // [T]
     int *counters;  // [8]
-    Item *items_wi, *items_wo;
+    Item *items_wi, *items_wo, *items_mm;
     int tb_wi, tb_wo;
+    int mm_min;     // experts with at least this many tokens go to the matrix-core kernel (tiles of 64)
     float *y;       // rows of dropped tokens are zeroed (may be nullptr)
     int d_model;
 };
@@ -751,27 +1036,37 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
     // each thread owns a contiguous chunk of experts
     const int chunk = (E + nthr - 1) / nthr;
     const int e0 = min(E, tid * chunk), e1 = min(E, e0 + chunk);
-    int s_tok = 0, s_act = 0, s_wi = 0, s_wo = 0;
+    int s_tok = 0, s_act = 0, s_wi = 0, s_wo = 0, s_mm = 0;
     for (int e = e0; e < e1; e++) {
         const int n = cnt[e];
         s_tok += n;
         s_act += n > 0;
-        s_wi += (n + a.tb_wi - 1) / a.tb_wi;
-        s_wo += (n + a.tb_wo - 1) / a.tb_wo;
+        if (n >= a.mm_min) {
+            s_mm += (n + kMmTokens - 1) / kMmTokens;
+        } else {
+            s_wi += (n + a.tb_wi - 1) / a.tb_wi;
+            s_wo += (n + a.tb_wo - 1) / a.tb_wo;
+        }
     }
-    int tot_tok, tot_act, tot_wi, tot_wo, tot_drop;
+    int tot_tok, tot_act, tot_wi, tot_wo, tot_mm, tot_drop;
     int p_tok = block_exclusive_scan(s_tok, tmp, tot_tok);
     block_exclusive_scan(s_act, tmp, tot_act);
     int p_wi = block_exclusive_scan(s_wi, tmp, tot_wi);
     int p_wo = block_exclusive_scan(s_wo, tmp, tot_wo);
+    int p_mm = block_exclusive_scan(s_mm, tmp, tot_mm);
     block_exclusive_scan(dropped, tmp, tot_drop);
     for (int e = e0; e < e1; e++) {
         const int n = cnt[e];
         a.tok_off[e] = p_tok;
-        for (int i = 0; i * a.tb_wi < n; i++)
-            a.items_wi[p_wi++] = Item{e, p_tok + i * a.tb_wi, min(a.tb_wi, n - i * a.tb_wi), 0};
-        for (int i = 0; i * a.tb_wo < n; i++)
-            a.items_wo[p_wo++] = Item{e, p_tok + i * a.tb_wo, min(a.tb_wo, n - i * a.tb_wo), 0};
+        if (n >= a.mm_min) {
+            for (int i = 0; i * kMmTokens < n; i++)
+                a.items_mm[p_mm++] = Item{e, p_tok + i * kMmTokens, min(kMmTokens, n - i * kMmTokens), 0};
+        } else {
+            for (int i = 0; i * a.tb_wi < n; i++)
+                a.items_wi[p_wi++] = Item{e, p_tok + i * a.tb_wi, min(a.tb_wi, n - i * a.tb_wi), 0};
+            for (int i = 0; i * a.tb_wo < n; i++)
+                a.items_wo[p_wo++] = Item{e, p_tok + i * a.tb_wo, min(a.tb_wo, n - i * a.tb_wo), 0};
+        }
         cnt[e] = p_tok;  // becomes the expert's write cursor
         p_tok += n;
     }
@@ -782,7 +1077,10 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
         a.counters[2] = tot_act;
         a.counters[3] = tot_wi;
         a.counters[4] = tot_wo;
-        a.counters[5] = 0; a.counters[6] = 0; a.counters[7] = 0;
+        a.counters[5] = 0; a.counters[6] = 0;  // work hand-out of the two scalar products
+        a.counters[7] = tot_mm;
+        a.counters[8] = 0; a.counters[9] = 0;  // work hand-out of the two matrix-core products
+        for (int i = 10; i < kLayerCounters; i++) a.counters[i] = 0;
     }
     __syncthreads();
 
@@ -1001,7 +1299,7 @@ struct ProductPlan {
 // Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
 // matrices with the lane-per-row kernel (compressed path).
 qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p,
-                         int n_order = 0)
+                         int n_order = 0, int force_blocks = 0)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
@@ -1055,10 +1353,11 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     int best_t = 64, best_b = 1;
     double best_score = -1.0;
     for (int b = 1; b <= 64; b++) {
+        if (force_blocks > 0 && b != std::min(force_blocks, 64)) continue;
         for (int t = 64; t <= max_threads; t += 64) {
             const long long nl = (long long)b * t;
             const int rpl = (int)((rows + nl - 1) / nl);
-            if (rpl < want_rpl && !(b == 1 && t == 64)) continue;
+            if (rpl < want_rpl && force_blocks <= 0 && !(b == 1 && t == 64)) continue;
             const double fill = (double)rows / ((double)nl * rpl);
             // prefer full workgroups (occupancy) and few blocks (less restaging)
             const double score = fill * std::min(1.0, (double)t / (0.625 * max_threads)) - 0.002 * b;
@@ -1148,6 +1447,56 @@ qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run,
     return a.epilogue ? launch_product_as<kDictRun, 1>(a, p, s) : launch_product_as<kDictRun, 0>(a, p, s);
 }
 
+// Which experts of a layer go to the matrix-core kernel, and its launch shape.
+struct MmPlan {
+    int min_tokens = 0x7FFFFFFF;  // experts with at least this many tokens; INT_MAX = path off
+    int grid = 0;
+    size_t smem = 0;
+};
+
+void mm_rows(int rows, int *row_blocks, int *rows_per_block)
+{
+    const int nb = (rows + kMmThreads - 1) / kMmThreads;
+    const int per = (rows + nb - 1) / nb;
+    *row_blocks = nb;
+    *rows_per_block = std::min(kMmThreads, (per + 63) / 64 * 64);
+}
+
+qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, bool x_aligned, MmPlan *mp)
+{
+    *mp = MmPlan{};
+    DeviceInfo di;
+    const qmoe_status st = device_info(&di);
+    if (st != QMOE_OK) return st;
+    const Tuning &tu = tuning();
+    const int n_order = (int)d->order_table.size();
+    const bool fits = mm_lds_bytes(n_order) <= (size_t)di.max_lds;
+    // 16-byte activation loads: widths divisible by eight, aligned base
+    if (code_order != 1 || n_order == 0 || d->max_nonzeros > kRunMaxNonzeros || !fits || (d_model % 8) ||
+        (d_ff % 8) || !x_aligned || tu.mfma_min_tokens < 0)
+        return QMOE_OK;
+    mp->min_tokens = tu.mfma_min_tokens > 0 ? tu.mfma_min_tokens : kMmMinTokensDefault;
+    mp->grid = di.cus;
+    mp->smem = mm_lds_bytes(n_order);
+    return QMOE_OK;
+}
+
+qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
+{
+    mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
+    if (a.epilogue) {
+        const qmoe_status st = allow_lds(k_product_mm<1>, mp.smem);
+        if (st != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_product_mm<1>, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
+    } else {
+        const qmoe_status st = allow_lds(k_product_mm<0>, mp.smem);
+        if (st != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_product_mm<0>, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
+    }
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
+}
+
 qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
 {
     if (!d || !W) return QMOE_E_INVALID_ARG;
@@ -1187,7 +1536,7 @@ qmoe_status layer_limits(int n_experts, int d_model, int d_ff, int n_tokens)
 
 struct LayerPtrs {
     int *tok_off, *perm, *counters;
-    Item *items_wi, *items_wo;
+    Item *items_wi, *items_wo, *items_mm;
     uint16_t *hidden;
 };
 
@@ -1196,11 +1545,12 @@ LayerPtrs layer_ptrs(void *ws, const qmoe_ws_layout &l)
     unsigned char *b = static_cast<unsigned char *>(ws);
     return LayerPtrs{reinterpret_cast<int *>(b + l.tok_off), reinterpret_cast<int *>(b + l.perm),
                      reinterpret_cast<int *>(b + l.counters), reinterpret_cast<Item *>(b + l.items_wi),
-                     reinterpret_cast<Item *>(b + l.items_wo), reinterpret_cast<uint16_t *>(b + l.hidden)};
+                     reinterpret_cast<Item *>(b + l.items_wo), reinterpret_cast<Item *>(b + l.items_mm),
+                     reinterpret_cast<uint16_t *>(b + l.hidden)};
 }
 
 qmoe_status launch_dispatch(const int32_t *expert_idx, int n_tokens, int n_experts, int d_model,
-                            const LayerPtrs &lp, int tb_wi, int tb_wo, float *y, hipStream_t s)
+                            const LayerPtrs &lp, int tb_wi, int tb_wo, int mm_min, float *y, hipStream_t s)
 {
     DispatchArgs da;
     da.expert_idx = expert_idx;
@@ -1211,8 +1561,10 @@ qmoe_status launch_dispatch(const int32_t *expert_idx, int n_tokens, int n_exper
     da.counters = lp.counters;
     da.items_wi = lp.items_wi;
     da.items_wo = lp.items_wo;
+    da.items_mm = lp.items_mm;
     da.tb_wi = tb_wi;
     da.tb_wo = tb_wo;
+    da.mm_min = mm_min;
     da.y = y;
     da.d_model = d_model;
     const size_t smem = sizeof(int) * ((size_t)n_experts + 32);
@@ -1333,9 +1685,10 @@ qmoe_status qmoe_moe_layer_ws_layout(int n_experts, int d_model, int d_ff, int n
     size_t off = 0;
     out->tok_off = off;  off = align_up(off + sizeof(int) * ((size_t)n_experts + 1), 256);
     out->perm = off;     off = align_up(off + sizeof(int) * (size_t)n_tokens, 256);
-    out->counters = off; off = align_up(off + sizeof(int) * 8, 256);
+    out->counters = off; off = align_up(off + sizeof(int) * kLayerCounters, 256);
     out->items_wi = off; off = align_up(off + sizeof(Item) * (size_t)n_tokens, 256);
     out->items_wo = off; off = align_up(off + sizeof(Item) * (size_t)n_tokens, 256);
+    out->items_mm = off; off = align_up(off + sizeof(Item) * (size_t)n_tokens, 256);
     out->hidden = off;   off = align_up(off + sizeof(uint16_t) * (size_t)n_tokens * (size_t)d_ff, 256);
     out->total = off;
     return QMOE_OK;
@@ -1347,20 +1700,26 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
     return qmoe_moe_layer_ws_layout(n_experts, d_model, d_ff, n_tokens, &l) == QMOE_OK ? l.total : 0;
 }
 
-qmoe_status qmoe_moe_dispatch(const int32_t *expert_idx, int n_tokens, int n_experts, int d_model, int d_ff,
-                              void *workspace, size_t workspace_bytes, void *stream)
+qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t *expert_idx, int n_tokens,
+                              int n_experts, int d_model, int d_ff, void *workspace, size_t workspace_bytes,
+                              void *stream)
 {
     qmoe_ws_layout l;
     qmoe_status st = qmoe_moe_layer_ws_layout(n_experts, d_model, d_ff, n_tokens, &l);
     if (st != QMOE_OK) return st;
-    if (!expert_idx) return QMOE_E_INVALID_ARG;
+    if (!d || !expert_idx) return QMOE_E_INVALID_ARG;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
+    if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
+    const bool run = d->max_nonzeros <= kRunMaxNonzeros;
+    const int n_order = code_order ? (int)d->order_table.size() : 0;
     ProductPlan pwi, pwo;
-    if ((st = plan_product(d_ff, d_model, true, n_tokens, &pwi)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, true, n_tokens, &pwo)) != QMOE_OK) return st;
+    MmPlan mp;
+    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
+    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
+    if ((st = plan_mm(d, code_order, d_model, d_ff, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
-                           pwo.tb_max, nullptr, static_cast<hipStream_t>(stream));
+                           pwo.tb_max, mp.min_tokens, nullptr, static_cast<hipStream_t>(stream));
 }
 
 qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
@@ -1379,14 +1738,18 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
     ProductPlan pwi, pwo;
-    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order)) != QMOE_OK) return st;
+    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
+    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
+    MmPlan mp;
+    if ((st = plan_mm(d, code_order, d_model, d_ff, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
+        return st;
+    const bool mm = mp.min_tokens <= n_tokens;  // otherwise no expert can reach the threshold
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
     const int phases = tuning().phases > 0 ? tuning().phases : 7;
     if (phases & 1)
-        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
-            QMOE_OK)
+        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max,
+                                  mp.min_tokens, y, s)) != QMOE_OK)
             return st;
 
     ProductArgs a{};
@@ -1411,6 +1774,14 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwi.blocks_per_pass;
     a.tb_max = pwi.tb_max;
     a.lds_dict_entries = pwi.lds_dict_entries;
+    if ((phases & 2) && mm) {
+        // crowded experts first: their tiles are the long items
+        ProductArgs am = a;
+        am.items = lp.items_mm;
+        am.n_items_dev = lp.counters + 7;
+        am.work_counter = lp.counters + 8;
+        if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+    }
     a.work_counter = lp.counters + 5;
     if (phases & 2)
         if ((st = launch_product(a, pwi, run, s)) != QMOE_OK) return st;
@@ -1431,6 +1802,13 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.blocks_per_pass = pwo.blocks_per_pass;
     a.tb_max = pwo.tb_max;
     a.lds_dict_entries = pwo.lds_dict_entries;
+    if ((phases & 4) && mm) {
+        ProductArgs am = a;
+        am.items = lp.items_mm;
+        am.n_items_dev = lp.counters + 7;
+        am.work_counter = lp.counters + 9;
+        if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+    }
     a.work_counter = lp.counters + 6;
     if (phases & 4) return launch_product(a, pwo, run, s);
     return QMOE_OK;
@@ -1455,8 +1833,8 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint1
     const LayerPtrs lp = layer_ptrs(workspace, l);
     const int phases = tuning().phases > 0 ? tuning().phases : 7;
     if (phases & 1)
-        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max, y, s)) !=
-            QMOE_OK)
+        if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max,
+                                  0x7FFFFFFF, y, s)) != QMOE_OK)
             return st;
     DenseArgs a{};
     a.n_experts = n_experts;

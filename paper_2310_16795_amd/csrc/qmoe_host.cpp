@@ -99,7 +99,10 @@ void build_device_order(qmoe_dict *d)
     for (int k = 0; k < n; k++) {
         if (device_of[k] >= 0) continue;
         device_of[k] = next++;
-        table.push_back(d->run[k]);
+        // fields right-aligned like those of the groups: unused ones (0) come first
+        uint32_t e = d->run[k];
+        while ((e >> 8) != 0u && (e >> 24) == 0u) e = (e & 0xFFu) | ((e & 0xFFFFFF00u) << 8);
+        table.push_back(e);
     }
     int absent = -1;  // codes that name no entry all map to one empty single entry
     if (n < kTableEntries) {
@@ -416,6 +419,9 @@ qmoe_status qmoe_set_tuning(const char *key, int value)
     else if (!std::strcmp(key, "lds_dict_entries")) t.lds_dict_entries = value;
     else if (!std::strcmp(key, "grid_per_cu")) t.grid_per_cu = value;
     else if (!std::strcmp(key, "host_threads")) t.host_threads = value;
+    else if (!std::strcmp(key, "blocks_first")) t.blocks_first = value;
+    else if (!std::strcmp(key, "blocks_second")) t.blocks_second = value;
+    else if (!std::strcmp(key, "mfma_min_tokens")) t.mfma_min_tokens = value;
     else if (!std::strcmp(key, "phases")) t.phases = value;
     else return QMOE_E_INVALID_ARG;
     return QMOE_OK;

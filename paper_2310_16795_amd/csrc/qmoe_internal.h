@@ -55,6 +55,9 @@ struct Tuning {
     int lds_dict_entries = 0;  // 0 = heuristic, -1 = keep the table in L2 only
     int grid_per_cu = 0;
     int host_threads = 0;
+    int blocks_first = 0;   // forced blocks per matrix pass, first / single product
+    int blocks_second = 0;  // same, second product of a layer
+    int mfma_min_tokens = 0;  // 0 = heuristic, -1 = never use the matrix-core kernel
     int phases = 0;  // bit 0 dispatch, bit 1 first product, bit 2 second product; 0 = all
 };
 Tuning &tuning();

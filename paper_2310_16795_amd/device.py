@@ -123,8 +123,9 @@ def read_workspace(workspace: torch.Tensor, n_experts: int, d_model: int, d_ff: 
     return {
         "tok_off": view(l.tok_off, n_experts + 1, np.int32),
         "perm": view(l.perm, n_tokens, np.int32),
-        "counters": view(l.counters, 8, np.int32),
+        "counters": view(l.counters, 16, np.int32),
         "items_wi": view(l.items_wi, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
         "items_wo": view(l.items_wo, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
+        "items_mm": view(l.items_mm, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
         "hidden": view(l.hidden, n_tokens * d_ff, np.uint16).reshape(n_tokens, d_ff),
     }

@@ -147,16 +147,18 @@ def test_library_encoder_feeds_the_kernels(gpu, oracle_dict):
     dd.close()
 
 
+@pytest.mark.parametrize("order", [0, 1])
 @pytest.mark.parametrize("E,T,seed", [(1, 5, 1), (7, 1, 2), (16, 100, 3), (300, 1000, 4), (2048, 2048, 5), (64, 5000, 6)])
-def test_dispatch_bit_exact(gpu, E, T, seed):
+def test_dispatch_bit_exact(gpu, E, T, seed, order):
     rng = np.random.default_rng(seed)
     idx = rng.integers(0, E, T).astype(np.int32)
     if T > 50:
         idx[rng.integers(0, T, 5)] = np.array([-1, E, E + 7, -5, 2 ** 30], dtype=np.int32)  # dropped tokens
         idx[10:40] = idx[10]  # one crowded expert
     d_model, d_ff = 64, 128
+    dd = dev.DeviceDict(device=gpu)
     ws = torch.empty(q.qmoe_moe_layer_workspace(E, d_model, d_ff, T), dtype=torch.uint8, device=gpu)
-    q.qmoe_moe_dispatch(torch.from_numpy(idx).to(gpu), E, d_model, d_ff, ws)
+    q.qmoe_moe_dispatch(dd.handle, order, torch.from_numpy(idx).to(gpu), E, d_model, d_ff, ws)
     torch.cuda.synchronize()
     got = dev.read_workspace(ws, E, d_model, d_ff, T)
     tok_off, perm = oracle.dispatch(idx, E)
@@ -166,14 +168,28 @@ def test_dispatch_bit_exact(gpu, E, T, seed):
     counts = np.diff(tok_off)
     assert got["counters"][0] == n_valid and got["counters"][1] == T - n_valid
     assert got["counters"][2] == int((counts > 0).sum())
+    n_mm = got["counters"][7]
+    if order == 0:
+        assert n_mm == 0  # crowded experts only leave the scalar kernel with device-order streams
+    elif T > 50:
+        assert n_mm > 0
+    crowded = set()
+    for e, slot0, ntok, _ in got["items_mm"][:n_mm]:
+        assert 1 <= ntok <= 64
+        crowded.add(int(e))
+    for e in crowded:  # an expert is wholly on one side, with full tiles except the last
+        sizes = [int(n) for ee, _, n, _ in got["items_mm"][:n_mm] if ee == e]
+        assert sum(sizes) == counts[e] and all(n == 64 for n in sizes[:-1])
     for key, n_items in (("items_wi", got["counters"][3]), ("items_wo", got["counters"][4])):
-        items = got[key][:n_items]
         covered = np.zeros(n_valid, dtype=np.int32)
-        for e, slot0, ntok, _ in items:
-            assert counts[e] > 0 and 1 <= ntok <= 8  # never an expert without tokens
-            assert tok_off[e] <= slot0 and slot0 + ntok <= tok_off[e + 1]
-            covered[slot0:slot0 + ntok] += 1
+        for limit, items in ((8, got[key][:n_items]), (64, got["items_mm"][:n_mm])):
+            for e, slot0, ntok, _ in items:
+                assert counts[e] > 0 and 1 <= ntok <= limit  # never an expert without tokens
+                assert tok_off[e] <= slot0 and slot0 + ntok <= tok_off[e + 1]
+                covered[slot0:slot0 + ntok] += 1
         assert np.all(covered == 1)
+        assert not crowded & {int(e) for e, *_ in got[key][:n_items]}
+    dd.close()
 
 
 def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None):
@@ -227,6 +243,43 @@ def test_small_layer_every_token(gpu, ddict, oracle_dict, d_model, d_ff, order):
     # same call again: bitwise identical (fixed reduction order)
     y2, _ = _run_layer(layer, ddict, x, idx, gpu, gate)
     assert np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(136, 600), (520, 72)])
+def test_crowded_experts_take_the_matrix_core_kernel(gpu, ddict, oracle_dict, d_model, d_ff):
+    """Experts with 8..130 tokens (tiles of 64: full, one short, one over; 32-token blocks
+    likewise), more than 512 rows on one side (two row blocks), widths that are no
+    multiple of the 64-column step, gates, a dropped token.  Every token is checked."""
+    counts = [130, 65, 64, 33, 32, 31, 8, 7, 1, 0]
+    idx = np.concatenate([np.full(n, e, dtype=np.int32) for e, n in enumerate(counts)])
+    np.random.default_rng(11).shuffle(idx)
+    idx = np.concatenate([idx, np.array([-1], dtype=np.int32)])
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=len(counts), d_model=d_model, d_ff=d_ff,
+                                                 n_tokens=idx.size)
+    x = w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    gate = np.random.default_rng(12).uniform(0.2, 1.0, idx.size)
+    y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
+    n_mm = wsout["counters"][7]
+    assert n_mm == 3 + 2 + 1 + 1 + 1 + 1 + 1  # tiles of the experts with at least 8 tokens
+    assert sorted(int(n) for _, _, n, _ in wsout["items_mm"][:n_mm]) == sorted([64, 64, 2, 64, 1, 64, 33, 32, 31, 8])
+    good = [t for t in range(idx.size) if idx[t] >= 0]
+    assert not y[-1].any()
+    _check_layer(w, idx, x, y, wsout, good, gate)
+    y2, _ = _run_layer(layer, ddict, x, idx, gpu, gate)
+    assert np.array_equal(y, y2)
+    # every expert with two tokens or more through the matrix cores, then none: same answers
+    try:
+        q.qmoe_set_tuning("mfma_min_tokens", 2)
+        y3, ws3 = _run_layer(layer, ddict, x, idx, gpu, gate)
+        assert ws3["counters"][7] == n_mm + 1
+        _check_layer(w, idx, x, y3, ws3, good, gate)
+        q.qmoe_set_tuning("mfma_min_tokens", -1)
+        y4, ws4 = _run_layer(layer, ddict, x, idx, gpu, gate)
+        assert ws4["counters"][7] == 0
+        _check_layer(w, idx, x, y4, ws4, good, gate)
+    finally:
+        q.qmoe_set_tuning("mfma_min_tokens", 0)
 
 
 def test_layer_drops_tokens_with_bad_expert_index(gpu, ddict, oracle_dict):

@@ -167,9 +167,10 @@ def test_validate_detects_corruption(lib_dict):
 
 def test_layer_workspace_layout_and_limits():
     l = q.qmoe_moe_layer_ws_layout(128, 768, 3072, 128)
-    offs = [l.tok_off, l.perm, l.counters, l.items_wi, l.items_wo, l.hidden, l.total]
+    offs = [l.tok_off, l.perm, l.counters, l.items_wi, l.items_wo, l.items_mm, l.hidden, l.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert l.perm - l.tok_off >= 4 * 129 and l.items_wo - l.items_wi >= 16 * 128
+    assert l.hidden - l.items_mm >= 16 * 128 and l.items_wi - l.counters >= 4 * 16
     assert l.total - l.hidden >= 2 * 128 * 3072
     assert q.qmoe_moe_layer_workspace(128, 768, 3072, 128) == l.total
     assert q.qmoe_moe_layer_workspace(0, 768, 3072, 128) == 0
@@ -198,7 +199,8 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     assert L.qmoe_dict_upload(lib_dict, None, 0, None) == -1
     assert L.qmoe_dict_upload(lib_dict, 256, 10, None) == -2
     assert L.qmoe_bf16_layer_forward(256, 256, 4, 12, 16, 256, 256, None, 4, 256, 256, 1 << 30, None) == -1
-    assert L.qmoe_moe_dispatch(256, 4, 4, 8, 16, 256, 16, None) == -5                   # workspace too small
+    assert L.qmoe_moe_dispatch(lib_dict, 0, 256, 4, 4, 8, 16, 256, 16, None) == -5
+    assert L.qmoe_moe_dispatch(None, 0, 256, 4, 4, 8, 16, 256, 1 << 30, None) == -1                   # workspace too small
 
 
 def _decode_device_code(code, table, n_groups):
