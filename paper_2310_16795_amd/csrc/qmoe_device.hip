@@ -81,6 +81,7 @@ struct ProductArgs {
     int n_groups, n_order;
     int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
     int mm_row_blocks, mm_rows_per_block;  // matrix-core kernel: workgroups per matrix, rows each takes (<= 512)
+    int mm_stagger;           // matrix-core kernel: the two wavefronts of a SIMD half a step apart
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -703,11 +704,32 @@ using lp_u32x4 = const __attribute__((address_space(3))) u32x4 *;
 using lp_i32 = const __attribute__((address_space(3))) int *;
 using lp_f32 = const __attribute__((address_space(3))) float *;
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global
+// memory, which makes every wavefront wait for all its loads in flight: the prefetches
+// of codewords and activations would then be exposed at every step.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Table entry of the codeword at index `at` (0..15) of the window c0..c3, n0..n3 (anything
+// when at > 15: not used then).  A macro, so that the window stays in registers.
+#define QMOE_MM_ENTRY_AT(dst, at)                                                                       \
+    do {                                                                                                \
+        const bool hi8_ = ((at) & 8u) != 0u, hi4_ = ((at) & 4u) != 0u;                                  \
+        const uint32_t lo_ = hi8_ ? (hi4_ ? n2 : n0) : (hi4_ ? c2 : c0);                                \
+        const uint32_t hi_ = hi8_ ? (hi4_ ? n3 : n1) : (hi4_ ? c3 : c1);                                \
+        /* bytes 2s, 2s+1 of {hi, lo}: selector 0x0c0c0100 + 0x0202 * s */                              \
+        const uint32_t code_ = __builtin_amdgcn_perm(hi_, lo_, 0x0c0c0100u + 0x0202u * ((at) & 3u));    \
+        (dst) = order_entry(table, code_, (uint32_t)a.n_groups, (uint32_t)a.n_order);                   \
+    } while (0)
+
 // MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
 // rings and the two activation buffers.
 template <int MB, int EPI>
 __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
-                                        lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s)
+                                        lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s,
+                                        int lag)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -720,11 +742,16 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         const int tok = a.perm ? a.perm[slot0 + tx] : slot0 + tx;
         xrow = a.x_by_slot ? (size_t)(slot0 + tx) : (size_t)tok;
     }
-    const uintptr_t xsrc = reinterpret_cast<uintptr_t>(a.x) + 2 * (xrow * (size_t)a.ldx + 8 * (size_t)seg);
-    auto load_x = [&](int kc) -> u32x4 {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (x_live && kc + 8 * seg + 8 <= a.cols) v = *(gp_u32x4)(xsrc + 2 * (uintptr_t)kc);
-        return v;
+    // Loads are unconditional (a lane without a token, or past the last column, reads a
+    // valid address and drops the value when it stages it): a load under a branch would
+    // be waited for at the end of the branch instead of staying in flight.
+    const bool x_ok = x_live && 8 * seg + 8 <= a.cols;
+    const uintptr_t xsrc =
+        reinterpret_cast<uintptr_t>(a.x) + (x_ok ? 2 * (xrow * (size_t)a.ldx + 8 * (size_t)seg) : (size_t)0);
+    const int x_last = x_ok ? a.cols - 8 * seg - 8 : 0;  // last column offset this thread may read at
+    auto load_x = [&](int kc) -> u32x4 { return *(gp_u32x4)(xsrc + 2 * (uintptr_t)min(kc, x_last)); };
+    auto keep_x = [&](const u32x4 &v, int kc) -> u32x4 {
+        return (x_ok && kc <= x_last) ? v : u32x4{0u, 0u, 0u, 0u};
     };
     const uint32_t x_slot = xt + (uint32_t)(tx * kMmXRowBytes + 16 * seg);  // in buffer 0
 
@@ -751,7 +778,15 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     // decoder picks codewords from (index sub = 0..15), `fut` is in flight.  Pieces past the
     // lane's last one re-read the last (never used: `left` runs out first).
     auto piece = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
-    u32x4 cur = piece(pp), nxt = piece(pp + 16u), fut = piece(pp + 32u);
+    // (plain scalars: selecting between members of two vectors makes the compiler keep
+    // the vectors in memory)
+    uint32_t c0, c1, c2, c3, n0, n1, n2, n3;
+    {
+        const u32x4 a0 = piece(pp), a1 = piece(pp + 16u);
+        c0 = a0.x; c1 = a0.y; c2 = a0.z; c3 = a0.w;
+        n0 = a1.x; n1 = a1.y; n2 = a1.z; n3 = a1.w;
+    }
+    u32x4 fut = piece(pp + 32u);
     int pos = 0;  // column where the next codeword starts
     const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
 
@@ -763,48 +798,64 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[mb][nb][v] = 0.0f;
 
-    // activations: step c is read from LDS buffer c & 1, step c + 1 is written there during
-    // step c, steps c + 2 and c + 3 are in registers / in flight
-    *(lw_u32x4)(uintptr_t)x_slot = load_x(0);
-    u32x4 xr0 = load_x(kMmKc), xr1 = load_x(2 * kMmKc);
+    // Activations: step c is read from LDS buffer c & 1; step c + 1 is in flight to a
+    // register during step c and staged at its end.
+    *(lw_u32x4)(uintptr_t)x_slot = keep_x(load_x(0), 0);
+    u32x4 xr = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
-    __syncthreads();  // token ids, gates and the first activation step are in place
 
     const uint32_t wfrag = wt + (uint32_t)((64 * wave + l32) * kMmWRowBytes + 8 * lhi);
     const uint32_t xfrag0 = xt + (uint32_t)(l32 * kMmXRowBytes + 16 * lhi);
     const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+
+    // The two wavefronts that share a SIMD work half a step apart, so that one decodes
+    // (vector ALU, LDS) while the other multiplies (matrix cores): both run the same
+    // sequence -- decode, barrier, multiply and stage, barrier -- but the trailing one
+    // (lag 1) passes one barrier before it starts and the leading one passes one after it
+    // has finished.
+    __syncthreads();  // token ids, gates and the first activation step are in place
+    if (lag != 0) lds_barrier();
     for (int c = 0; c < nsteps; c++) {
         const int kc = c * kMmKc, kend = kc + kMmKc;
-        const uint32_t other = (uint32_t)((c + 1) & 1);
-        // stage the next step's activations, fetch those three steps on
-        *(lw_u32x4)(uintptr_t)(x_slot + other * (uint32_t)(kMmTokens * kMmXRowBytes)) = xr0;
-        xr0 = xr1;
-        xr1 = load_x(kc + 3 * kMmKc);
-        // the half of the ring the previous step multiplied becomes columns kend .. kend+63
+        // ---- decode step c: until every lane has passed column kend; lanes that are there
+        // already keep going while their next codeword fits into the ring.
+        // The half of the ring the previous step multiplied becomes columns kend .. kend+63.
 #pragma unroll
-        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + other * kMmKc))[i] = 0ull;
-
-        // Decode until every lane has passed column kend; lanes that are there already keep
-        // going while their next codeword fits into the ring.  No branches inside: a lane
-        // that sits out decodes an empty entry into the spare bytes after its ring.
-        for (;;) {
-            if (sub >= 8u) {  // slide the window (seldom more than once per step)
-                sub -= 8u;
-                pp += 16u;
-                cur = nxt;
-                nxt = fut;
-                fut = piece(pp + 32u);
+        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + (uint32_t)(((c + 1) & 1) * kMmKc)))[i] = 0ull;
+        do {
+            // Slide the window by one piece where its first half is used up (once per step
+            // as a rule; the loop comes back only for lanes that use up a whole window in one
+            // step).  The other lanes fetch the piece they already wait for again, so that
+            // the load is unconditional and stays in flight until the next slide.
+            {
+                const bool s8 = sub >= 8u;
+                sub -= s8 ? 8u : 0u;
+                pp += s8 ? 16u : 0u;
+                const uint32_t f0 = fut.x, f1 = fut.y, f2 = fut.z, f3 = fut.w;
+                c0 = s8 ? n0 : c0; c1 = s8 ? n1 : c1; c2 = s8 ? n2 : c2; c3 = s8 ? n3 : c3;
+                n0 = s8 ? f0 : n0; n1 = s8 ? f1 : n1; n2 = s8 ? f2 : n2; n3 = s8 ? f3 : n3;
+                fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);
             }
+            // The next step's activations, staged after this step's product; fetched here,
+            // after the window's wait, so that a whole step hides the latency of both loads
+            // (the empty asm keeps the compiler from moving the load up, in front of that wait).
+            {
+                int k_next = kend;
+                asm volatile("" : "+s"(k_next));
+                xr = load_x(k_next);
+            }
+            // No branches inside the inner loop: a lane that sits out decodes an empty entry
+            // into the spare bytes after its ring.  The look-up of the next codeword is
+            // issued before the current one is applied.
+            uint32_t ent_next;
+            QMOE_MM_ENTRY_AT(ent_next, sub);
             while (__any(left != 0u && pos < kend && sub < 16u)) {
                 const bool go = left != 0u && pos <= kc + kMmAhead && sub < 16u;
-                const bool hi8 = (sub & 8u) != 0u, hi4 = (sub & 4u) != 0u;
-                const uint32_t lo = hi8 ? (hi4 ? nxt.z : nxt.x) : (hi4 ? cur.z : cur.x);
-                const uint32_t hi = hi8 ? (hi4 ? nxt.w : nxt.y) : (hi4 ? cur.w : cur.y);
-                // bytes 2s, 2s+1 of {hi, lo}: selector 0x0c0c0100 + 0x0202 * s
-                const uint32_t code = __builtin_amdgcn_perm(hi, lo, 0x0c0c0100u + 0x0202u * (sub & 3u));
-                uint32_t ent = order_entry(table, code, (uint32_t)a.n_groups, (uint32_t)a.n_order);
-                ent = go ? ent : 0u;
+                const uint32_t ent = go ? ent_next : 0u;
+                left -= go ? 1u : 0u;
+                sub += go ? 1u : 0u;
+                QMOE_MM_ENTRY_AT(ent_next, sub);
                 const uint32_t base = go ? (uint32_t)pos : (uint32_t)kMmRing;
                 const uint32_t mask = go ? (uint32_t)(kMmRing - 1) : 0xFFu;
                 // fields are right-aligned in device-order entries: an unused one (0) comes
@@ -816,15 +867,14 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                     *(lw_u8)(uintptr_t)(wrow + col) = (unsigned char)((f & 6u) << 5);  // 0, 0x40 (+2.0), 0xC0 (-2.0)
                 }
                 pos += (int)((ent & 0xFFu) >> 3);
-                left -= go ? 1u : 0u;
-                sub += go ? 1u : 0u;
             }
-            if (!__any(left != 0u && pos < kend)) break;
-        }
+        } while (__any(left != 0u && pos < kend));
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        lds_barrier();
 
+        // ---- multiply step c
         const uint32_t xf = xfrag0 + (uint32_t)((c & 1) * kMmTokens * kMmXRowBytes);
         const uint32_t wf = wfrag + (uint32_t)((c & 1) * kMmKc);
 #pragma unroll
@@ -848,8 +898,16 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        __syncthreads();  // next step's activations visible; this step's reads of the other buffer are done
+
+        // ---- stage this thread's part of step c + 1 of the activations: the buffer held
+        // step c - 1, which every wavefront has finished by now (the trailing ones one
+        // barrier ago), and nobody reads step c + 1 before two more barriers
+        *(lw_u32x4)(uintptr_t)(x_slot + (uint32_t)(((c + 1) & 1) * kMmTokens * kMmXRowBytes)) =
+            keep_x(xr, kend);
+        lds_barrier();
     }
+    if (lag == 0) lds_barrier();
+#undef QMOE_MM_ENTRY_AT
 
     // accumulator v of lane l: token 32*mb + 8*(v/4) + 4*(l/32) + v%4, row 32*nb + l%32 of the wavefront's 64
 #pragma unroll
@@ -896,6 +954,20 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     if (total <= 0) return;
     for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
 
+    // Order of arrival of this wavefront on its SIMD (SIMD_ID: bits 5:4 of HW_ID): the
+    // first and the second wavefront of a SIMD take opposite halves of the step.  (The
+    // tile's first bytes serve as counters; the first item clears them again.)
+    int lag = 0;
+    if (a.mm_stagger) {
+        int *simd_count = reinterpret_cast<int *>(wt);
+        if (threadIdx.x < 4) simd_count[threadIdx.x] = 0;
+        __syncthreads();
+        const int simd = (int)__builtin_amdgcn_s_getreg(4 | (4 << 6) | (1 << 11));
+        int rank = 0;
+        if ((threadIdx.x & 63) == 0) rank = atomicAdd(&simd_count[simd & 3], 1);
+        lag = __builtin_amdgcn_readfirstlane(rank) & 1;
+    }
+
     for (;;) {
         __syncthreads();  // everyone is done with the previous item
         if (threadIdx.x == 0) {
@@ -921,10 +993,10 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
         const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, xt_addr = (uint32_t)(uintptr_t)(lw_u8)xt;
         if (ntok <= 32)
             mm_item<1, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
-                            (lp_f32)gate_s);
+                            (lp_f32)gate_s, lag);
         else
             mm_item<2, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
-                            (lp_f32)gate_s);
+                            (lp_f32)gate_s, lag);
     }
 }
 
@@ -1036,25 +1108,39 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
     // each thread owns a contiguous chunk of experts
     const int chunk = (E + nthr - 1) / nthr;
     const int e0 = min(E, tid * chunk), e1 = min(E, e0 + chunk);
-    int s_tok = 0, s_act = 0, s_wi = 0, s_wo = 0, s_mm = 0;
+    // Work items of the scalar products are listed longest first (tiles of more than four
+    // tokens, then of three or four, of two, of one): handed out in that order, the last
+    // workgroups to finish are busy with short items.
+    auto tile_class = [](int n) { return n > 4 ? 0 : (n > 2 ? 1 : (n == 2 ? 2 : 3)); };
+    int s_tok = 0, s_act = 0, s_mm = 0;
+    int s_wi[4] = {0, 0, 0, 0}, s_wo[4] = {0, 0, 0, 0};
     for (int e = e0; e < e1; e++) {
         const int n = cnt[e];
         s_tok += n;
         s_act += n > 0;
         if (n >= a.mm_min) {
             s_mm += (n + kMmTokens - 1) / kMmTokens;
-        } else {
-            s_wi += (n + a.tb_wi - 1) / a.tb_wi;
-            s_wo += (n + a.tb_wo - 1) / a.tb_wo;
+        } else if (n > 0) {
+            s_wi[tile_class(a.tb_wi)] += n / a.tb_wi;
+            if (n % a.tb_wi) s_wi[tile_class(n % a.tb_wi)]++;
+            s_wo[tile_class(a.tb_wo)] += n / a.tb_wo;
+            if (n % a.tb_wo) s_wo[tile_class(n % a.tb_wo)]++;
         }
     }
-    int tot_tok, tot_act, tot_wi, tot_wo, tot_mm, tot_drop;
+    int tot_tok, tot_act, tot_mm, tot_drop;
     int p_tok = block_exclusive_scan(s_tok, tmp, tot_tok);
     block_exclusive_scan(s_act, tmp, tot_act);
-    int p_wi = block_exclusive_scan(s_wi, tmp, tot_wi);
-    int p_wo = block_exclusive_scan(s_wo, tmp, tot_wo);
     int p_mm = block_exclusive_scan(s_mm, tmp, tot_mm);
     block_exclusive_scan(dropped, tmp, tot_drop);
+    int p_wi[4], p_wo[4], tot_wi = 0, tot_wo = 0;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        int t_wi, t_wo;
+        p_wi[k] = tot_wi + block_exclusive_scan(s_wi[k], tmp, t_wi);
+        p_wo[k] = tot_wo + block_exclusive_scan(s_wo[k], tmp, t_wo);
+        tot_wi += t_wi;
+        tot_wo += t_wo;
+    }
     for (int e = e0; e < e1; e++) {
         const int n = cnt[e];
         a.tok_off[e] = p_tok;
@@ -1062,10 +1148,14 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
             for (int i = 0; i * kMmTokens < n; i++)
                 a.items_mm[p_mm++] = Item{e, p_tok + i * kMmTokens, min(kMmTokens, n - i * kMmTokens), 0};
         } else {
-            for (int i = 0; i * a.tb_wi < n; i++)
-                a.items_wi[p_wi++] = Item{e, p_tok + i * a.tb_wi, min(a.tb_wi, n - i * a.tb_wi), 0};
-            for (int i = 0; i * a.tb_wo < n; i++)
-                a.items_wo[p_wo++] = Item{e, p_tok + i * a.tb_wo, min(a.tb_wo, n - i * a.tb_wo), 0};
+            for (int i = 0; i * a.tb_wi < n; i++) {
+                const int m = min(a.tb_wi, n - i * a.tb_wi);
+                a.items_wi[p_wi[tile_class(m)]++] = Item{e, p_tok + i * a.tb_wi, m, 0};
+            }
+            for (int i = 0; i * a.tb_wo < n; i++) {
+                const int m = min(a.tb_wo, n - i * a.tb_wo);
+                a.items_wo[p_wo[tile_class(m)]++] = Item{e, p_tok + i * a.tb_wo, m, 0};
+            }
         }
         cnt[e] = p_tok;  // becomes the expert's write cursor
         p_tok += n;
@@ -1484,6 +1574,7 @@ qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, b
 qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
 {
     mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
+    a.mm_stagger = tuning().mm_stagger > 0 ? 1 : 0;
     if (a.epilogue) {
         const qmoe_status st = allow_lds(k_product_mm<1>, mp.smem);
         if (st != QMOE_OK) return st;
