@@ -99,22 +99,28 @@ def time_steps(fn, steps, warmup):
     return start.elapsed_time(stop) / steps, wall / steps * 1e3
 
 
+PHASES = (("dispatch", 1), ("first_product_mfma", 8), ("first_product_scalar", 2),
+          ("second_product_mfma", 16), ("second_product_scalar", 4))
+
+
 def time_phases(fn, steps):
-    """Per-kernel durations: the three kernels of a step enqueued one by one with
-    HIP events between them, on the stream they run on."""
+    """Per-kernel durations: the kernels of a step enqueued one by one, in the order a
+    step runs them, with HIP events between them on the stream they run on."""
     import torch
     import paper_2310_16795_amd as q
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    n = len(PHASES)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(steps)]
     for s in range(steps):
         ev[s][0].record()
-        for i, mask in enumerate((1, 2, 4)):
+        for i, (_, mask) in enumerate(PHASES):
             q.qmoe_set_tuning("phases", mask)
             fn()
             ev[s][i + 1].record()
     q.qmoe_set_tuning("phases", 0)
     torch.cuda.synchronize()
-    return [float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)])) for i in range(3)]
+    return {name: float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)]))
+            for i, (name, _) in enumerate(PHASES)}
 
 
 def cpu_baseline(w, idx, x_bits, active, budget_s=12.0):
@@ -198,18 +204,34 @@ def main():
         layer.forward(dd, x, d_idx, y, ws)
 
     ms, wall_ms = time_steps(step, args.steps, args.warmup)
-    t_disp, t_wi, t_wo = time_phases(step, args.steps)
+    kernel_ms = time_phases(step, args.steps)
 
-    # algorithmic bytes: what the method itself has to move once per step
+    # which experts went to the matrix-core kernels (tiles of up to 64 tokens), which to the scalar ones
+    torch.cuda.synchronize()
+    wsout = dev.read_workspace(ws, w.n_experts, w.d_model, w.d_ff, T)
+    crowded = sorted({int(e) for e, _, _, _ in wsout["items_mm"][: wsout["counters"][7]]})
+    few = [e for e in active if e not in set(crowded)]
+
+    # algorithmic bytes: what the method itself has to move once per step -- every active
+    # expert's compressed matrix (codewords + 6 bytes of row metadata) once, activations in, results out
     n_params = 2 * w.d_model * w.d_ff
-    wi_bytes = int(sum(2 * layer.n_codes["wi"][e] + 6 * w.d_ff for e in active))
-    wo_bytes = int(sum(2 * layer.n_codes["wo"][e] + 6 * w.d_model for e in active))
-    weight_bytes = wi_bytes + wo_bytes
-    k_wi = wi_bytes + T * w.d_model * 2 + T * w.d_ff * 2
-    k_wo = wo_bytes + T * w.d_ff * 2 + T * w.d_model * 4
+    def mat_bytes(which, rows, experts):
+        return int(sum(2 * layer.n_codes[which][e] + 6 * rows for e in experts))
+    weight_bytes = mat_bytes("wi", w.d_ff, active) + mat_bytes("wo", w.d_model, active)
+    def kernel_bytes(which, experts):
+        toks = int(sum(counts[e] for e in experts))
+        if which == "wi":
+            return mat_bytes("wi", w.d_ff, experts) + toks * w.d_model * 2 + toks * w.d_ff * 2
+        return mat_bytes("wo", w.d_model, experts) + toks * w.d_ff * 2 + toks * w.d_model * 4
     dict_mode = "0|1" if args.interchange_order else "3"  # template argument: where the table is read from
-    dom = (f"k_product<{dict_mode}, 0> (second product, d_model x d_ff)", t_wo, k_wo) if t_wo >= t_wi else \
-          (f"k_product<{dict_mode}, 1> (first product, d_ff x d_model)", t_wi, k_wi)
+    kernels = {
+        "first_product_scalar": (f"k_product<{dict_mode}, 1> (first product, experts with few tokens)", kernel_bytes("wi", few)),
+        "second_product_scalar": (f"k_product<{dict_mode}, 0> (second product, experts with few tokens)", kernel_bytes("wo", few)),
+        "first_product_mfma": ("k_product_mm<1> (first product, crowded experts)", kernel_bytes("wi", crowded)),
+        "second_product_mfma": ("k_product_mm<0> (second product, crowded experts)", kernel_bytes("wo", crowded)),
+    }
+    dom_key = max(kernels, key=lambda k: kernel_ms[k])
+    dom = (kernels[dom_key][0], kernel_ms[dom_key], kernels[dom_key][1])
     achieved = dom[2] / (dom[1] * 1e-3) / 1e9
 
     # plain copy kernel: what pure streaming reaches here
@@ -225,7 +247,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("first_product" if dom[1] == t_wi else "second_product")
+            traffic = json.load(f).get(dom_key)
 
     result = {
         "metric": "compressed_weight_GBps", "value": weight_bytes / (ms * 1e-3) / 1e9, "unit": "GB/s",
@@ -239,7 +261,12 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
                      "kernel_ms": dom[1], "algorithmic_bytes": dom[2]},
         "hbm_frac_whole_step": weight_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "kernel_ms": {"dispatch": t_disp, "first_product": t_wi, "second_product": t_wo},
+        "kernel_ms": kernel_ms,
+        "kernels": {k: {"name": v[0], "algorithmic_bytes": v[1],
+                        "GBps": (v[1] / (kernel_ms[k] * 1e-3) / 1e9) if kernel_ms[k] > 0 else None}
+                    for k, v in kernels.items()},
+        "experts_on_matrix_cores": len(crowded),
+        "tokens_on_matrix_cores": int(sum(counts[e] for e in crowded)),
         "wall_ms_per_step": wall_ms,
         "compressed_bytes_touched": weight_bytes,
         "compressed_bytes_resident": layer.compressed_bytes,

@@ -243,7 +243,11 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * Enqueues a dispatch kernel and, per product, the scalar kernel for experts with few
  * tokens and (device-order streams, widths divisible by 8, x 16-byte aligned) the
  * matrix-core kernel for crowded ones: an expert's matrix is decoded once per tile of up
- * to 64 tokens there, instead of once per 4.
+ * to 64 tokens there, instead of once per 4.  When both kinds of experts are present the
+ * two scalar kernels run on a library-owned side stream (one per device, created on first
+ * use, default priority) that forks from `stream` after the dispatch and joins it again
+ * before the call's work ends, so that later work on `stream` sees y complete as usual;
+ * calls on one device must not be issued concurrently from several host threads.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
  * n_tokens > 2^20, d_model or d_ff > 32768; code_order 1 without a device order), HIP.
  */
@@ -283,12 +287,14 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
  * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
  * "grid_per_cu", "blocks_first" / "blocks_second" (workgroups that share one pass over a
  * matrix in the first or only / the second product), "mfma_min_tokens" (experts with at
- * least this many tokens use the matrix-core kernel; -1 = never), "host_threads" (encoder
+ * least this many tokens use the matrix-core kernel; -1 = never), "overlap" (-1 = no side
+ * stream: all kernels of a layer one after the other on the caller's stream),
+ * "host_threads" (encoder
  * threads),
- * "phases" (bit mask of the layer's
- * kernels to enqueue: 1 dispatch, 2 first product, 4 second product -- lets a
- * benchmark time one kernel on a workspace a full call has filled).  value 0 restores
- * the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2.
+ * "phases" (bit mask of the layer's kernels to enqueue: 1 dispatch, 2 / 4 scalar kernel of
+ * the first / second product, 8 / 16 matrix-core kernel of the first / second product --
+ * lets a benchmark time one kernel on a workspace a full call has filled).  value 0
+ * restores the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2.
  * Unknown key: INVALID_ARG.
  */
 qmoe_status qmoe_set_tuning(const char *key, int value);

@@ -19,6 +19,7 @@
 //    block) items that the dispatch kernel wrote; experts without tokens never
 //    appear in it.
 #include <hip/hip_runtime.h>
+#include <mutex>
 
 #include <atomic>
 #include <cstdio>
@@ -387,21 +388,30 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &s
 #pragma unroll
     for (int t = 0; t < TBI; t++) snap[t] = 0.0f;
     if constexpr (TBI == 1) {
-        float x[24];
+        // the three bf16 values of a codeword are added with two packed dot products
+        // against (1, 1): two of them share a register, no widening shifts
+        uint32_t x[24];
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const uint32_t rec = xs_addr + pos[j];
 #pragma unroll
             for (int z = 0; z < 3; z++) {
                 const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
-                x[3 * j + z] = __uint_as_float((uint32_t)(*(lp_u16)(uintptr_t)addr) << 16);
+                x[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)addr);
             }
         }
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const uint32_t one2 = 0x3F803F80u;
+        bf16x2 ones;
+        __builtin_memcpy(&ones, &one2, 4);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            st.acc[0] += x[3 * j];
-            st.acc[0] += x[3 * j + 1];
-            st.acc[0] += x[3 * j + 2];
+            const uint32_t pair = x[3 * j] | (x[3 * j + 1] << 16);
+            bf16x2 p2, p1;
+            __builtin_memcpy(&p2, &pair, 4);
+            __builtin_memcpy(&p1, &x[3 * j + 2], 4);
+            st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, st.acc[0], false);
+            st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p1, ones, st.acc[0], false);
             snap[0] = wrap[j] ? st.acc[0] : snap[0];
             wrapped = wrapped || wrap[j];
         }
@@ -1379,6 +1389,33 @@ qmoe_status device_info(DeviceInfo *out)
     return QMOE_OK;
 }
 
+// A side stream and two events per device, made on first use and kept until the process
+// ends: the scalar kernels of a layer run there, next to the matrix-core kernels.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+};
+
+qmoe_status side_stream(SideStream *out)
+{
+    static SideStream cached[64];
+    static std::mutex mu;
+    int dev = 0;
+    QMOE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return QMOE_E_LIMIT;
+    std::lock_guard<std::mutex> lock(mu);
+    SideStream &c = cached[dev];
+    if (!c.ok) {
+        QMOE_HIP_TRY(hipStreamCreateWithFlags(&c.stream, hipStreamNonBlocking));
+        QMOE_HIP_TRY(hipEventCreateWithFlags(&c.fork, hipEventDisableTiming));
+        QMOE_HIP_TRY(hipEventCreateWithFlags(&c.join, hipEventDisableTiming));
+        c.ok = true;
+    }
+    *out = c;
+    return QMOE_OK;
+}
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct ProductPlan {
@@ -1837,71 +1874,93 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     const bool mm = mp.min_tokens <= n_tokens;  // otherwise no expert can reach the threshold
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerPtrs lp = layer_ptrs(workspace, l);
-    const int phases = tuning().phases > 0 ? tuning().phases : 7;
+    const int phases = tuning().phases > 0 ? tuning().phases : 31;
     if (phases & 1)
         if ((st = launch_dispatch(expert_idx, n_tokens, n_experts, d_model, lp, pwi.tb_max, pwo.tb_max,
                                   mp.min_tokens, y, s)) != QMOE_OK)
             return st;
 
+    // The experts with few tokens and the crowded ones are two independent chains of two
+    // kernels (each second product reads only the hidden rows its own first product wrote).
+    // With both kinds present the scalar chain goes to a side stream that forks from
+    // `stream` after the dispatch and joins it again at the end, so the kernels fill each
+    // other's idle compute units; the caller sees the usual stream order.
+    const bool overlap = mm && tuning().overlap >= 0 && (phases & 6) && (phases & 24);
+    hipStream_t s_scalar = s;
+    SideStream side;
+    if (overlap) {
+        if ((st = side_stream(&side)) != QMOE_OK) return st;
+        s_scalar = side.stream;
+        QMOE_HIP_TRY(hipEventRecord(side.fork, s));
+        QMOE_HIP_TRY(hipStreamWaitEvent(s_scalar, side.fork, 0));
+    }
     ProductArgs a{};
     fill_tables(d, &a, code_order);
     a.n_experts = n_experts;
     a.max_items = n_tokens;
     a.perm = lp.perm;
-    a.gate = nullptr;
     // first product: hidden[slot] = bf16(relu(Wi x[token]))
-    a.mats = wi;
-    a.items = lp.items_wi;
-    a.n_items_dev = lp.counters + 3;
-    a.x = x_bf16;
-    a.x_by_slot = 0;
-    a.ldx = d_model;
-    a.out = lp.hidden;
-    a.ld_out = d_ff;
-    a.epilogue = 1;
-    a.rows = d_ff;
-    a.cols = d_model;
-    a.rows_per_item = pwi.rows_per_item;
-    a.blocks_per_pass = pwi.blocks_per_pass;
-    a.tb_max = pwi.tb_max;
-    a.lds_dict_entries = pwi.lds_dict_entries;
-    if ((phases & 2) && mm) {
-        // crowded experts first: their tiles are the long items
-        ProductArgs am = a;
+    ProductArgs a1 = a;
+    a1.gate = nullptr;
+    a1.mats = wi;
+    a1.x = x_bf16;
+    a1.x_by_slot = 0;
+    a1.ldx = d_model;
+    a1.out = lp.hidden;
+    a1.ld_out = d_ff;
+    a1.epilogue = 1;
+    a1.rows = d_ff;
+    a1.cols = d_model;
+    // second product: y[token] = gate * Wo hidden[slot]
+    ProductArgs a2 = a;
+    a2.gate = gate;
+    a2.mats = wo;
+    a2.x = lp.hidden;
+    a2.x_by_slot = 1;
+    a2.ldx = d_ff;
+    a2.out = y;
+    a2.ld_out = d_model;
+    a2.epilogue = 0;
+    a2.rows = d_model;
+    a2.cols = d_ff;
+    // crowded experts (matrix cores) on `stream`: their tiles are the long items
+    if (mm) {
+        ProductArgs am = a1;
         am.items = lp.items_mm;
         am.n_items_dev = lp.counters + 7;
         am.work_counter = lp.counters + 8;
-        if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
-    }
-    a.work_counter = lp.counters + 5;
-    if (phases & 2)
-        if ((st = launch_product(a, pwi, run, s)) != QMOE_OK) return st;
-    // second product: y[token] = gate * Wo hidden[slot]
-    a.mats = wo;
-    a.items = lp.items_wo;
-    a.n_items_dev = lp.counters + 4;
-    a.x = lp.hidden;
-    a.x_by_slot = 1;
-    a.ldx = d_ff;
-    a.out = y;
-    a.ld_out = d_model;
-    a.gate = gate;
-    a.epilogue = 0;
-    a.rows = d_model;
-    a.cols = d_ff;
-    a.rows_per_item = pwo.rows_per_item;
-    a.blocks_per_pass = pwo.blocks_per_pass;
-    a.tb_max = pwo.tb_max;
-    a.lds_dict_entries = pwo.lds_dict_entries;
-    if ((phases & 4) && mm) {
-        ProductArgs am = a;
+        if (phases & 8)
+            if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+        am = a2;
         am.items = lp.items_mm;
         am.n_items_dev = lp.counters + 7;
         am.work_counter = lp.counters + 9;
-        if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+        if (phases & 16)
+            if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
     }
-    a.work_counter = lp.counters + 6;
-    if (phases & 4) return launch_product(a, pwo, run, s);
+    // experts with few tokens (scalar kernels)
+    a1.items = lp.items_wi;
+    a1.n_items_dev = lp.counters + 3;
+    a1.rows_per_item = pwi.rows_per_item;
+    a1.blocks_per_pass = pwi.blocks_per_pass;
+    a1.tb_max = pwi.tb_max;
+    a1.lds_dict_entries = pwi.lds_dict_entries;
+    a1.work_counter = lp.counters + 5;
+    if (phases & 2)
+        if ((st = launch_product(a1, pwi, run, s_scalar)) != QMOE_OK) return st;
+    a2.items = lp.items_wo;
+    a2.n_items_dev = lp.counters + 4;
+    a2.rows_per_item = pwo.rows_per_item;
+    a2.blocks_per_pass = pwo.blocks_per_pass;
+    a2.tb_max = pwo.tb_max;
+    a2.lds_dict_entries = pwo.lds_dict_entries;
+    a2.work_counter = lp.counters + 6;
+    if (phases & 4)
+        if ((st = launch_product(a2, pwo, run, s_scalar)) != QMOE_OK) return st;
+    if (overlap) {
+        QMOE_HIP_TRY(hipEventRecord(side.join, s_scalar));
+        QMOE_HIP_TRY(hipStreamWaitEvent(s, side.join, 0));
+    }
     return QMOE_OK;
 }
 
