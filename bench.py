@@ -82,21 +82,28 @@ def dense_bf16_experts(layer, dd, active, gpu):
     return (torch.from_numpy(ptrs["wi"]).to(gpu), torch.from_numpy(ptrs["wo"]).to(gpu), keep)
 
 
-def time_steps(fn, steps, warmup):
+def time_steps(fn, steps, warmup, spread=None):
+    """Mean ms per step over exactly `steps` steps (HIP events on the current stream around
+    the whole run, device idle before and after) and the wall-clock figure; with `spread`
+    (a dict) also the median, 10th and 90th percentile of the single steps."""
     import torch
 
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    start.record()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         fn()
-    stop.record()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return start.elapsed_time(stop) / steps, wall / steps * 1e3
+    if spread is not None:
+        each = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+        spread.update({"median": float(np.median(each)), "p10": float(np.percentile(each, 10)),
+                       "p90": float(np.percentile(each, 90))})
+    return marks[0].elapsed_time(marks[steps]) / steps, wall / steps * 1e3
 
 
 PHASES = (("dispatch", 1), ("first_product_mfma", 8), ("first_product_scalar", 2),
@@ -155,8 +162,8 @@ def cpu_baseline(w, idx, x_bits, active, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2048")
     ap.add_argument("--no-bf16", action="store_true", help="skip the uncompressed comparator")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -203,8 +210,9 @@ def main():
     def step():
         layer.forward(dd, x, d_idx, y, ws)
 
-    ms, wall_ms = time_steps(step, args.steps, args.warmup)
-    kernel_ms = time_phases(step, args.steps)
+    spread = {}
+    ms, wall_ms = time_steps(step, args.steps, args.warmup, spread)
+    kernel_ms = time_phases(step, min(args.steps, 30))
 
     # which experts went to the matrix-core kernels (tiles of up to 64 tokens), which to the scalar ones
     torch.cuda.synchronize()
@@ -218,6 +226,7 @@ def main():
     def mat_bytes(which, rows, experts):
         return int(sum(2 * layer.n_codes[which][e] + 6 * rows for e in experts))
     weight_bytes = mat_bytes("wi", w.d_ff, active) + mat_bytes("wo", w.d_model, active)
+    n_codewords = int(sum(layer.n_codes["wi"][e] + layer.n_codes["wo"][e] for e in active))
     def kernel_bytes(which, experts):
         toks = int(sum(counts[e] for e in experts))
         if which == "wi":
@@ -261,6 +270,12 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
                      "kernel_ms": dom[1], "algorithmic_bytes": dom[2]},
         "hbm_frac_whole_step": weight_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "ms_per_step_spread": spread,
+        "frac_of_stream_copy_rate": weight_bytes / (ms * 1e-3) / 1e9 / copy_gbps,
+        # decode rate of the whole step: codewords per clock per compute unit at 2.4 GHz, 256 units
+        "codewords_per_clk_per_cu": n_codewords / (ms * 1e-3) / (256 * 2.4e9),
+        "cache_state": "cold by construction: a step touches %.2f GB of codewords, more than four times "
+                       "the 256 MB last-level cache plus L2" % (weight_bytes / 1e9),
         "kernel_ms": kernel_ms,
         "kernels": {k: {"name": v[0], "algorithmic_bytes": v[1],
                         "GBps": (v[1] / (kernel_ms[k] * 1e-3) / 1e9) if kernel_ms[k] > 0 else None}
