@@ -1589,7 +1589,8 @@ void mm_rows(int rows, int *row_blocks, int *rows_per_block)
     *rows_per_block = std::min(kMmThreads, (per + 63) / 64 * 64);
 }
 
-qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, bool x_aligned, MmPlan *mp)
+qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, int n_tokens, bool x_aligned,
+                    MmPlan *mp)
 {
     *mp = MmPlan{};
     DeviceInfo di;
@@ -1602,6 +1603,11 @@ qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, b
     if (code_order != 1 || n_order == 0 || d->max_nonzeros > kRunMaxNonzeros || !fits || (d_model % 8) ||
         (d_ff % 8) || !x_aligned || tu.mfma_min_tokens < 0)
         return QMOE_OK;
+    // A tile is walked column step by column step by one workgroup per 512 rows: a long chain
+    // that pays only when the scalar kernel would need several rounds of items per compute
+    // unit anyway.  With few tokens in the call (measured: 512 tokens on 128 experts) the
+    // scalar kernel finishes every expert in one round and the chain would be the critical path.
+    if (tu.mfma_min_tokens == 0 && n_tokens < 4 * di.cus) return QMOE_OK;
     mp->min_tokens = tu.mfma_min_tokens > 0 ? tu.mfma_min_tokens : kMmMinTokensDefault;
     mp->grid = di.cus;
     mp->smem = mm_lds_bytes(n_order);
@@ -1845,7 +1851,7 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     MmPlan mp;
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
-    if ((st = plan_mm(d, code_order, d_model, d_ff, true, &mp)) != QMOE_OK) return st;
+    if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
                            pwo.tb_max, mp.min_tokens, nullptr, static_cast<hipStream_t>(stream));
 }
@@ -1869,7 +1875,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
     MmPlan mp;
-    if ((st = plan_mm(d, code_order, d_model, d_ff, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
+    if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
         return st;
     const bool mm = mp.min_tokens <= n_tokens;  // otherwise no expert can reach the threshold
     hipStream_t s = static_cast<hipStream_t>(stream);
