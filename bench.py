@@ -61,25 +61,40 @@ def build_layer(w, dd, gpu, workers, interchange_order=False):
     return layer
 
 
-def dense_bf16_experts(layer, dd, active, gpu):
-    """Uncompressed bf16 copies (scale folded in) of the experts that receive tokens."""
+def dense_bf16_experts(layer, dd, active, gpu, stats=None):
+    """Uncompressed bf16 copies (scale folded in) of the experts that receive tokens, made by
+    the library's decompression kernel, one launch per projection; `stats` receives its rate."""
     import torch
     import paper_2310_16795_amd as q
 
-    ptrs = {"wi": np.zeros(layer.n_experts, dtype=np.int64), "wo": np.zeros(layer.n_experts, dtype=np.int64)}
-    keep = []
+    ptrs, keep, out = {}, [], {}
     for which in ("wi", "wo"):
         rows = layer.d_ff if which == "wi" else layer.d_model
         cols = layer.d_model if which == "wi" else layer.d_ff
-        tmp = torch.empty((rows, cols), dtype=torch.int8, device=gpu)
-        d_scale = layer.bufs[which][2].view(torch.float16).view(layer.n_experts, rows)
+        p = np.zeros(layer.n_experts, dtype=np.int64)
         for e in active:
-            q.qmoe_decode_dense(dd.handle, layer.desc_host[which][e], tmp, 0)
-            dense = (tmp.to(torch.float32) * d_scale[e].to(torch.float32)[:, None]).to(torch.bfloat16).contiguous()
+            dense = torch.empty((rows, cols), dtype=torch.bfloat16, device=gpu)
             keep.append(dense)
-            ptrs[which][e] = dense.data_ptr()
-    torch.cuda.synchronize()
-    return (torch.from_numpy(ptrs["wi"]).to(gpu), torch.from_numpy(ptrs["wo"]).to(gpu), keep)
+            p[e] = dense.data_ptr()
+        ptrs[which] = torch.from_numpy(p).to(gpu)
+        out[which] = (rows, cols)
+    def run():
+        for which in ("wi", "wo"):
+            q.qmoe_decompress(dd.handle, layer.desc_dev[which], 1, layer.n_experts, out[which][0], out[which][1], 1,
+                              ptrs[which])
+    ms, _ = time_steps(run, 3, 1)
+    if stats is not None:
+        written = 2 * len(active) * 2 * layer.d_model * layer.d_ff
+        stats.update({"experts": len(active), "ms": ms, "bf16_bytes_written": written,
+                      "GBps_written": written / (ms * 1e-3) / 1e9,
+                      "compressed_GBps_read": layer_bytes_of(layer, active) / (ms * 1e-3) / 1e9,
+                      "kind": "qmoe_decompress to bf16, both projections of every expert with tokens, two launches"})
+    return ptrs["wi"], ptrs["wo"], keep
+
+
+def layer_bytes_of(layer, experts):
+    return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + 6 * (layer.d_ff + layer.d_model)
+                   for e in experts))
 
 
 def time_steps(fn, steps, warmup, spread=None):
@@ -291,9 +306,14 @@ def main():
 
     if not args.no_bf16:
         t0 = time.time()
-        wi_p, wo_p, keep = dense_bf16_experts(layer, dd, active, gpu)
+        if args.interchange_order:
+            raise SystemExit("bench.py: the bf16 comparator needs device-order streams (drop --interchange-order "
+                             "or add --no-bf16)")
+        dstats = {}
+        wi_p, wo_p, keep = dense_bf16_experts(layer, dd, active, gpu, dstats)
+        result["decompress"] = dstats
         log(f"bf16 copies of {len(active)} experts: {sum(k.numel() for k in keep) * 2 / 1e9:.1f} GB "
-            f"({time.time() - t0:.0f} s)")
+            f"({time.time() - t0:.0f} s), decompressed at {dstats['GBps_written']:.0f} GB/s written")
         y2 = torch.empty_like(y)
 
         def step_bf16():

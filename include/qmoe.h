@@ -200,6 +200,21 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W /*host*/
 qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/, int8_t *out /*device*/,
                               int path, void *stream);
 
+/*
+ * Decompress whole matrices (the codec of Section 4.3.3 without the product; the
+ * "decompress, then a standard matrix product" alternative named in Section 5.3):
+ * out[m] receives matrix mats[m], row-major rows x cols, as int8 in {-1, 0, +1}
+ * (out_kind 0) or as bf16 with the row scale folded in, bf16(s_r) * w (out_kind 1).
+ * mats: device array [n_mats] of qmoe_matrix, all rows x cols, device numbering
+ * (code_order must be 1).  out: device array [n_mats] of device pointers, 16-byte
+ * aligned, NULL = skip that matrix.  cols must be a multiple of 8.  One launch for all
+ * matrices; nothing is allocated.
+ * Errors: INVALID_ARG, NO_DEVICE_DICT, LIMIT (no device order; cols > 32768), HIP.
+ */
+qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats /*device*/, int code_order,
+                            int n_mats, int rows, int cols, int out_kind,
+                            void *const *out /*device*/, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* One MoE feed-forward layer (Section 2.1; Section 5.1 on skipping experts)  */
 /* ------------------------------------------------------------------------- */

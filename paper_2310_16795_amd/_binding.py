@@ -42,7 +42,7 @@ EXPORTS = [
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
     "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
-    "qmoe_codes_to_device_order",
+    "qmoe_codes_to_device_order", "qmoe_decompress",
 ]
 
 
@@ -73,6 +73,7 @@ def lib():
         L.qmoe_dict_device_order.argtypes = [vp, POINTER(vp), POINTER(vp), POINTER(i), POINTER(i)]
         L.qmoe_codes_to_device_order.argtypes = [vp, vp, sz, vp]
         L.qmoe_moe_dispatch.argtypes = [vp, i, vp, i, i, i, i, vp, sz, vp]
+        L.qmoe_decompress.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
         L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -242,6 +243,14 @@ def qmoe_moe_dispatch(d, code_order: int, expert_idx, n_experts: int, d_model: i
     _check(lib().qmoe_moe_dispatch(d, code_order, _dev_ptr(expert_idx), expert_idx.numel(), n_experts, d_model, d_ff,
                                    _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream_ptr(stream)), "qmoe_moe_dispatch")
+
+
+def qmoe_decompress(d, mats, code_order: int, n_mats: int, rows: int, cols: int, out_kind: int, out_ptrs,
+                    stream=None) -> None:
+    """mats: device uint8 tensor holding n_mats qmoe_matrix descriptors; out_ptrs: device int64 tensor
+    [n_mats] of destination addresses (0 = skip)."""
+    _check(lib().qmoe_decompress(d, _dev_ptr(mats), code_order, n_mats, rows, cols, out_kind, _dev_ptr(out_ptrs),
+                                 _stream_ptr(stream)), "qmoe_decompress")
 
 
 def qmoe_bf16_layer_forward(wi_ptrs, wo_ptrs, n_experts: int, d_model: int, d_ff: int, x_bf16, expert_idx,

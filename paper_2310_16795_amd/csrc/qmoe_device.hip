@@ -722,8 +722,42 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Table entry of the codeword at index `at` (0..15) of the window c0..c3, n0..n3 (anything
-// when at > 15: not used then).  A macro, so that the window stays in registers.
+// ---- the ring decoder shared by the matrix-core product and the decompression kernel ----
+// (macros rather than a struct with member functions: the decoder's state has to stay in
+// plain scalar registers, and the compiler keeps it there only when it sees scalars.)
+//
+// QMOE_RING_ROW_SETUP declares the state for one lane = one row: `left` codewords to go,
+// the stream in 16-byte pieces (eight codewords) -- c0..c3 and n0..n3 are the window the
+// decoder picks codewords from (index sub = 0..15), `fut` is in flight; pieces past the
+// lane's last one re-read the last (never used: `left` runs out first) -- and `pos`, the
+// column where the next codeword starts.
+#define QMOE_RING_ROW_SETUP(M, row, row_live)                                                           \
+    uint32_t left = 0;                                                                                  \
+    uintptr_t pp = reinterpret_cast<uintptr_t>((M).codes), last = pp;                                   \
+    uint32_t sub = 0;                                                                                   \
+    if (row_live) {                                                                                     \
+        gp_u32 row_off_ = (gp_u32)(M).row_off;                                                          \
+        const uint32_t cap_ = min((M).n_codes, kMaxCodes);                                              \
+        const uint32_t K1_ = min(row_off_[(row) + 1], cap_);                                            \
+        const uint32_t K0_ = min(row_off_[(row)], K1_);                                                 \
+        left = K1_ - K0_;                                                                               \
+        const uintptr_t first_byte_ = reinterpret_cast<uintptr_t>((M).codes) + 2 * (uintptr_t)K0_;      \
+        const uint32_t lead_ = (uint32_t)(first_byte_ & 15u);                                           \
+        pp = first_byte_ - lead_;                                                                       \
+        sub = lead_ >> 1;                                                                               \
+        last = pp + 16u * (uintptr_t)(left ? ((lead_ + 2u * left + 15u) >> 4) - 1u : 0u);               \
+    }                                                                                                   \
+    uint32_t c0, c1, c2, c3, n0, n1, n2, n3;                                                            \
+    {                                                                                                   \
+        const u32x4 a0_ = *(gp_u32x4)pp, a1_ = *(gp_u32x4)(pp + 16u < last ? pp + 16u : last);          \
+        c0 = a0_.x; c1 = a0_.y; c2 = a0_.z; c3 = a0_.w;                                                 \
+        n0 = a1_.x; n1 = a1_.y; n2 = a1_.z; n3 = a1_.w;                                                 \
+    }                                                                                                   \
+    u32x4 fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                         \
+    int pos = 0
+
+// Table entry of the codeword at index `at` (0..15) of the window (anything when at > 15:
+// not used then).
 #define QMOE_MM_ENTRY_AT(dst, at)                                                                       \
     do {                                                                                                \
         const bool hi8_ = ((at) & 8u) != 0u, hi4_ = ((at) & 4u) != 0u;                                  \
@@ -733,6 +767,55 @@ __device__ __forceinline__ void lds_barrier()
         const uint32_t code_ = __builtin_amdgcn_perm(hi_, lo_, 0x0c0c0100u + 0x0202u * ((at) & 3u));    \
         (dst) = order_entry(table, code_, (uint32_t)a.n_groups, (uint32_t)a.n_order);                   \
     } while (0)
+
+// Decode step c of the ring at LDS byte address `wrow` (128 one-byte columns + 8 spare
+// bytes): clear the half that becomes columns kend .. kend+63, then decode until every lane
+// has passed column kend = 64 (c + 1); lanes that are there already keep going while their
+// next codeword fits into the ring.  AFTER_WAIT runs right after the step's one wait for
+// global memory (a good place to issue loads that should stay in flight for a whole step).
+#define QMOE_RING_DECODE_STEP(c, AFTER_WAIT)                                                            \
+    const int kc = (c) * kMmKc, kend = kc + kMmKc;                                                      \
+    _Pragma("unroll") for (int i_ = 0; i_ < kMmKc / 8; i_++)                                            \
+        ((lw_u64)(uintptr_t)(wrow + (uint32_t)((((c) + 1) & 1) * kMmKc)))[i_] = 0ull;                   \
+    do {                                                                                                \
+        /* Slide the window by one piece where its first half is used up (once per step as a */        \
+        /* rule; the loop comes back only for lanes that use up a whole window in one step). */        \
+        /* The other lanes fetch the piece they already wait for again, so that the load is */         \
+        /* unconditional and stays in flight until the next slide. */                                   \
+        {                                                                                               \
+            const bool s8_ = sub >= 8u;                                                                 \
+            sub -= s8_ ? 8u : 0u;                                                                       \
+            pp += s8_ ? 16u : 0u;                                                                       \
+            const uint32_t f0_ = fut.x, f1_ = fut.y, f2_ = fut.z, f3_ = fut.w;                          \
+            c0 = s8_ ? n0 : c0; c1 = s8_ ? n1 : c1; c2 = s8_ ? n2 : c2; c3 = s8_ ? n3 : c3;             \
+            n0 = s8_ ? f0_ : n0; n1 = s8_ ? f1_ : n1; n2 = s8_ ? f2_ : n2; n3 = s8_ ? f3_ : n3;         \
+            fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                       \
+        }                                                                                               \
+        AFTER_WAIT                                                                                      \
+        /* No branches inside the inner loop: a lane that sits out decodes an empty entry into */      \
+        /* the spare bytes after its ring.  The look-up of the next codeword is issued before */       \
+        /* the current one is applied. */                                                               \
+        uint32_t ent_next_;                                                                             \
+        QMOE_MM_ENTRY_AT(ent_next_, sub);                                                               \
+        while (__any(left != 0u && pos < kend && sub < 16u)) {                                          \
+            const bool go_ = left != 0u && pos <= kc + kMmAhead && sub < 16u;                           \
+            const uint32_t ent_ = go_ ? ent_next_ : 0u;                                                 \
+            left -= go_ ? 1u : 0u;                                                                      \
+            sub += go_ ? 1u : 0u;                                                                       \
+            QMOE_MM_ENTRY_AT(ent_next_, sub);                                                           \
+            const uint32_t base_ = go_ ? (uint32_t)pos : (uint32_t)kMmRing;                             \
+            const uint32_t mask_ = go_ ? (uint32_t)(kMmRing - 1) : 0xFFu;                               \
+            /* fields are right-aligned in device-order entries: an unused one (0) comes first */      \
+            /* and writes a zero at the run's first column, before any real weight */                   \
+            _Pragma("unroll") for (int z_ = 0; z_ < kRunMaxNonzeros; z_++) {                            \
+                const uint32_t f_ = (ent_ >> (8 + 8 * z_)) & 0xFFu;                                     \
+                const uint32_t col_ = (base_ + (f_ >> 3)) & mask_;                                      \
+                /* 0, 0x40 (+2.0), 0xC0 (-2.0) */                                                       \
+                *(lw_u8)(uintptr_t)(wrow + col_) = (unsigned char)((f_ & 6u) << 5);                     \
+            }                                                                                           \
+            pos += (int)((ent_ & 0xFFu) >> 3);                                                          \
+        }                                                                                               \
+    } while (__any(left != 0u && pos < kend))
 
 // MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
 // rings and the two activation buffers.
@@ -769,35 +852,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     const int r0 = blk * a.mm_rows_per_block;
     const int row = r0 + tid;
     const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
-    uint32_t left = 0;
-    uintptr_t pp = reinterpret_cast<uintptr_t>(M.codes), last = pp;
-    uint32_t sub = 0;
-    if (row_live) {
-        gp_u32 row_off = (gp_u32)M.row_off;
-        const uint32_t cap = min(M.n_codes, kMaxCodes);
-        const uint32_t K1 = min(row_off[row + 1], cap);
-        const uint32_t K0 = min(row_off[row], K1);
-        left = K1 - K0;
-        const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + 2 * (uintptr_t)K0;
-        const uint32_t lead = (uint32_t)(first_byte & 15u);
-        pp = first_byte - lead;
-        sub = lead >> 1;
-        last = pp + 16u * (uintptr_t)(left ? ((lead + 2u * left + 15u) >> 4) - 1u : 0u);
-    }
-    // The stream in 16-byte pieces (eight codewords): `cur` and `nxt` are the window the
-    // decoder picks codewords from (index sub = 0..15), `fut` is in flight.  Pieces past the
-    // lane's last one re-read the last (never used: `left` runs out first).
-    auto piece = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
-    // (plain scalars: selecting between members of two vectors makes the compiler keep
-    // the vectors in memory)
-    uint32_t c0, c1, c2, c3, n0, n1, n2, n3;
-    {
-        const u32x4 a0 = piece(pp), a1 = piece(pp + 16u);
-        c0 = a0.x; c1 = a0.y; c2 = a0.z; c3 = a0.w;
-        n0 = a1.x; n1 = a1.y; n2 = a1.z; n3 = a1.w;
-    }
-    u32x4 fut = piece(pp + 32u);
-    int pos = 0;  // column where the next codeword starts
+    QMOE_RING_ROW_SETUP(M, row, row_live);
     const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
 
     f32x16 acc[MB][2];
@@ -827,62 +882,19 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     __syncthreads();  // token ids, gates and the first activation step are in place
     if (lag != 0) lds_barrier();
     for (int c = 0; c < nsteps; c++) {
-        const int kc = c * kMmKc, kend = kc + kMmKc;
-        // ---- decode step c: until every lane has passed column kend; lanes that are there
-        // already keep going while their next codeword fits into the ring.
-        // The half of the ring the previous step multiplied becomes columns kend .. kend+63.
-#pragma unroll
-        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + (uint32_t)(((c + 1) & 1) * kMmKc)))[i] = 0ull;
-        do {
-            // Slide the window by one piece where its first half is used up (once per step
-            // as a rule; the loop comes back only for lanes that use up a whole window in one
-            // step).  The other lanes fetch the piece they already wait for again, so that
-            // the load is unconditional and stays in flight until the next slide.
-            {
-                const bool s8 = sub >= 8u;
-                sub -= s8 ? 8u : 0u;
-                pp += s8 ? 16u : 0u;
-                const uint32_t f0 = fut.x, f1 = fut.y, f2 = fut.z, f3 = fut.w;
-                c0 = s8 ? n0 : c0; c1 = s8 ? n1 : c1; c2 = s8 ? n2 : c2; c3 = s8 ? n3 : c3;
-                n0 = s8 ? f0 : n0; n1 = s8 ? f1 : n1; n2 = s8 ? f2 : n2; n3 = s8 ? f3 : n3;
-                fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);
-            }
-            // The next step's activations, staged after this step's product; fetched here,
-            // after the window's wait, so that a whole step hides the latency of both loads
-            // (the empty asm keeps the compiler from moving the load up, in front of that wait).
-            {
-                int k_next = kend;
-                asm volatile("" : "+s"(k_next));
-                xr = load_x(k_next);
-            }
-            // No branches inside the inner loop: a lane that sits out decodes an empty entry
-            // into the spare bytes after its ring.  The look-up of the next codeword is
-            // issued before the current one is applied.
-            uint32_t ent_next;
-            QMOE_MM_ENTRY_AT(ent_next, sub);
-            while (__any(left != 0u && pos < kend && sub < 16u)) {
-                const bool go = left != 0u && pos <= kc + kMmAhead && sub < 16u;
-                const uint32_t ent = go ? ent_next : 0u;
-                left -= go ? 1u : 0u;
-                sub += go ? 1u : 0u;
-                QMOE_MM_ENTRY_AT(ent_next, sub);
-                const uint32_t base = go ? (uint32_t)pos : (uint32_t)kMmRing;
-                const uint32_t mask = go ? (uint32_t)(kMmRing - 1) : 0xFFu;
-                // fields are right-aligned in device-order entries: an unused one (0) comes
-                // first and writes a zero at the run's first column, before any real weight
-#pragma unroll
-                for (int z = 0; z < kRunMaxNonzeros; z++) {
-                    const uint32_t f = (ent >> (8 + 8 * z)) & 0xFFu;
-                    const uint32_t col = (base + (f >> 3)) & mask;
-                    *(lw_u8)(uintptr_t)(wrow + col) = (unsigned char)((f & 6u) << 5);  // 0, 0x40 (+2.0), 0xC0 (-2.0)
-                }
-                pos += (int)((ent & 0xFFu) >> 3);
-            }
-        } while (__any(left != 0u && pos < kend));
+        // ---- decode step c; the next step's activations, staged after this step's product,
+        // are fetched right after the window's wait, so that a whole step hides the latency
+        // of both loads (the empty asm keeps the compiler from moving the load up, in front
+        // of that wait)
+        QMOE_RING_DECODE_STEP(c, {
+            int k_next = kend;
+            asm volatile("" : "+s"(k_next));
+            xr = load_x(k_next);
+        });
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        lds_barrier();
+        if (a.mm_stagger) lds_barrier();
 
         // ---- multiply step c
         const uint32_t xf = xfrag0 + (uint32_t)((c & 1) * kMmTokens * kMmXRowBytes);
@@ -917,7 +929,6 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         lds_barrier();
     }
     if (lag == 0) lds_barrier();
-#undef QMOE_MM_ENTRY_AT
 
     // accumulator v of lane l: token 32*mb + 8*(v/4) + 4*(l/32) + v%4, row 32*nb + l%32 of the wavefront's 64
 #pragma unroll
@@ -1007,6 +1018,105 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
         else
             mm_item<2, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
                             (lp_f32)gate_s, lag);
+    }
+}
+
+// ---------------------------------------------------------------- decompression of whole matrices
+//
+// The codec without the product: dense ternary (int8) or scaled bf16 copies of compressed
+// matrices, for consumers that want a plain matrix (a library GEMM, a check).  Same ring
+// decoder as the matrix-core product: a workgroup of 512 lanes owns up to 512 rows, one lane
+// per row; after each 64-column step a wavefront writes out the 64 x 64 tile its own lanes
+// decoded, 8 rows per store instruction with 8 lanes covering a row's 64 columns, so that
+// the stores are whole 64- or 128-byte runs.  Wavefronts never wait for each other.
+
+struct DecompressArgs {
+    const qmoe_matrix *mats;  // device array
+    void *const *out;         // device array of destinations (row-major rows x cols), nullptr = skip
+    int n_mats, rows, cols;
+    int rows_per_block, row_blocks;
+    const uint32_t *order_table;
+    int n_groups, n_order;
+};
+
+template <int OUT>  // 0: int8 in {-1, 0, +1}; 1: bf16(scale of the row) with the weight's sign, or 0
+__global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
+    uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
+    for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
+    __syncthreads();
+    lp_u32 table = (lp_u32)table_w;
+    const uint32_t wt = (uint32_t)(uintptr_t)(lw_u8)(smem + table_bytes);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
+    const int seg = lane & 7, sub_row = lane >> 3;  // write-out role: columns 8*seg.., rows sub_row + 8*i
+    const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+    const long long total = (long long)a.n_mats * a.row_blocks;
+
+    for (long long g = blockIdx.x; g < total; g += gridDim.x) {
+        const int m = (int)(g / a.row_blocks);
+        const int blk = (int)(g - (long long)m * a.row_blocks);
+        unsigned char *out = static_cast<unsigned char *>(a.out[m]);
+        if (!out) continue;
+        const qmoe_matrix M = a.mats[m];
+        const int r0 = blk * a.rows_per_block;
+        const int row = r0 + tid;
+        const bool row_live = tid < a.rows_per_block && row < a.rows;
+        QMOE_RING_ROW_SETUP(M, row, row_live);
+#pragma unroll
+        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+
+        // bf16 scale of the eight rows this lane writes out, in both halves of a register
+        uint32_t s2[8];
+        if constexpr (OUT == 1) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                uint32_t b = 0;
+                if (rl < a.rows_per_block && r0 + rl < a.rows)
+                    b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[r0 + rl]));
+                s2[i] = b | (b << 16);
+            }
+        }
+
+        for (int c = 0; c < nsteps; c++) {
+            QMOE_RING_DECODE_STEP(c, {});
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int k = kc + 8 * seg;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                const int r = r0 + rl;
+                if (rl < a.rows_per_block && r < a.rows && k + 8 <= a.cols) {
+                    const unsigned long long d =
+                        *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes + (c & 1) * kMmKc + 8 * seg));
+                    const uint32_t w0 = (uint32_t)d, w1 = (uint32_t)(d >> 32);
+                    const size_t at = (size_t)r * a.cols + k;
+                    if constexpr (OUT == 0) {
+                        // ring byte 0x40 -> 0x01, 0xC0 -> 0xFF, 0 -> 0
+                        const uint32_t o0 = ((w0 >> 6) & 0x01010101u) | (((w0 >> 7) & 0x01010101u) * 0xFEu);
+                        const uint32_t o1 = ((w1 >> 6) & 0x01010101u) | (((w1 >> 7) & 0x01010101u) * 0xFEu);
+                        *reinterpret_cast<unsigned long long *>(out + at) = (unsigned long long)o0 | ((unsigned long long)o1 << 32);
+                    } else {
+                        u32x4 o;
+#pragma unroll
+                        for (int h = 0; h < 4; h++) {
+                            // two ring bytes -> the high bytes of two 16-bit halves: 0x4000 / 0xC000 / 0
+                            const uint32_t e = __builtin_amdgcn_perm(0u, h < 2 ? w0 : w1, (h & 1) ? 0x030c020cu : 0x010c000cu);
+                            const uint32_t present = ((e >> 14) & 0x00010001u) * 0xFFFFu;
+                            o[h] = ((e & 0x80008000u) | s2[i]) & present;
+                        }
+                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
+                    }
+                }
+            }
+            // the next step clears this half of the ring: after these reads
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 }
 
@@ -1519,6 +1629,17 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     return QMOE_OK;
 }
 
+// A layer call with fewer work items than compute units (few tokens) splits every pass over
+// a matrix between several workgroups; 0 = let plan_product choose (one block as a rule).
+int layer_blocks_hint(int n_experts, int n_tokens)
+{
+    DeviceInfo di;
+    if (device_info(&di) != QMOE_OK) return 0;
+    const int items = std::max(1, std::min(n_tokens, n_experts + n_tokens / 4));  // upper bound
+    const int b = di.cus / items;
+    return b >= 2 ? std::min(b, 8) : 0;
+}
+
 // The dense bf16 comparator keeps its own simple plan: token-major fp32 activations in
 // LDS, one wavefront per row.
 qmoe_status plan_dense(int rows, int cols, long long max_passes_hint, ProductPlan *p)
@@ -1811,6 +1932,46 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W, int8_t *
     return QMOE_OK;
 }
 
+qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats, int code_order, int n_mats, int rows,
+                            int cols, int out_kind, void *const *out, void *stream)
+{
+    if (!d || !mats || !out || n_mats < 1 || rows < 1 || cols < 2 || (out_kind != 0 && out_kind != 1))
+        return QMOE_E_INVALID_ARG;
+    if (cols % 8) return QMOE_E_INVALID_ARG;  // whole 8-column stores
+    if (cols > kMaxCols) return QMOE_E_LIMIT;
+    if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
+    if (code_order != 1) return QMOE_E_INVALID_ARG;  // the ring decoder reads the device-order table from LDS
+    qmoe_status st = check_code_order(d, code_order);
+    if (st != QMOE_OK) return st;
+    if (d->max_nonzeros > kRunMaxNonzeros) return QMOE_E_LIMIT;
+    DeviceInfo di;
+    if ((st = device_info(&di)) != QMOE_OK) return st;
+    DecompressArgs a{};
+    a.mats = mats;
+    a.out = out;
+    a.n_mats = n_mats;
+    a.rows = rows;
+    a.cols = cols;
+    mm_rows(rows, &a.row_blocks, &a.rows_per_block);
+    a.order_table = reinterpret_cast<const uint32_t *>(static_cast<const unsigned char *>(d->dev) + kDevOrderTableOffset);
+    a.n_groups = d->n_groups;
+    a.n_order = (int)d->order_table.size();
+    const size_t smem = (((size_t)a.n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes;
+    if (smem > (size_t)di.max_lds) return QMOE_E_LIMIT;
+    const long long total = (long long)n_mats * a.row_blocks;
+    const int grid = (int)std::min<long long>(total, 2LL * di.cus);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (out_kind == 0) {
+        if ((st = allow_lds(k_decompress<0>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<0>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    } else {
+        if ((st = allow_lds(k_decompress<1>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<1>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    }
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
+}
+
 qmoe_status qmoe_moe_layer_ws_layout(int n_experts, int d_model, int d_ff, int n_tokens, qmoe_ws_layout *out)
 {
     if (!out) return QMOE_E_INVALID_ARG;
@@ -1849,8 +2010,13 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     const int n_order = code_order ? (int)d->order_table.size() : 0;
     ProductPlan pwi, pwo;
     MmPlan mp;
-    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
+    const int spread = layer_blocks_hint(n_experts, n_tokens);
+    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
+                           tuning().blocks_first > 0 ? tuning().blocks_first : spread)) != QMOE_OK)
+        return st;
+    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
+                           tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
+        return st;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
                            pwo.tb_max, mp.min_tokens, nullptr, static_cast<hipStream_t>(stream));
@@ -1872,8 +2038,13 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
     ProductPlan pwi, pwo;
-    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order, tuning().blocks_first)) != QMOE_OK) return st;
-    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order, tuning().blocks_second)) != QMOE_OK) return st;
+    const int spread = layer_blocks_hint(n_experts, n_tokens);
+    if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
+                           tuning().blocks_first > 0 ? tuning().blocks_first : spread)) != QMOE_OK)
+        return st;
+    if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
+                           tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
+        return st;
     MmPlan mp;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
         return st;

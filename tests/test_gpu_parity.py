@@ -293,6 +293,61 @@ def test_crowded_experts_take_the_matrix_core_kernel(gpu, ddict, oracle_dict, d_
         q.qmoe_set_tuning("mfma_min_tokens", 0)
 
 
+def _bf16_bits_of_f16(scale_f16_bits):
+    """Round-to-nearest-even bf16 bit patterns of binary16 values (numpy only)."""
+    u = scale_f16_bits.view(np.float16).astype(np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(136, 600), (1024, 72)])
+def test_decompress_whole_matrices_bit_exact(gpu, ddict, oracle_dict, d_model, d_ff):
+    """Every expert of a small layer to int8 and to scaled bf16 in one launch each: widths
+    that are no multiple of the 64-column step, more than 512 rows on one side, a skipped
+    matrix.  int8 must equal the encoder's input, bf16 must equal bf16(scale) * weight."""
+    w = synth.WORKLOADS["c2048_ragged256"].scaled(n_experts=5, d_model=d_model, d_ff=d_ff, n_tokens=8)
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    for which, rows, cols in (("wi", d_ff, d_model), ("wo", d_model, d_ff)):
+        tern = [w.wi_ternary(e) if which == "wi" else w.wo_ternary(e) for e in range(w.n_experts)]
+        scale = [w.wi_scale(e) if which == "wi" else w.wo_scale(e) for e in range(w.n_experts)]
+        skip = 3
+        for kind, dt in ((0, torch.int8), (1, torch.int16)):
+            outs = [torch.full((rows, cols), 77, dtype=dt, device=gpu) for _ in range(w.n_experts)]
+            ptrs = torch.tensor([0 if e == skip else o.data_ptr() for e, o in enumerate(outs)], dtype=torch.int64,
+                                device=gpu)
+            q.qmoe_decompress(ddict.handle, layer.desc_dev[which], 1, w.n_experts, rows, cols, kind, ptrs)
+            torch.cuda.synchronize()
+            for e in range(w.n_experts):
+                got = outs[e].cpu().numpy()
+                if e == skip:
+                    assert (got == 77).all()
+                elif kind == 0:
+                    assert np.array_equal(got, tern[e]), f"{which} expert {e}"
+                else:
+                    sb = _bf16_bits_of_f16(scale[e])[:, None].astype(np.uint16)
+                    want = np.where(tern[e] == 0, np.uint16(0), np.where(tern[e] > 0, sb, sb | np.uint16(0x8000)))
+                    assert np.array_equal(got.view(np.uint16), want.astype(np.uint16)), f"{which} expert {e}"
+
+
+def test_decompress_full_size_expert(gpu, ddict, oracle_dict):
+    """Two c2048-sized matrices (2080 x 6144): the oracle's decode of the oracle's stream."""
+    w = synth.WORKLOADS["c2048"]
+    mats, want = [], []
+    for e in (5, 1234):
+        tern = w.wo_ternary(e)
+        codes, row_off = oracle.encode(oracle_dict, tern)
+        assert np.array_equal(oracle.decode(oracle_dict.words, codes, row_off, *tern.shape), tern)
+        mats.append(dev.DeviceMatrix(codes, row_off, w.wo_scale(e), *tern.shape, device=gpu, device_order_of=ddict))
+        want.append(tern)
+    desc = (q.qmoe_matrix * 2)(mats[0].desc, mats[1].desc)
+    d_desc = torch.from_numpy(np.frombuffer(bytes(desc), dtype=np.uint8).copy()).to(gpu)
+    outs = [torch.empty(want[0].shape, dtype=torch.int8, device=gpu) for _ in range(2)]
+    ptrs = torch.tensor([o.data_ptr() for o in outs], dtype=torch.int64, device=gpu)
+    q.qmoe_decompress(ddict.handle, d_desc, 1, 2, want[0].shape[0], want[0].shape[1], 0, ptrs)
+    torch.cuda.synchronize()
+    for o, t in zip(outs, want):
+        assert np.array_equal(o.cpu().numpy(), t)
+
+
 def test_layer_drops_tokens_with_bad_expert_index(gpu, ddict, oracle_dict):
     w = synth.WORKLOADS["switch_base128"].scaled(n_experts=4, d_model=64, d_ff=96, n_tokens=20)
     idx, x = w.expert_idx(), w.tokens()

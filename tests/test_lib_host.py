@@ -199,6 +199,9 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     assert L.qmoe_dict_upload(lib_dict, None, 0, None) == -1
     assert L.qmoe_dict_upload(lib_dict, 256, 10, None) == -2
     assert L.qmoe_bf16_layer_forward(256, 256, 4, 12, 16, 256, 256, None, 4, 256, 256, 1 << 30, None) == -1
+    assert L.qmoe_decompress(lib_dict, 256, 1, 2, 8, 16, 0, 256, None) == -9               # not uploaded
+    assert L.qmoe_decompress(lib_dict, 256, 1, 2, 8, 12, 0, 256, None) == -1               # cols % 8
+    assert L.qmoe_decompress(lib_dict, None, 1, 2, 8, 16, 0, 256, None) == -1
     assert L.qmoe_moe_dispatch(lib_dict, 0, 256, 4, 4, 8, 16, 256, 16, None) == -5
     assert L.qmoe_moe_dispatch(None, 0, 256, 4, 4, 8, 16, 256, 1 << 30, None) == -1                   # workspace too small
 
