@@ -19,6 +19,7 @@
 //    block) items that the dispatch kernel wrote; experts without tokens never
 //    appear in it.
 #include <hip/hip_runtime.h>
+#include <cmath>
 #include <mutex>
 
 #include <atomic>
@@ -1635,7 +1636,9 @@ int layer_blocks_hint(int n_experts, int n_tokens)
 {
     DeviceInfo di;
     if (device_info(&di) != QMOE_OK) return 0;
-    const int items = std::max(1, std::min(n_tokens, n_experts + n_tokens / 4));  // upper bound
+    // experts that receive a token under uniform routing, or tiles of four tokens if that is more
+    const double active = n_experts * (1.0 - std::exp(-(double)n_tokens / n_experts));
+    const int items = std::max(1, (int)std::max(active, n_tokens / 4.0));
     const int b = di.cus / items;
     return b >= 2 ? std::min(b, 8) : 0;
 }
