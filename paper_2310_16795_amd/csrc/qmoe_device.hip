@@ -131,25 +131,6 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h)
     return (float)f;
 }
 
-template <int TBI>
-__device__ __forceinline__ void lds_load_tile(const float *xs, int col, float (&v)[TBI])
-{
-    if constexpr (TBI == 1) {
-        v[0] = xs[col];
-    } else if constexpr (TBI == 2) {
-        const float2 t = reinterpret_cast<const float2 *>(xs)[col];
-        v[0] = t.x; v[1] = t.y;
-    } else if constexpr (TBI == 4) {
-        const float4 t = reinterpret_cast<const float4 *>(xs)[col];
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else {
-        const float4 t0 = reinterpret_cast<const float4 *>(xs)[2 * col];
-        const float4 t1 = reinterpret_cast<const float4 *>(xs)[2 * col + 1];
-        v[0] = t0.x; v[1] = t0.y; v[2] = t0.z; v[3] = t0.w;
-        v[4] = t1.x; v[5] = t1.y; v[6] = t1.z; v[7] = t1.w;
-    }
-}
-
 // Global-memory pointers with their address space spelled out: pointers that reach
 // a kernel through memory would otherwise be generic and cost flat loads.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
