@@ -348,6 +348,55 @@ def test_decompress_full_size_expert(gpu, ddict, oracle_dict):
         assert np.array_equal(o.cpu().numpy(), t)
 
 
+def test_layer_forward_in_a_hip_graph(gpu, ddict, oracle_dict):
+    """A layer call captured into a HIP graph (dispatch, both chains, the fork to the side
+    stream and the join) and replayed with other work in between: every replay must equal
+    the eager result bit for bit, also after the inputs change in place."""
+    counts = [70, 9, 3, 2, 1, 1, 0, 5]
+    idx = np.concatenate([np.full(n, e, dtype=np.int32) for e, n in enumerate(counts)])
+    np.random.default_rng(21).shuffle(idx)
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=len(counts), d_model=136, d_ff=264, n_tokens=idx.size)
+    x = w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    T = idx.size
+    d_x, d_idx = _to_dev16(x, gpu), torch.from_numpy(idx).to(gpu)
+    y = torch.zeros((T, w.d_model), dtype=torch.float32, device=gpu)
+    ws = layer.workspace(T)
+    q.qmoe_set_tuning("mfma_min_tokens", 8)  # both kinds of experts, hence both streams
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            layer.forward(ddict, d_x, d_idx, y, ws)  # warm-up outside the capture
+            torch.cuda.synchronize()
+            eager = y.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                layer.forward(ddict, d_x, d_idx, y, ws, stream=side.cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, eager), f"replay {rep}"
+            (y * 2).sum().item()  # unrelated eager work between replays
+        # new activations in the same buffers: the graph must follow
+        x2 = w.scaled(cfg_id=97).tokens()  # other seeds, same shape
+        d_x.copy_(_to_dev16(x2, gpu))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        layer.forward(ddict, d_x, d_idx, y, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(got, y)
+        wsout = dev.read_workspace(ws, w.n_experts, w.d_model, w.d_ff, T)
+        assert wsout["counters"][7] == 3
+        _check_layer(w, idx, x2, got.cpu().numpy(), wsout, list(range(T)))
+    finally:
+        q.qmoe_set_tuning("mfma_min_tokens", 0)
+
+
 def test_layer_drops_tokens_with_bad_expert_index(gpu, ddict, oracle_dict):
     w = synth.WORKLOADS["switch_base128"].scaled(n_experts=4, d_model=64, d_ff=96, n_tokens=20)
     idx, x = w.expert_idx(), w.tokens()
