@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <mutex>
+#include <type_traits>
 
 #include <atomic>
 #include <cstdio>
@@ -1003,6 +1004,89 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     }
 }
 
+// ---------------------------------------------------------------- one matrix, a few tokens: a row per 16 lanes
+//
+// A single matrix gives the lane-per-row kernel above a few thousand lanes, each walking a
+// whole row codeword by codeword: fine for throughput over hundreds of experts, slow as the
+// latency of one product.  Here 16 lanes (a DPP row) share a matrix row: every lane takes
+// one codeword of the next 16, the running column index of the sequential decoder becomes
+// an inclusive prefix sum of the 16 run lengths (four DPP row shifts, the previous step's
+// total carried in through lane 0), each lane gathers the activations of its own run, and
+// the 16 partial sums are added in a fixed order at the row's end.  rows x 16 lanes keep the
+// whole GPU busy with one matrix.  The table is read from L2 (no 65 KB staging per
+// workgroup: the launch is over in microseconds).
+template <bool RUN>
+__global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *xs_w = reinterpret_cast<uint16_t *>(smem);
+    const uint32_t xs_addr = (uint32_t)(uintptr_t)(lp_u16)xs_w;
+    constexpr int DICT = RUN ? kDictRun : kDictWords;
+    const qmoe_matrix M = a.single;
+    const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
+    const int row_blocks = (a.rows + ngrp - 1) / ngrp;
+    const int n_tiles = (a.batch + a.tb_max - 1) / a.tb_max;
+    const long long total = (long long)n_tiles * row_blocks;
+    gp_u16 xg = (gp_u16)a.x;
+    int cur_tile = -1, ntok = 0, slot0 = 0, tbi = 1;
+    for (long long g = blockIdx.x; g < total; g += gridDim.x) {
+        const int tile = (int)(g / row_blocks);
+        const int rb = (int)(g - (long long)tile * row_blocks);
+        if (tile != cur_tile) {
+            __syncthreads();  // everyone is done with the previous tile's activations
+            slot0 = tile * a.tb_max;
+            ntok = min(a.tb_max, a.batch - slot0);
+            tbi = ntok <= 1 ? 1 : (ntok <= 2 ? 2 : (ntok <= 4 ? 4 : 8));
+            if (tbi == 1) {
+                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
+                    uint32_t v = 0;
+                    if (c < a.cols) v = xg[(size_t)slot0 * a.ldx + c];
+                    reinterpret_cast<uint2 *>(xs_w)[c] = make_uint2(v << 16, 0u);  // {0, x, 0, 0}: lds_load_x<1> reads the second slot
+                }
+            } else {
+                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x)
+                    for (int t = 0; t < tbi; t++) {
+                        uint16_t v = 0;
+                        if (c < a.cols && t < ntok) v = xg[(size_t)(slot0 + t) * a.ldx + c];
+                        xs_w[(size_t)c * tbi + t] = v;
+                    }
+            }
+            __syncthreads();
+            cur_tile = tile;
+        }
+        const int r = rb * ngrp + grp;
+        if (r >= a.rows) continue;
+        const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
+        const uint32_t kbeg = min(M.row_off[r], kend);
+        const float scale = half_bits_to_float(M.scale_f16[r]);
+        auto row = [&](auto tag) {
+            constexpr int TBI = decltype(tag)::value;
+            float acc[TBI];
+#pragma unroll
+            for (int t = 0; t < TBI; t++) acc[t] = 0.0f;
+            int incl = 0;
+            for (uint32_t kb = kbeg; kb < kend; kb += 16) {
+                const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl);
+                const Entry e{s.e0, s.e1};
+                accumulate<TBI, DICT>(e, xs_addr, 8u * (uint32_t)s.start, acc);
+            }
+#pragma unroll
+            for (int t = 0; t < TBI; t++) acc[t] = row_sum16_to_last(acc[t]);
+            if (l16 == 15) {
+#pragma unroll
+                for (int t = 0; t < TBI; t++)
+                    if (t < ntok) reinterpret_cast<float *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] = acc[t] * scale;
+            }
+        };
+        switch (tbi) {
+        case 1: row(std::integral_constant<int, 1>{}); break;
+        case 2: row(std::integral_constant<int, 2>{}); break;
+        case 4: row(std::integral_constant<int, 4>{}); break;
+        default: row(std::integral_constant<int, 8>{}); break;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- decompression of whole matrices
 //
 // The codec without the product: dense ternary (int8) or scaled bf16 copies of compressed
@@ -1853,39 +1937,42 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     const int code_order = (int)W->code_order;
     if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
-    ProductPlan p;
-    if ((st = plan_product(W->rows, W->cols, run, ((long long)batch + 7) / 8 + 1, &p,
-                           code_order ? (int)d->order_table.size() : 0)) != QMOE_OK)
-        return st;
-    // grid sized for the real number of tiles
-    {
-        const long long items = (long long)((batch + p.tb_max - 1) / p.tb_max) * p.blocks_per_pass;
-        if (items < p.grid) p.grid = (int)std::max(1LL, items);
-    }
+    DeviceInfo di;
+    if ((st = device_info(&di)) != QMOE_OK) return st;
+    // activations of a tile in LDS: 8 bytes per column for up to four tokens, 16 for eight
+    int tb = batch > 4 ? 8 : 4;
+    auto xs_bytes = [&](int t) { return (size_t)(W->cols + kPadCols) * 2 * (size_t)t; };
+    if (tb == 8 && xs_bytes(8) > (size_t)di.max_lds) tb = 4;
+    if (xs_bytes(tb) > (size_t)di.max_lds) return QMOE_E_LIMIT;
+    if (tuning().token_tile > 0) tb = std::max(1, std::min(tb, tuning().token_tile));
     ProductArgs a{};
     a.mats = nullptr;
     a.single = *W;
     fill_tables(d, &a, code_order);
-    a.items = nullptr;
-    a.n_items_dev = nullptr;
-    a.max_items = 0;
     a.n_experts = 1;
     a.batch = batch;
-    a.perm = nullptr;
     a.x = x_bf16;
     a.x_by_slot = 1;
     a.ldx = W->cols;
     a.out = y;
     a.ld_out = W->rows;
-    a.gate = nullptr;
-    a.epilogue = 0;
     a.rows = W->rows;
     a.cols = W->cols;
-    a.rows_per_item = p.rows_per_item;
-    a.blocks_per_pass = p.blocks_per_pass;
-    a.tb_max = p.tb_max;
-    a.lds_dict_entries = p.lds_dict_entries;
-    return launch_product(a, p, run, static_cast<hipStream_t>(stream));
+    a.tb_max = tb;
+    const int threads = 256;  // 16 rows at a time
+    const long long items = (long long)((batch + tb - 1) / tb) * ((W->rows + threads / 16 - 1) / (threads / 16));
+    const int grid = (int)std::min<long long>(items, 8LL * di.cus);
+    const size_t smem = xs_bytes(std::max(tb, 4));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (run) {
+        if ((st = allow_lds(k_matvec_rows<true>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_matvec_rows<true>, dim3(grid), dim3(threads), smem, s, a);
+    } else {
+        if ((st = allow_lds(k_matvec_rows<false>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_matvec_rows<false>, dim3(grid), dim3(threads), smem, s, a);
+    }
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
 }
 
 qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W, int8_t *out, int path, void *stream)
