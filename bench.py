@@ -92,6 +92,31 @@ def dense_bf16_experts(layer, dd, active, gpu, stats=None):
     return ptrs["wi"], ptrs["wo"], keep
 
 
+def single_matvec(w, layer, dd, gpu, expert):
+    """The paper's per-matrix benchmark: one compressed expert matrix times one token
+    (`qmoe_decode_matvec`) next to torch.matmul on the same matrix in bf16, back-to-back
+    launches, microseconds per call."""
+    import torch
+    import paper_2310_16795_amd as q
+
+    out = {}
+    for which in ("wi", "wo"):
+        rows = layer.d_ff if which == "wi" else layer.d_model
+        cols = layer.d_model if which == "wi" else layer.d_ff
+        desc = layer.desc_host[which][expert]
+        x = torch.randn(1, cols, device=gpu).to(torch.bfloat16)
+        y = torch.empty(1, rows, dtype=torch.float32, device=gpu)
+        dense = torch.empty((rows, cols), dtype=torch.bfloat16, device=gpu)
+        q.qmoe_decompress(dd.handle, layer.desc_dev[which][40 * expert: 40 * expert + 40], 1, 1, rows, cols, 1,
+                          torch.tensor([dense.data_ptr()], dtype=torch.int64, device=gpu))
+        t_c, _ = time_steps(lambda: q.qmoe_decode_matvec(dd.handle, desc, x.view(torch.int16), y), 200, 20)
+        t_b, _ = time_steps(lambda: torch.matmul(x, dense.T), 200, 20)
+        ref = torch.matmul(x.float(), dense.float().T)
+        out[which] = {"rows": rows, "cols": cols, "compressed_us": t_c * 1e3, "bf16_torch_matmul_us": t_b * 1e3,
+                      "ratio": t_c / t_b, "max_abs_diff_vs_dense": float((y - ref).abs().max())}
+    return out
+
+
 def layer_bytes_of(layer, experts):
     return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + 6 * (layer.d_ff + layer.d_model)
                    for e in experts))
@@ -303,6 +328,9 @@ def main():
         "bits_per_param": 8.0 * layer.compressed_bytes / (w.n_experts * n_params),
         "stream_copy_GBps": copy_gbps,
     }
+
+    if not args.interchange_order:
+        result["single_matvec_batch1"] = single_matvec(w, layer, dd, gpu, active[0])
 
     if not args.no_bf16:
         t0 = time.time()
