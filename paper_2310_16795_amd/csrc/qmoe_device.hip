@@ -1652,7 +1652,9 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     // rows / lanes should round up with little waste since a wavefront is as slow as its
     // lane with the most rows.  Search workgroup sizes and block counts for the best fill.
     const int want_rpl = std::max(1, (int)std::ceil(256.0 / codes_per_row));
-    const int max_threads = fit >= 4 ? 256 : (fit >= 2 ? 512 : 1024);
+    // 768 rather than 1024 lanes: measured 4 % faster on 6144-row matrices (12 wavefronts keep
+    // the compute unit as busy as 16 do, and each gets more of the caches)
+    const int max_threads = fit >= 4 ? 256 : (fit >= 2 ? 512 : 768);
     int best_t = 64, best_b = 1;
     double best_score = -1.0;
     for (int b = 1; b <= 64; b++) {
@@ -1662,8 +1664,8 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
             const int rpl = (int)((rows + nl - 1) / nl);
             if (rpl < want_rpl && force_blocks <= 0 && !(b == 1 && t == 64)) continue;
             const double fill = (double)rows / ((double)nl * rpl);
-            // prefer full workgroups (occupancy) and few blocks (less restaging)
-            const double score = fill * std::min(1.0, (double)t / (0.625 * max_threads)) - 0.002 * b;
+            // fill first, then larger workgroups (occupancy) and few blocks (less restaging)
+            const double score = fill * (0.75 + 0.25 * (double)t / max_threads) - 0.002 * b;
             if (score > best_score) { best_score = score; best_t = t; best_b = b; }
         }
     }
