@@ -208,6 +208,9 @@ def main():
     ap.add_argument("--no-bf16", action="store_true", help="skip the uncompressed comparator")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--tune", action="append", default=[], help="key=value for qmoe_set_tuning")
+    ap.add_argument("--dict-entries", type=int, default=65536,
+                    help="dictionary size (the paper's is 65536; smaller tables trade bits per parameter for LDS)")
+    ap.add_argument("--dict-max-pairs", type=int, default=14, help="longest dictionary entry in pairs (the paper's is 14)")
     ap.add_argument("--interchange-order", action="store_true",
                     help="leave the codeword streams as encoded instead of renumbering them at load time")
     args = ap.parse_args()
@@ -236,7 +239,9 @@ def main():
     log(f"workload {w.name}: {w.n_experts} experts {w.d_model}x{w.d_ff}, {T} tokens, {len(active)} experts with tokens, "
         f"max {counts.max()} tokens on one expert")
 
-    dd = dev.DeviceDict(device=gpu)
+    custom_dict = (args.dict_entries, args.dict_max_pairs) != (65536, 14)
+    dd = dev.DeviceDict(q.qmoe_dict_create(0.885, args.dict_max_pairs, args.dict_entries) if custom_dict else None,
+                        device=gpu)
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
     layer = build_layer(w, dd, gpu, workers, args.interchange_order)
@@ -305,7 +310,8 @@ def main():
         "config": {"workload": w.name, "n_experts": w.n_experts, "d_model": w.d_model, "d_ff": w.d_ff,
                    "tokens": T, "experts_with_tokens": len(active), "routing": w.routing,
                    "zero_fraction": "0.80-0.97 per row" if w.p0_spread else w.p0,
-                   "code_order": "interchange" if args.interchange_order else "device"},
+                   "code_order": "interchange" if args.interchange_order else "device",
+                   "dict_entries": args.dict_entries, "dict_max_pairs": args.dict_max_pairs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
                      "kernel_ms": dom[1], "algorithmic_bytes": dom[2]},
