@@ -408,6 +408,42 @@ def test_layer_drops_tokens_with_bad_expert_index(gpu, ddict, oracle_dict):
     _check_layer(w, idx, x, y, wsout, good)
 
 
+def test_layer_with_every_token_dropped(gpu, ddict, oracle_dict):
+    """No token names a valid expert: nothing to multiply, every output row is zero, and
+    the poisoned descriptors of the experts are never read."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=4, d_model=64, d_ff=96, n_tokens=9)
+    x = w.tokens()
+    idx = np.array([-1, 4, 7, -3, 2 ** 30, -(2 ** 31), 4, 5, 99], dtype=np.int32)
+    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu).finalize(device_order_of=ddict)  # no expert set
+    y, wsout = _run_layer(layer, ddict, x, idx, gpu)
+    assert not y.any()
+    assert wsout["counters"][0] == 0 and wsout["counters"][1] == idx.size and wsout["counters"][2] == 0
+    assert wsout["counters"][3] == 0 and wsout["counters"][4] == 0 and wsout["counters"][7] == 0
+
+
+def test_dispatch_many_tokens(gpu):
+    """100 000 tokens on 2048 experts, Zipf-like crowding: the single-workgroup dispatch at scale."""
+    rng = np.random.default_rng(9)
+    E, T = 2048, 100_000
+    idx = np.minimum((rng.pareto(1.1, T) * 3).astype(np.int64), E - 1).astype(np.int32)
+    dd = dev.DeviceDict(device=gpu)
+    ws = torch.empty(q.qmoe_moe_layer_workspace(E, 64, 128, T), dtype=torch.uint8, device=gpu)
+    q.qmoe_moe_dispatch(dd.handle, 1, torch.from_numpy(idx).to(gpu), E, 64, 128, ws)
+    torch.cuda.synchronize()
+    got = dev.read_workspace(ws, E, 64, 128, T)
+    tok_off, perm = oracle.dispatch(idx, E)
+    assert np.array_equal(got["tok_off"], tok_off) and np.array_equal(got["perm"], perm)
+    counts = np.diff(tok_off)
+    n_mm = got["counters"][7]
+    assert n_mm == int(sum((c + 63) // 64 for c in counts if c >= 8))
+    covered = np.zeros(T, dtype=np.int32)
+    for items, n in ((got["items_mm"], n_mm), (got["items_wi"], got["counters"][3])):
+        for e, slot0, ntok, _ in items[:n]:
+            covered[slot0:slot0 + ntok] += 1
+    assert np.all(covered == 1)
+    dd.close()
+
+
 def test_layer_single_token(gpu, ddict, oracle_dict):
     w = synth.WORKLOADS["switch_base128"].scaled(n_experts=3, d_model=770, d_ff=130, n_tokens=1)
     idx, x = w.expert_idx(), w.tokens()
