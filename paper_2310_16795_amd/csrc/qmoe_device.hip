@@ -79,6 +79,7 @@ struct ProductArgs {
     int rows_per_item, blocks_per_pass;
     int tb_max;
     int lds_dict_entries;     // leading run entries copied to LDS (0 = none)
+    int stage_out;            // first product: results of a block staged in LDS and written as whole lines (LDS after the table)
     int *work_counter;        // device counter (zeroed by the dispatch kernel) for handing out items, or nullptr
     const uint32_t *order_table;  // device-order table (n_order entries, the first n_groups are groups)
     int n_groups, n_order;
@@ -301,6 +302,8 @@ struct RowSink {
     const __attribute__((address_space(3))) int *tok_ids;   // output token of each tile slot
     const __attribute__((address_space(3))) float *gate_s;  // gate of each tile slot
     int ntok, slot0;
+    uint32_t out_s;   // LDS byte address of the block's staged bf16 results [tile][out_rows], 0 = none
+    int out_rows;     // rows of the block
 };
 
 template <int TBI, int EPI>
@@ -317,8 +320,15 @@ __device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<
                 reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = rs.gate_s[t] * v;
             } else {
                 const float h = v > 0.0f ? v : 0.0f;
-                reinterpret_cast<uint16_t *>(a.out)[(size_t)(rs.slot0 + t) * a.ld_out + st.row] =
-                    float_to_bf16_bits(h);
+                if (rs.out_s) {
+                    // a pass's hidden values leave the compute unit as whole lines at its end
+                    // (one 2-byte store per lane and row would reach HBM as partial lines)
+                    *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)(
+                        rs.out_s + 2u * (uint32_t)(t * rs.out_rows + (st.row - rs.r0))) = float_to_bf16_bits(h);
+                } else {
+                    reinterpret_cast<uint16_t *>(a.out)[(size_t)(rs.slot0 + t) * a.ld_out + st.row] =
+                        float_to_bf16_bits(h);
+                }
             }
         }
     }
@@ -528,6 +538,8 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     uint16_t *scale_w = reinterpret_cast<uint16_t *>(smem + xs_bytes + 128);  // [rows_per_item] row scales
     const size_t scale_bytes = ((size_t)a.rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
     uint32_t *lds_run_w = reinterpret_cast<uint32_t *>(smem + xs_bytes + 128 + scale_bytes);
+    const size_t table_entries = DICT == kDictOrder ? (size_t)a.n_order : (DICT == kDictRunLds ? (size_t)a.lds_dict_entries : 0);
+    uint16_t *out_w = reinterpret_cast<uint16_t *>(smem + xs_bytes + 128 + scale_bytes + ((table_entries * 4 + 15) & ~(size_t)15));
     lp_u16 xs = (lp_u16)xs_w;
     lp_u32 lds_run = (lp_u32)lds_run_w;
     const uint32_t xs_addr = (uint32_t)(uintptr_t)xs;  // LDS byte address of the activations
@@ -631,11 +643,31 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         rs.gate_s = (const __attribute__((address_space(3))) float *)gate_s;
         rs.ntok = ntok;
         rs.slot0 = slot0;
+        const bool staged = EPI == 1 && a.stage_out && (r0 % 8) == 0;
+        rs.out_s = staged ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)out_w : 0u;
+        rs.out_rows = (r1 - r0 + 7) & ~7;
         switch (tbi) {
         case 1: product_block<1, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         case 2: product_block<2, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         case 4: product_block<4, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         default: product_block<8, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
+        }
+        if constexpr (EPI == 1) {
+            if (staged) {
+                __syncthreads();  // every row of the block is staged
+                const int nrows = r1 - r0, per_tok = rs.out_rows / 8;  // 16-byte pieces per token
+                uint16_t *hidden = reinterpret_cast<uint16_t *>(a.out);
+                for (int i = threadIdx.x; i < ntok * per_tok; i += blockDim.x) {
+                    const int t = i / per_tok, j = i - t * per_tok;
+                    const uint16_t *src = out_w + (size_t)t * rs.out_rows + 8 * j;
+                    uint16_t *dst = hidden + (size_t)(slot0 + t) * a.ld_out + r0 + 8 * j;
+                    if (8 * j + 8 <= nrows) {
+                        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+                    } else {
+                        for (int k = 0; 8 * j + k < nrows; k++) dst[k] = src[k];
+                    }
+                }
+            }
         }
     }
 }
@@ -1596,13 +1628,14 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct ProductPlan {
     int threads, rows_per_item, blocks_per_pass, tb_max, lds_dict_entries, grid;
+    int stage_out;  // results of a block staged in LDS (first product of a layer, LDS permitting)
     size_t smem;
 };
 
 // Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
 // matrices with the lane-per-row kernel (compressed path).
 qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p,
-                         int n_order = 0, int force_blocks = 0)
+                         int n_order = 0, int force_blocks = 0, int stage_out_row_bytes = 0)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
@@ -1689,6 +1722,16 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     p->lds_dict_entries = lds_dict;
     p->smem = xs_bytes(tb) + fixed + scale_bytes + 4 * (size_t)lds_dict;
     if (p->smem > max_lds) return QMOE_E_LIMIT;
+    p->stage_out = 0;
+    if (stage_out_row_bytes > 0) {
+        // [tile][rows of a block, rounded up to 8] values after the table (itself rounded up to 16 bytes)
+        const size_t table_end = xs_bytes(tb) + fixed + scale_bytes + ((4 * (size_t)lds_dict + 15) & ~(size_t)15);
+        const size_t need = (size_t)tb * (((size_t)p->rows_per_item + 7) & ~(size_t)7) * stage_out_row_bytes;
+        if (table_end + need <= max_lds) {
+            p->stage_out = 1;
+            p->smem = table_end + need;
+        }
+    }
     const int wg_per_cu = tu.grid_per_cu > 0 ? tu.grid_per_cu : std::max(1, std::min(fit, 2048 / best_t));
     long long grid = (long long)di.cus * wg_per_cu;
     const long long items = max_passes_hint * p->blocks_per_pass;
@@ -2085,7 +2128,8 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     MmPlan mp;
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
-                           tuning().blocks_first > 0 ? tuning().blocks_first : spread)) != QMOE_OK)
+                           tuning().blocks_first > 0 ? tuning().blocks_first : spread,
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
@@ -2113,7 +2157,8 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     ProductPlan pwi, pwo;
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
-                           tuning().blocks_first > 0 ? tuning().blocks_first : spread)) != QMOE_OK)
+                           tuning().blocks_first > 0 ? tuning().blocks_first : spread,
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
@@ -2195,6 +2240,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a1.blocks_per_pass = pwi.blocks_per_pass;
     a1.tb_max = pwi.tb_max;
     a1.lds_dict_entries = pwi.lds_dict_entries;
+    a1.stage_out = pwi.stage_out;
     a1.work_counter = lp.counters + 5;
     if (phases & 2)
         if ((st = launch_product(a1, pwi, run, s_scalar)) != QMOE_OK) return st;

@@ -424,6 +424,7 @@ qmoe_status qmoe_set_tuning(const char *key, int value)
     else if (!std::strcmp(key, "mfma_min_tokens")) t.mfma_min_tokens = value;
     else if (!std::strcmp(key, "mm_stagger")) t.mm_stagger = value;
     else if (!std::strcmp(key, "overlap")) t.overlap = value;
+    else if (!std::strcmp(key, "stage_out")) t.stage_out = value;
     else if (!std::strcmp(key, "phases")) t.phases = value;
     else return QMOE_E_INVALID_ARG;
     return QMOE_OK;
