@@ -149,6 +149,24 @@ qmoe_status qmoe_encode_host(const qmoe_dict *d, const int8_t *tern /*host [rows
 qmoe_status qmoe_validate_host(const qmoe_dict *d, const uint16_t *codes /*host*/,
                                const uint32_t *row_off /*host [rows+1]*/, int rows, int cols);
 
+/*
+ * The same encoder on the device (Section 4.3.3 "Encoding"), one matrix row per lane:
+ * ternary (device, row-major int8 [rows][cols], values -1/0/+1) is coded into codes
+ * (device, capacity codes_cap codewords, interchange numbering -- run
+ * qmoe_codes_to_device_order on it afterwards for the device numbering) and row_off
+ * (device [rows+1]); row_off[rows] is the number of codewords.  Codeword for codeword the
+ * stream qmoe_encode_host produces.  Nothing is read back: status (device int32[2]) holds
+ * 0 or the first error (BAD_SYMBOL, UNENCODABLE, BUFFER_TOO_SMALL) and a row it happened
+ * in once the work on `stream` is done; with an error the contents of codes are
+ * undefined.  Enqueues a 8-byte memset of status and three kernels; do not capture it
+ * into a HIP graph (memset node).
+ * Errors at the call: INVALID_ARG, NO_DEVICE_DICT, LIMIT (the table's trie has more than
+ * 131072 nodes), HIP.
+ */
+qmoe_status qmoe_encode_device(const qmoe_dict *d, const int8_t *ternary /*device*/, int rows, int cols,
+                               uint16_t *codes /*device*/, size_t codes_cap, uint32_t *row_off /*device*/,
+                               int32_t *status /*device*/, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Device kernels (Section 4.3.3 "GPU Kernel")                                */
 /* ------------------------------------------------------------------------- */

@@ -42,7 +42,7 @@ EXPORTS = [
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
     "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
-    "qmoe_codes_to_device_order", "qmoe_decompress",
+    "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device",
 ]
 
 
@@ -74,6 +74,7 @@ def lib():
         L.qmoe_codes_to_device_order.argtypes = [vp, vp, sz, vp]
         L.qmoe_moe_dispatch.argtypes = [vp, i, vp, i, i, i, i, vp, sz, vp]
         L.qmoe_decompress.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
+        L.qmoe_encode_device.argtypes = [vp, vp, i, i, vp, sz, vp, vp, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
         L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -243,6 +244,16 @@ def qmoe_moe_dispatch(d, code_order: int, expert_idx, n_experts: int, d_model: i
     _check(lib().qmoe_moe_dispatch(d, code_order, _dev_ptr(expert_idx), expert_idx.numel(), n_experts, d_model, d_ff,
                                    _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream_ptr(stream)), "qmoe_moe_dispatch")
+
+
+def qmoe_encode_device(d, ternary, codes, row_off, status, stream=None) -> None:
+    """ternary: device int8 [rows, cols]; codes: device 16-bit [capacity]; row_off: device 32-bit [rows + 1];
+    status: device int32 [2].  Asynchronous: check status[0] == 0 after synchronising."""
+    rows, cols = ternary.shape
+    if row_off.numel() != rows + 1 or status.numel() < 2:
+        raise ValueError("shape mismatch")
+    _check(lib().qmoe_encode_device(d, _dev_ptr(ternary), rows, cols, _dev_ptr(codes), codes.numel(),
+                                    _dev_ptr(row_off), _dev_ptr(status), _stream_ptr(stream)), "qmoe_encode_device")
 
 
 def qmoe_decompress(d, mats, code_order: int, n_mats: int, rows: int, cols: int, out_kind: int, out_ptrs,

@@ -1421,6 +1421,80 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
     }
 }
 
+// ---------------------------------------------------------------- encoder
+//
+// Longest-prefix coding of ternary rows with the dictionary's trie (Section 4.3.3
+// "Encoding"), one row per lane: walk pairs from the root while a child exists, emit the
+// codeword of the deepest node that ends an entry, continue after that entry.  Three
+// launches: count codewords per row, turn the counts into row offsets (one workgroup), write
+// the codewords.  Same stream as qmoe_encode_host, codeword for codeword.
+
+struct EncodeArgs {
+    const int8_t *tern;   // [rows][cols], values -1 / 0 / +1
+    int rows, cols;
+    const int32_t *child, *code;
+    uint32_t *row_off;    // [rows+1]
+    uint16_t *codes;
+    unsigned long long codes_cap;
+    int *status;          // [2]: first error (qmoe_status, 0 = none), a row it happened in
+};
+
+template <bool WRITE>
+__global__ __launch_bounds__(256) void k_encode(const EncodeArgs a)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= a.rows) return;
+    if (WRITE && a.status[0] != 0) return;
+    const int8_t *row = a.tern + (size_t)r * a.cols;
+    const int np = a.cols / 2;
+    const size_t out = WRITE ? (size_t)a.row_off[r] : 0;
+    uint32_t n = 0;
+    int bad = 0;
+    int i = 0;
+    while (i < np) {
+        int node = 0, best = -1, best_len = 0, depth = 0;
+        while (i + depth < np) {
+            const int va = row[2 * (i + depth)], vb = row[2 * (i + depth) + 1];
+            if (va < -1 || va > 1 || vb < -1 || vb > 1) { bad = QMOE_E_BAD_SYMBOL; break; }
+            // value -> symbol: 0 -> 0, -1 -> 1, +1 -> 2; pair index = 3 * first + second
+            const int sa = va == 0 ? 0 : (va < 0 ? 1 : 2), sb = vb == 0 ? 0 : (vb < 0 ? 1 : 2);
+            const int nx = a.child[(size_t)node * 9 + 3 * sa + sb];
+            if (nx < 0) break;
+            node = nx;
+            depth++;
+            const int c = a.code[node];
+            if (c >= 0) { best = c; best_len = depth; }
+        }
+        if (bad) break;
+        if (best < 0) { bad = QMOE_E_UNENCODABLE; break; }
+        if (WRITE) a.codes[out + n] = (uint16_t)best;
+        n++;
+        i += best_len;
+    }
+    if (bad) {
+        if (atomicCAS(&a.status[0], 0, bad) == 0) a.status[1] = r;
+        n = 0;
+    }
+    if (!WRITE) a.row_off[r + 1] = n;
+}
+
+// counts in row_off[1..rows] -> offsets; one workgroup
+__global__ __launch_bounds__(1024) void k_encode_offsets(const EncodeArgs a)
+{
+    __shared__ int tmp[32];
+    unsigned long long base = 0;
+    if (threadIdx.x == 0) a.row_off[0] = 0;
+    for (int r0 = 0; r0 < a.rows; r0 += (int)blockDim.x) {
+        const int r = r0 + (int)threadIdx.x;
+        const int c = r < a.rows ? (int)a.row_off[r + 1] : 0;
+        int total;
+        const int excl = block_exclusive_scan(c, tmp, total);
+        if (r < a.rows) a.row_off[r + 1] = (uint32_t)(base + (unsigned long long)(excl + c));
+        base += (unsigned long long)total;
+    }
+    if (threadIdx.x == 0 && (base > a.codes_cap || base > 0xFFFFFFFFull)) atomicCAS(&a.status[0], 0, QMOE_E_BUFFER_TOO_SMALL);
+}
+
 // ---------------------------------------------------------------- uncompressed bf16 comparator
 
 struct DenseArgs {
@@ -1969,7 +2043,40 @@ qmoe_status qmoe_dict_upload(qmoe_dict *d, void *dev_buf, size_t dev_bytes, void
         QMOE_HIP_TRY(hipMemcpyAsync(b + kDevOrderMapOffset, d->order_map.data(), sizeof(uint16_t) * kTableEntries,
                                     hipMemcpyHostToDevice, s));
     }
+    if (!d->code.empty() && d->code.size() <= (size_t)kMaxTrieNodes) {
+        QMOE_HIP_TRY(hipMemcpyAsync(b + kDevTrieChildOffset, d->child.data(), sizeof(int32_t) * d->child.size(),
+                                    hipMemcpyHostToDevice, s));
+        QMOE_HIP_TRY(hipMemcpyAsync(b + kDevTrieCodeOffset, d->code.data(), sizeof(int32_t) * d->code.size(),
+                                    hipMemcpyHostToDevice, s));
+    }
     d->dev = dev_buf;
+    return QMOE_OK;
+}
+
+qmoe_status qmoe_encode_device(const qmoe_dict *d, const int8_t *ternary, int rows, int cols, uint16_t *codes,
+                               size_t codes_cap, uint32_t *row_off, int32_t *status, void *stream)
+{
+    if (!d || !ternary || !codes || !row_off || !status || rows < 1 || cols < 2 || (cols & 1)) return QMOE_E_INVALID_ARG;
+    if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
+    if (d->code.empty() || d->code.size() > (size_t)kMaxTrieNodes) return QMOE_E_LIMIT;
+    const unsigned char *base = static_cast<const unsigned char *>(d->dev);
+    EncodeArgs a{};
+    a.tern = ternary;
+    a.rows = rows;
+    a.cols = cols;
+    a.child = reinterpret_cast<const int32_t *>(base + kDevTrieChildOffset);
+    a.code = reinterpret_cast<const int32_t *>(base + kDevTrieCodeOffset);
+    a.row_off = row_off;
+    a.codes = codes;
+    a.codes_cap = codes_cap;
+    a.status = status;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    QMOE_HIP_TRY(hipMemsetAsync(status, 0, 2 * sizeof(int32_t), s));
+    const int grid = (rows + 255) / 256;
+    hipLaunchKernelGGL(k_encode<false>, dim3(grid), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_encode_offsets, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(k_encode<true>, dim3(grid), dim3(256), 0, s, a);
+    QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }
 

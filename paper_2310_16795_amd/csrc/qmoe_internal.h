@@ -46,7 +46,14 @@ constexpr size_t kDevRunOffset = 0;
 constexpr size_t kDevWordsOffset = sizeof(uint32_t) * kTableEntries;
 constexpr size_t kDevOrderTableOffset = kDevWordsOffset + 2 * sizeof(uint32_t) * kTableEntries;
 constexpr size_t kDevOrderMapOffset = kDevOrderTableOffset + sizeof(uint32_t) * kMaxOrderTable;
-constexpr size_t kDevDictBytes = kDevOrderMapOffset + sizeof(uint16_t) * kTableEntries;
+// ... then the encoder's trie for qmoe_encode_device: child[node][9] (next node by pair, -1 =
+// none; node 0 is the root) and code[node] (codeword that ends here, -1 = none).  A
+// prefix-closed table (the paper's is) has n_entries + 1 nodes; tables with more than
+// kMaxTrieNodes nodes cannot be used by the device encoder.
+constexpr int kMaxTrieNodes = 1 << 17;
+constexpr size_t kDevTrieChildOffset = (kDevOrderMapOffset + sizeof(uint16_t) * kTableEntries + 255) / 256 * 256;
+constexpr size_t kDevTrieCodeOffset = kDevTrieChildOffset + sizeof(int32_t) * 9 * kMaxTrieNodes;
+constexpr size_t kDevDictBytes = kDevTrieCodeOffset + sizeof(int32_t) * kMaxTrieNodes;
 
 struct Tuning {
     int threads = 0;

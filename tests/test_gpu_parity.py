@@ -328,6 +328,44 @@ def test_decompress_whole_matrices_bit_exact(gpu, ddict, oracle_dict, d_model, d
                     assert np.array_equal(got.view(np.uint16), want.astype(np.uint16)), f"{which} expert {e}"
 
 
+@pytest.mark.parametrize("rows,cols,p0,seed", [(1, 2, 0.5, 1), (7, 58, 0.9, 2), (300, 136, 0.885, 3), (2080, 6144, 0.9, 4),
+                                               (513, 770, 0.3, 5)])
+def test_encode_device_equals_the_oracle_stream(gpu, ddict, oracle_dict, rows, cols, p0, seed):
+    """The device encoder's codewords and row offsets against the oracle's longest-prefix coder."""
+    tern = synth.ternary(seed, rows, cols, p0)
+    codes_ref, off_ref = oracle.encode(oracle_dict, tern)
+    d_t = torch.from_numpy(tern).to(gpu)
+    d_codes = torch.full((codes_ref.size + 8,), -1, dtype=torch.int16, device=gpu)
+    d_off = torch.empty(rows + 1, dtype=torch.int32, device=gpu)
+    d_status = torch.full((2,), 99, dtype=torch.int32, device=gpu)
+    q.qmoe_encode_device(ddict.handle, d_t, d_codes, d_off, d_status)
+    torch.cuda.synchronize()
+    assert d_status[0].item() == 0
+    assert np.array_equal(d_off.cpu().numpy().view(np.uint32), off_ref.astype(np.uint32))
+    got = d_codes.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[: codes_ref.size], codes_ref) and (got[codes_ref.size:] == 0xFFFF).all()
+
+
+def test_encode_device_reports_errors(gpu, ddict, oracle_dict):
+    tern = synth.ternary(9, 20, 64, 0.9)
+    n_ref = oracle.encode(oracle_dict, tern)[0].size
+    d_off = torch.empty(21, dtype=torch.int32, device=gpu)
+    d_status = torch.zeros(2, dtype=torch.int32, device=gpu)
+    # capacity one codeword short
+    d_codes = torch.zeros(n_ref - 1, dtype=torch.int16, device=gpu)
+    q.qmoe_encode_device(ddict.handle, torch.from_numpy(tern).to(gpu), d_codes, d_off, d_status)
+    torch.cuda.synchronize()
+    assert d_status[0].item() == -2  # BUFFER_TOO_SMALL
+    assert d_off[-1].item() == n_ref  # the size needed is still reported
+    # a value that is no ternary symbol
+    bad = tern.copy()
+    bad[11, 5] = 2
+    d_codes = torch.zeros(n_ref + 8, dtype=torch.int16, device=gpu)
+    q.qmoe_encode_device(ddict.handle, torch.from_numpy(bad).to(gpu), d_codes, d_off, d_status)
+    torch.cuda.synchronize()
+    assert d_status[0].item() == -3 and d_status[1].item() == 11  # BAD_SYMBOL in row 11
+
+
 def test_decompress_full_size_expert(gpu, ddict, oracle_dict):
     """Two c2048-sized matrices (2080 x 6144): the oracle's decode of the oracle's stream."""
     w = synth.WORKLOADS["c2048"]

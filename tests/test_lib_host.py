@@ -35,7 +35,8 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
     assert ctypes.sizeof(q.qmoe_matrix) == 40
     assert L.qmoe_strerror(0) == b"ok" and L.qmoe_strerror(-4) == b"corrupt codeword stream"
-    assert q.qmoe_dict_device_bytes() == 65536 * 4 + 65536 * 8 + 20480 * 4 + 65536 * 2
+    # run entries, interchange words, device-order table and map, then the encoder's trie (2^17 nodes)
+    assert q.qmoe_dict_device_bytes() == 65536 * 4 + 65536 * 8 + 20480 * 4 + 65536 * 2 + (9 + 1) * 4 * (1 << 17)
 
 
 def test_dictionary_equals_oracle_table(lib_dict, oracle_dict):
@@ -200,6 +201,9 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     assert L.qmoe_dict_upload(lib_dict, 256, 10, None) == -2
     assert L.qmoe_bf16_layer_forward(256, 256, 4, 12, 16, 256, 256, None, 4, 256, 256, 1 << 30, None) == -1
     assert L.qmoe_decompress(lib_dict, 256, 1, 2, 8, 16, 0, 256, None) == -9               # not uploaded
+    assert L.qmoe_encode_device(lib_dict, 256, 4, 8, 256, 100, 256, 256, None) == -9
+    assert L.qmoe_encode_device(lib_dict, 256, 4, 7, 256, 100, 256, 256, None) == -1       # odd cols
+    assert L.qmoe_encode_device(lib_dict, 256, 4, 8, 256, 100, 256, None, None) == -1      # no status
     assert L.qmoe_decompress(lib_dict, 256, 1, 2, 8, 12, 0, 256, None) == -1               # cols % 8
     assert L.qmoe_decompress(lib_dict, None, 1, 2, 8, 16, 0, 256, None) == -1
     assert L.qmoe_moe_dispatch(lib_dict, 0, 256, 4, 4, 8, 16, 256, 16, None) == -5
