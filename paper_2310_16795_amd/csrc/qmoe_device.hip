@@ -302,7 +302,7 @@ struct RowSink {
     const __attribute__((address_space(3))) int *tok_ids;   // output token of each tile slot
     const __attribute__((address_space(3))) float *gate_s;  // gate of each tile slot
     int ntok, slot0;
-    uint32_t out_s;   // LDS byte address of the block's staged bf16 results [tile][out_rows], 0 = none
+    uint32_t out_s;   // LDS byte address of the block's staged results [tile][out_rows] (bf16 or fp32), 0 = none
     int out_rows;     // rows of the block
 };
 
@@ -316,8 +316,13 @@ __device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<
         if (t < rs.ntok) {
             const float v = sum[t] * scale;
             if constexpr (EPI == 0) {
-                const int tok = rs.tok_ids[t];
-                reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = rs.gate_s[t] * v;
+                if (rs.out_s) {
+                    *(__attribute__((address_space(3))) float *)(uintptr_t)(
+                        rs.out_s + 4u * (uint32_t)(t * rs.out_rows + (st.row - rs.r0))) = rs.gate_s[t] * v;
+                } else {
+                    const int tok = rs.tok_ids[t];
+                    reinterpret_cast<float *>(a.out)[(size_t)tok * a.ld_out + st.row] = rs.gate_s[t] * v;
+                }
             } else {
                 const float h = v > 0.0f ? v : 0.0f;
                 if (rs.out_s) {
@@ -643,7 +648,7 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         rs.gate_s = (const __attribute__((address_space(3))) float *)gate_s;
         rs.ntok = ntok;
         rs.slot0 = slot0;
-        const bool staged = EPI == 1 && a.stage_out && (r0 % 8) == 0;
+        const bool staged = a.stage_out && (r0 % 8) == 0;
         rs.out_s = staged ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)out_w : 0u;
         rs.out_rows = (r1 - r0 + 7) & ~7;
         switch (tbi) {
@@ -652,20 +657,23 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         case 4: product_block<4, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         default: product_block<8, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
         }
-        if constexpr (EPI == 1) {
-            if (staged) {
-                __syncthreads();  // every row of the block is staged
-                const int nrows = r1 - r0, per_tok = rs.out_rows / 8;  // 16-byte pieces per token
-                uint16_t *hidden = reinterpret_cast<uint16_t *>(a.out);
-                for (int i = threadIdx.x; i < ntok * per_tok; i += blockDim.x) {
-                    const int t = i / per_tok, j = i - t * per_tok;
-                    const uint16_t *src = out_w + (size_t)t * rs.out_rows + 8 * j;
-                    uint16_t *dst = hidden + (size_t)(slot0 + t) * a.ld_out + r0 + 8 * j;
-                    if (8 * j + 8 <= nrows) {
-                        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
-                    } else {
-                        for (int k = 0; 8 * j + k < nrows; k++) dst[k] = src[k];
-                    }
+        if (staged) {
+            // the block's results, staged in LDS, go out as whole 16-byte pieces
+            __syncthreads();
+            constexpr int kPer = EPI == 1 ? 8 : 4;  // values per piece
+            using value_t = typename std::conditional<EPI == 1, uint16_t, float>::type;
+            const int nrows = r1 - r0, per_tok = rs.out_rows / kPer;
+            const value_t *stage = reinterpret_cast<const value_t *>(out_w);
+            value_t *out = reinterpret_cast<value_t *>(a.out);
+            for (int i = threadIdx.x; i < ntok * per_tok; i += blockDim.x) {
+                const int t = i / per_tok, j = i - t * per_tok;
+                const size_t out_row = EPI == 1 ? (size_t)(slot0 + t) : (size_t)tok_ids[t];
+                const value_t *src = stage + (size_t)t * rs.out_rows + kPer * j;
+                value_t *dst = out + out_row * a.ld_out + r0 + kPer * j;
+                if (kPer * j + kPer <= nrows) {
+                    *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+                } else {
+                    for (int k = 0; kPer * j + k < nrows; k++) dst[k] = src[k];
                 }
             }
         }
@@ -2239,7 +2247,8 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
                            (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
-                           tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
+                           tuning().blocks_second > 0 ? tuning().blocks_second : spread,
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0)) != QMOE_OK)
         return st;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
@@ -2268,7 +2277,8 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
                            (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
-                           tuning().blocks_second > 0 ? tuning().blocks_second : spread)) != QMOE_OK)
+                           tuning().blocks_second > 0 ? tuning().blocks_second : spread,
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0)) != QMOE_OK)
         return st;
     MmPlan mp;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
@@ -2357,6 +2367,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a2.blocks_per_pass = pwo.blocks_per_pass;
     a2.tb_max = pwo.tb_max;
     a2.lds_dict_entries = pwo.lds_dict_entries;
+    a2.stage_out = pwo.stage_out && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     a2.work_counter = lp.counters + 6;
     if (phases & 4)
         if ((st = launch_product(a2, pwo, run, s_scalar)) != QMOE_OK) return st;
