@@ -55,6 +55,10 @@ def _load():
         lib.orc_matvec.restype = None
         lib.orc_ffn_token.argtypes = [vp, vp, vp, vp, vp, i64, i64, dbl, vp, vp, vp]
         lib.orc_ffn_token.restype = None
+        lib.orc_matvec_asym.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+        lib.orc_matvec_asym.restype = None
+        lib.orc_ffn_token_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, dbl, vp, vp, vp]
+        lib.orc_ffn_token_asym.restype = None
         lib.orc_dispatch.argtypes = [vp, i64, i64, vp, vp]
         lib.orc_dispatch.restype = None
         lib.orc_bf16_to_double.argtypes = [c.c_uint16]
@@ -165,8 +169,11 @@ def decode(words: np.ndarray, codes: np.ndarray, row_off: np.ndarray, rows: int,
     return out
 
 
-def matvec(tern: np.ndarray, scale_f16: np.ndarray, x_bf16: np.ndarray, with_bound: bool = False):
-    """y[b, r] = s_r * sum_c T[r, c] x[b, c] in fp64.  x_bf16: uint16 [batch, cols]."""
+def matvec(tern: np.ndarray, scale_f16: np.ndarray, x_bf16: np.ndarray, with_bound: bool = False,
+           scale_neg_f16: np.ndarray | None = None):
+    """y[b, r] = s_r * sum_c T[r, c] x[b, c] in fp64.  x_bf16: uint16 [batch, cols].
+    With scale_neg_f16 the row's grid is {-n_r, 0, +s_r} (Section 4.1; "Ternary decoding" in Section 4.3.3): y = s_r * sum over the
+    positive weights - n_r * sum over the negative ones."""
     lib = _load()
     tern = np.ascontiguousarray(tern, dtype=np.int8)
     rows, cols = tern.shape
@@ -175,12 +182,18 @@ def matvec(tern: np.ndarray, scale_f16: np.ndarray, x_bf16: np.ndarray, with_bou
     assert s.shape == (rows,)
     y = np.zeros((x.shape[0], rows), dtype=np.float64)
     bound = np.zeros_like(y) if with_bound else None
-    lib.orc_matvec(_p(tern), _p(s), _p(x), rows, cols, x.shape[0], _p(y),
-                   _p(bound) if with_bound else None)
+    if scale_neg_f16 is None:
+        lib.orc_matvec(_p(tern), _p(s), _p(x), rows, cols, x.shape[0], _p(y),
+                       _p(bound) if with_bound else None)
+    else:
+        n = np.ascontiguousarray(scale_neg_f16, dtype=np.uint16)
+        assert n.shape == (rows,)
+        lib.orc_matvec_asym(_p(tern), _p(s), _p(n), _p(x), rows, cols, x.shape[0], _p(y),
+                            _p(bound) if with_bound else None)
     return (y, bound) if with_bound else y
 
 
-def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0):
+def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0, wi_scale_neg=None, wo_scale_neg=None):
     """One token through one expert: returns (y fp64 [d_model], h bf16 bits [d_ff], bound [d_model])."""
     lib = _load()
     wi = np.ascontiguousarray(wi, dtype=np.int8)
@@ -191,11 +204,14 @@ def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0):
     assert x.shape == (d_model,)
     wis = np.ascontiguousarray(wi_scale, dtype=np.uint16)
     wos = np.ascontiguousarray(wo_scale, dtype=np.uint16)
+    win = None if wi_scale_neg is None else np.ascontiguousarray(wi_scale_neg, dtype=np.uint16)
+    won = None if wo_scale_neg is None else np.ascontiguousarray(wo_scale_neg, dtype=np.uint16)
     y = np.zeros(d_model, dtype=np.float64)
     h = np.zeros(d_ff, dtype=np.uint16)
     bound = np.zeros(d_model, dtype=np.float64)
-    lib.orc_ffn_token(_p(wi), _p(wis), _p(wo), _p(wos), _p(x), d_model, d_ff, float(gate), _p(y), _p(h),
-                      _p(bound))
+    lib.orc_ffn_token_asym(_p(wi), _p(wis), None if win is None else _p(win), _p(wo), _p(wos),
+                           None if won is None else _p(won), _p(x), d_model, d_ff, float(gate), _p(y), _p(h),
+                           _p(bound))
     return y, h, bound
 
 
@@ -209,10 +225,11 @@ def dispatch(expert_idx: np.ndarray, n_experts: int):
     return tok_off, perm[: tok_off[-1]].copy()
 
 
-def moe_layer(workload, expert_idx: np.ndarray, x_bf16: np.ndarray, gate=None, tokens=None):
+def moe_layer(workload, expert_idx: np.ndarray, x_bf16: np.ndarray, gate=None, tokens=None, asym: bool = False):
     """y[t] = gate_t * Wo_e bf16(relu(Wi_e x_t)), e = expert_idx[t], for the tokens asked for.
 
-    ``workload`` supplies wi_ternary(e), wo_ternary(e), wi_scale(e), wo_scale(e).
+    ``workload`` supplies wi_ternary(e), wo_ternary(e), wi_scale(e), wo_scale(e) and, for the
+    asymmetric grid (asym), wi_scale_neg(e), wo_scale_neg(e).
     Returns dict token -> (y fp64, h bf16 bits, bound)."""
     out = {}
     toks = range(expert_idx.size) if tokens is None else tokens
@@ -222,9 +239,11 @@ def moe_layer(workload, expert_idx: np.ndarray, x_bf16: np.ndarray, gate=None, t
     for e, ts in by_expert.items():
         wi, wo = workload.wi_ternary(e), workload.wo_ternary(e)
         wis, wos = workload.wi_scale(e), workload.wo_scale(e)
+        win = workload.wi_scale_neg(e) if asym else None
+        won = workload.wo_scale_neg(e) if asym else None
         for t in ts:
             g = 1.0 if gate is None else float(gate[t])
-            out[t] = ffn_token(wi, wis, wo, wos, x_bf16[t], g)
+            out[t] = ffn_token(wi, wis, wo, wos, x_bf16[t], g, win, won)
     return out
 
 

@@ -145,6 +145,13 @@ class Workload:
     def wo_scale(self, expert: int) -> np.ndarray:
         return uniform_f16(_seed(self.cfg_id, 4, expert), (self.d_model,), 0.01, 0.1)
 
+    # magnitudes of the negative grid point, for the asymmetric grid {-n_r, 0, +s_r}
+    def wi_scale_neg(self, expert: int) -> np.ndarray:
+        return uniform_f16(_seed(self.cfg_id, 9, expert), (self.d_ff,), 0.01, 0.1)
+
+    def wo_scale_neg(self, expert: int) -> np.ndarray:
+        return uniform_f16(_seed(self.cfg_id, 10, expert), (self.d_model,), 0.01, 0.1)
+
     # ---- routing and activations --------------------------------------
     def expert_idx(self) -> np.ndarray:
         E = self.n_experts

@@ -145,3 +145,80 @@ def test_moe_layer_routing_invariance():
     alone = oracle.ffn_token(w.wi_ternary(int(idx[t0])), w.wi_scale(int(idx[t0])),
                              w.wo_ternary(int(idx[t0])), w.wo_scale(int(idx[t0])), x[t0])
     assert np.array_equal(alone[0], full[t0][0])
+
+
+def _f16_bits(v):
+    return np.asarray(v, dtype=np.float16).view(np.uint16)
+
+
+def test_asymmetric_grid_tiny_brute_force():
+    """Section 4.1's per-row grid {w_min, 0, w_max}: the product with the dequantised matrix written out."""
+    rng = np.random.default_rng(11)
+    rows, cols, batch = 12, 21, 2
+    t = rng.integers(-1, 2, (rows, cols)).astype(np.int8)
+    xi = rng.integers(-3, 4, (batch, cols))
+    x = _bf16_bits(xi.astype(np.float64))
+    # scales exact in binary16 and small powers of two times integers, so fp64 sums are exact in any order
+    pos = rng.integers(1, 8, rows) * 0.25
+    neg = rng.integers(1, 8, rows) * 0.125
+    y, bound = oracle.matvec(t, _f16_bits(pos), x, with_bound=True, scale_neg_f16=_f16_bits(neg))
+    for b in range(batch):
+        for r in range(rows):
+            acc = 0.0
+            mag = 0.0
+            for c in range(cols):
+                w = pos[r] if t[r, c] == 1 else (-neg[r] if t[r, c] == -1 else 0.0)
+                acc += w * xi[b, c]
+                mag += abs(w * xi[b, c])
+            assert y[b, r] == acc and bound[b, r] == mag
+    # sign convention: a lone -1 weight contributes -n * x, a lone +1 weight +s * x, whichever column it sits in
+    t1 = np.array([[0, -1, 0], [1, 0, 0]], dtype=np.int8)
+    got = oracle.matvec(t1, _f16_bits([0.5, 0.5]), _bf16_bits([[7.0, 3.0, 11.0]]), scale_neg_f16=_f16_bits([2.0, 2.0]))
+    assert got.tolist() == [[-6.0, 3.5]]
+
+
+def test_asymmetric_grid_special_cases():
+    rows, cols, batch = 64, 300, 4
+    t = synth.ternary(111, rows, cols, 0.85)
+    s = synth.uniform_f16(112, (rows,), 0.01, 0.1)
+    n = synth.uniform_f16(113, (rows,), 0.01, 0.1)
+    x = synth.normal_bf16(114, (batch, cols))
+    xd, sd, nd = synth.bf16_to_f64(x), synth.f16_to_f64(s), synth.f16_to_f64(n)
+    y, bound = oracle.matvec(t, s, x, with_bound=True, scale_neg_f16=n)
+    # against numpy on the dequantised matrix
+    w = np.where(t > 0, sd[:, None], 0.0) - np.where(t < 0, nd[:, None], 0.0)
+    assert np.allclose(y, xd @ w.T, rtol=1e-12, atol=1e-15)
+    assert np.allclose(bound, np.abs(xd) @ np.abs(w).T, rtol=1e-12)
+    assert not np.allclose(y, oracle.matvec(t, s, x), rtol=1e-3)  # the second scale really matters
+    # equal scales: the symmetric product (one signed sum against two sums: equal up to fp64 rounding)
+    sym = oracle.matvec(t, s, x)
+    assert np.allclose(oracle.matvec(t, s, x, scale_neg_f16=s), sym, rtol=1e-12, atol=1e-15)
+    # flipping every sign and swapping the two scales negates the output exactly
+    assert np.array_equal(oracle.matvec((-t).astype(np.int8), n, x, scale_neg_f16=s), -y)
+    # a row with only positive weights ignores the negative scale, and the other way round
+    tp = np.abs(t).astype(np.int8)
+    assert np.array_equal(oracle.matvec(tp, s, x, scale_neg_f16=n), oracle.matvec(tp, s, x, scale_neg_f16=s))
+    tn = (-tp).astype(np.int8)
+    assert np.array_equal(oracle.matvec(tn, s, x, scale_neg_f16=n), oracle.matvec(tn, n, x, scale_neg_f16=n))
+    # split into the two symmetric products it is made of
+    zero = np.zeros_like(s)
+    parts = oracle.matvec(t, s, x, scale_neg_f16=zero) + oracle.matvec(t, zero, x, scale_neg_f16=n)
+    assert np.allclose(parts, y, rtol=1e-15, atol=0)
+
+
+def test_asymmetric_ffn_token_and_layer():
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=5, d_model=32, d_ff=96, n_tokens=12)
+    idx, x = w.expert_idx(), w.tokens()
+    full = oracle.moe_layer(w, idx, x, asym=True)
+    sym = oracle.moe_layer(w, idx, x)
+    assert any(not np.allclose(full[t][0], sym[t][0], rtol=1e-3) for t in range(idx.size))
+    t0 = 4
+    e = int(idx[t0])
+    y, h, bound = full[t0]
+    pre = oracle.matvec(w.wi_ternary(e), w.wi_scale(e), x[t0][None, :], scale_neg_f16=w.wi_scale_neg(e))[0]
+    hb = (h.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.all(hb[pre <= 0] == 0.0) and np.all(np.abs(hb - np.maximum(pre, 0)) <= np.abs(pre) * 2.0 ** -8)
+    y2 = oracle.matvec(w.wo_ternary(e), w.wo_scale(e), h[None, :], scale_neg_f16=w.wo_scale_neg(e))[0]
+    assert np.array_equal(y, y2)
+    # the negative scales are drawn apart from the positive ones
+    assert not np.array_equal(w.wi_scale(e), w.wi_scale_neg(e)) and not np.array_equal(w.wo_scale(e), w.wo_scale_neg(e))
