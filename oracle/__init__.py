@@ -55,7 +55,7 @@ def _load():
         lib.orc_matvec.restype = None
         lib.orc_ffn_token.argtypes = [vp, vp, vp, vp, vp, i64, i64, dbl, vp, vp, vp]
         lib.orc_ffn_token.restype = None
-        lib.orc_matvec_asym.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+        lib.orc_matvec_asym.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         lib.orc_matvec_asym.restype = None
         lib.orc_ffn_token_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, dbl, vp, vp, vp]
         lib.orc_ffn_token_asym.restype = None
@@ -170,31 +170,33 @@ def decode(words: np.ndarray, codes: np.ndarray, row_off: np.ndarray, rows: int,
 
 
 def matvec(tern: np.ndarray, scale_f16: np.ndarray, x_bf16: np.ndarray, with_bound: bool = False,
-           scale_neg_f16: np.ndarray | None = None):
+           minmax_bf16: np.ndarray | None = None):
     """y[b, r] = s_r * sum_c T[r, c] x[b, c] in fp64.  x_bf16: uint16 [batch, cols].
-    With scale_neg_f16 the row's grid is {-n_r, 0, +s_r} (Section 4.1; "Ternary decoding" in Section 4.3.3): y = s_r * sum over the
-    positive weights - n_r * sum over the negative ones."""
+    With minmax_bf16 (uint16 [rows, 2] = bfloat16 (w_min, w_max) per row; scale_f16 is not read
+    then) the row's grid is {w_min, 0, w_max} (Section 4.1; "Ternary decoding" in Section 4.3.3):
+    y = w_max * (sum of x under +1) + w_min * (sum of x under -1)."""
     lib = _load()
     tern = np.ascontiguousarray(tern, dtype=np.int8)
     rows, cols = tern.shape
     x = np.ascontiguousarray(x_bf16, dtype=np.uint16).reshape(-1, cols)
-    s = np.ascontiguousarray(scale_f16, dtype=np.uint16)
-    assert s.shape == (rows,)
     y = np.zeros((x.shape[0], rows), dtype=np.float64)
     bound = np.zeros_like(y) if with_bound else None
-    if scale_neg_f16 is None:
+    if minmax_bf16 is None:
+        s = np.ascontiguousarray(scale_f16, dtype=np.uint16)
+        assert s.shape == (rows,)
         lib.orc_matvec(_p(tern), _p(s), _p(x), rows, cols, x.shape[0], _p(y),
                        _p(bound) if with_bound else None)
     else:
-        n = np.ascontiguousarray(scale_neg_f16, dtype=np.uint16)
-        assert n.shape == (rows,)
-        lib.orc_matvec_asym(_p(tern), _p(s), _p(n), _p(x), rows, cols, x.shape[0], _p(y),
+        mm = np.ascontiguousarray(minmax_bf16, dtype=np.uint16)
+        assert mm.shape == (rows, 2)
+        lib.orc_matvec_asym(_p(tern), _p(mm), _p(x), rows, cols, x.shape[0], _p(y),
                             _p(bound) if with_bound else None)
     return (y, bound) if with_bound else y
 
 
-def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0, wi_scale_neg=None, wo_scale_neg=None):
-    """One token through one expert: returns (y fp64 [d_model], h bf16 bits [d_ff], bound [d_model])."""
+def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0, wi_minmax=None, wo_minmax=None):
+    """One token through one expert: returns (y fp64 [d_model], h bf16 bits [d_ff], bound [d_model]).
+    With wi_minmax and wo_minmax (both or neither) the matrices use the asymmetric grid."""
     lib = _load()
     wi = np.ascontiguousarray(wi, dtype=np.int8)
     wo = np.ascontiguousarray(wo, dtype=np.int8)
@@ -202,16 +204,21 @@ def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0, wi_scale_ne
     assert wo.shape == (d_model, d_ff)
     x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
     assert x.shape == (d_model,)
-    wis = np.ascontiguousarray(wi_scale, dtype=np.uint16)
-    wos = np.ascontiguousarray(wo_scale, dtype=np.uint16)
-    win = None if wi_scale_neg is None else np.ascontiguousarray(wi_scale_neg, dtype=np.uint16)
-    won = None if wo_scale_neg is None else np.ascontiguousarray(wo_scale_neg, dtype=np.uint16)
+    assert (wi_minmax is None) == (wo_minmax is None)
     y = np.zeros(d_model, dtype=np.float64)
     h = np.zeros(d_ff, dtype=np.uint16)
     bound = np.zeros(d_model, dtype=np.float64)
-    lib.orc_ffn_token_asym(_p(wi), _p(wis), None if win is None else _p(win), _p(wo), _p(wos),
-                           None if won is None else _p(won), _p(x), d_model, d_ff, float(gate), _p(y), _p(h),
-                           _p(bound))
+    if wi_minmax is None:
+        wis = np.ascontiguousarray(wi_scale, dtype=np.uint16)
+        wos = np.ascontiguousarray(wo_scale, dtype=np.uint16)
+        lib.orc_ffn_token(_p(wi), _p(wis), _p(wo), _p(wos), _p(x), d_model, d_ff, float(gate), _p(y), _p(h),
+                          _p(bound))
+    else:
+        wim = np.ascontiguousarray(wi_minmax, dtype=np.uint16)
+        wom = np.ascontiguousarray(wo_minmax, dtype=np.uint16)
+        assert wim.shape == (d_ff, 2) and wom.shape == (d_model, 2)
+        lib.orc_ffn_token_asym(_p(wi), None, _p(wim), _p(wo), None, _p(wom), _p(x), d_model, d_ff, float(gate),
+                               _p(y), _p(h), _p(bound))
     return y, h, bound
 
 
@@ -229,7 +236,7 @@ def moe_layer(workload, expert_idx: np.ndarray, x_bf16: np.ndarray, gate=None, t
     """y[t] = gate_t * Wo_e bf16(relu(Wi_e x_t)), e = expert_idx[t], for the tokens asked for.
 
     ``workload`` supplies wi_ternary(e), wo_ternary(e), wi_scale(e), wo_scale(e) and, for the
-    asymmetric grid (asym), wi_scale_neg(e), wo_scale_neg(e).
+    asymmetric grid (asym), wi_minmax(e), wo_minmax(e).
     Returns dict token -> (y fp64, h bf16 bits, bound)."""
     out = {}
     toks = range(expert_idx.size) if tokens is None else tokens
@@ -239,11 +246,11 @@ def moe_layer(workload, expert_idx: np.ndarray, x_bf16: np.ndarray, gate=None, t
     for e, ts in by_expert.items():
         wi, wo = workload.wi_ternary(e), workload.wo_ternary(e)
         wis, wos = workload.wi_scale(e), workload.wo_scale(e)
-        win = workload.wi_scale_neg(e) if asym else None
-        won = workload.wo_scale_neg(e) if asym else None
+        wim = workload.wi_minmax(e) if asym else None
+        wom = workload.wo_minmax(e) if asym else None
         for t in ts:
             g = 1.0 if gate is None else float(gate[t])
-            out[t] = ffn_token(wi, wis, wo, wos, x_bf16[t], g, win, won)
+            out[t] = ffn_token(wi, wis, wo, wos, x_bf16[t], g, wim, wom)
     return out
 
 

@@ -25,10 +25,9 @@
  *    equal-probability sequences compare exactly equal; ties pop in
  *    ascending order of the symbol string read as a base-3 number;
  *  - symbols: 0 -> 0, 1 -> -s (the paper's w_min), 2 -> +s (w_max);
- *  - the asymmetric grid keeps the two magnitudes apart: 1 -> -n_r (w_min),
- *    2 -> +s_r (w_max), both binary16 per output row like the single scale
- *    (the printed kernel keeps the pair in bfloat16; the storage type of two
- *    numbers per row does not touch the arithmetic, which is fp64 here);
+ *  - the asymmetric grid: 1 -> w_min[r], 2 -> w_max[r], one bfloat16 pair per
+ *    output row as in the printed kernel's signature (Listing 1), no sign
+ *    assumed for either; the symmetric case keeps its single binary16 scale;
  *  - entry word h (h = 0,1): bits 0..3 = total pair count, symbol j of the
  *    half at bits 4+2j, 4+2j+1 (14 symbols per word), unused slots 0.
  */
@@ -320,36 +319,34 @@ int orc_decode(const uint32_t *words, int n_entries, const uint16_t *codes, cons
 /* ------------------------------------------------------------------ */
 
 /*
- * y[b][r] = sum_c value(T[r][c]) * x[b][c], value(+1) = s_r, value(-1) = -n_r, value(0) = 0
- * T int8 {-1,0,+1} [rows][cols]; s binary16 bits [rows]; n binary16 bits [rows], or
- * NULL for the symmetric grid n = s; x bfloat16 bits [batch][cols]; y double
- * [batch][rows].  The per-row grid {w_min, 0, w_max} = {-n_r, 0, +s_r} is Section
- * 4.1's (symbols 0, 1, 2 dequantise to 0, w_min, w_max: "Ternary decoding", Section
- * 4.3.3); with n = s it is {-s, 0, +s} and y = s_r * sum_c T x.  The positive and the
- * negative weights are summed apart, each sum scaled once.  Also returns, when abs_sum is
- * not NULL, sum_c |value(T[r][c]) * x[b][c]| (the scale of the rounding-error bound used
- * by the parity tests).
+ * y[b][r] = sum_c value_r(T[r][c]) * x[b][c], value_r(+1) = w_max[r], value_r(-1) = w_min[r],
+ * value_r(0) = 0: the per-row grid {w_min, 0, w_max} of Section 4.1 (symbols 0, 1, 2
+ * dequantise to 0, w_min, w_max: "Ternary decoding", Section 4.3.3).
+ * T int8 {-1,0,+1} [rows][cols]; minmax bfloat16 bits [rows][2] = (w_min, w_max) of each
+ * row, of any sign; x bfloat16 bits [batch][cols]; y double [batch][rows].  The inputs
+ * under w_max and those under w_min are summed apart and each sum is scaled once.  Also
+ * returns, when abs_sum is not NULL, sum_c |value_r(T[r][c]) * x[b][c]| (the scale of the
+ * rounding-error bound used by the parity tests).
  */
-void orc_matvec_asym(const int8_t *tern, const uint16_t *scale_f16, const uint16_t *scale_neg_f16,
-                     const uint16_t *x_bf16, int64_t rows, int64_t cols, int64_t batch, double *y, double *abs_sum)
+void orc_matvec_asym(const int8_t *tern, const uint16_t *minmax_bf16, const uint16_t *x_bf16, int64_t rows,
+                     int64_t cols, int64_t batch, double *y, double *abs_sum)
 {
     for (int64_t b = 0; b < batch; b++)
         for (int64_t r = 0; r < rows; r++) {
-            double pos = 0.0, neg = 0.0, pos_mag = 0.0, neg_mag = 0.0;
+            double hi = 0.0, lo = 0.0, hi_mag = 0.0, lo_mag = 0.0;
             for (int64_t c = 0; c < cols; c++) {
                 double xv = bf16_to_double(x_bf16[b * cols + c]);
                 if (tern[r * cols + c] > 0) {
-                    pos += xv;
-                    pos_mag += fabs(xv);
+                    hi += xv;
+                    hi_mag += fabs(xv);
                 } else if (tern[r * cols + c] < 0) {
-                    neg += xv;
-                    neg_mag += fabs(xv);
+                    lo += xv;
+                    lo_mag += fabs(xv);
                 }
             }
-            double s = f16_to_double(scale_f16[r]);
-            double n = scale_neg_f16 ? f16_to_double(scale_neg_f16[r]) : s;
-            y[b * rows + r] = s * pos - n * neg;
-            if (abs_sum) abs_sum[b * rows + r] = fabs(s) * pos_mag + fabs(n) * neg_mag;
+            double w_min = bf16_to_double(minmax_bf16[2 * r]), w_max = bf16_to_double(minmax_bf16[2 * r + 1]);
+            y[b * rows + r] = w_max * hi + w_min * lo;
+            if (abs_sum) abs_sum[b * rows + r] = fabs(w_max) * hi_mag + fabs(w_min) * lo_mag;
         }
 }
 
@@ -381,23 +378,22 @@ void orc_matvec(const int8_t *tern, const uint16_t *scale_f16, const uint16_t *x
  * rounded hidden vector; abs_sum (optional) the error-bound scale of the
  * second product, gate * s_r * sum |Wo h|.
  */
-void orc_ffn_token_asym(const int8_t *wi, const uint16_t *wi_scale, const uint16_t *wi_scale_neg,
-                        const int8_t *wo, const uint16_t *wo_scale, const uint16_t *wo_scale_neg,
-                        const uint16_t *x_bf16, int64_t d_model, int64_t d_ff, double gate, double *y,
-                        uint16_t *h_bf16, double *abs_sum)
+void orc_ffn_token_asym(const int8_t *wi, const uint16_t *wi_scale, const uint16_t *wi_minmax, const int8_t *wo,
+                        const uint16_t *wo_scale, const uint16_t *wo_minmax, const uint16_t *x_bf16,
+                        int64_t d_model, int64_t d_ff, double gate, double *y, uint16_t *h_bf16, double *abs_sum)
 {
     double *h = (double *)malloc((size_t)d_ff * sizeof(double));
     uint16_t *hb = (uint16_t *)malloc((size_t)d_ff * sizeof(uint16_t));
-    if (wi_scale_neg)
-        orc_matvec_asym(wi, wi_scale, wi_scale_neg, x_bf16, d_ff, d_model, 1, h, NULL);
+    if (wi_minmax)
+        orc_matvec_asym(wi, wi_minmax, x_bf16, d_ff, d_model, 1, h, NULL);
     else
         orc_matvec(wi, wi_scale, x_bf16, d_ff, d_model, 1, h, NULL);
     for (int64_t i = 0; i < d_ff; i++) {
         double v = h[i] > 0.0 ? h[i] : 0.0;
         hb[i] = double_to_bf16(v);
     }
-    if (wo_scale_neg)
-        orc_matvec_asym(wo, wo_scale, wo_scale_neg, hb, d_model, d_ff, 1, y, abs_sum);
+    if (wo_minmax)
+        orc_matvec_asym(wo, wo_minmax, hb, d_model, d_ff, 1, y, abs_sum);
     else
         orc_matvec(wo, wo_scale, hb, d_model, d_ff, 1, y, abs_sum);
     for (int64_t i = 0; i < d_model; i++) {

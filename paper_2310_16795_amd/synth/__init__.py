@@ -87,6 +87,21 @@ def uniform_f16(seed: int, shape, lo: float, hi: float) -> np.ndarray:
     return out
 
 
+def f64_to_bf16(v: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) of finite values that float32 holds exactly or nearly so:
+    float32 first, then round-to-nearest-even on the low 16 bits."""
+    b = np.ascontiguousarray(v, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def minmax_bf16(seed: int, rows: int, lo: float, hi: float) -> np.ndarray:
+    """bfloat16 bit patterns [rows, 2] of (w_min, w_max): w_max and -w_min uniform in [lo, hi)."""
+    u = uniform_f64(seed, 2 * rows).reshape(rows, 2)
+    mag = lo + (hi - lo) * u
+    mag[:, 0] = -mag[:, 0]
+    return f64_to_bf16(mag)
+
+
 def uniform_f64(seed: int, n: int, first: int = 0) -> np.ndarray:
     out = np.empty(n, dtype=np.float64)
     _load().synth_uniform_f64(seed, first, n, out.ctypes.data)
@@ -145,14 +160,14 @@ class Workload:
     def wo_scale(self, expert: int) -> np.ndarray:
         return uniform_f16(_seed(self.cfg_id, 4, expert), (self.d_model,), 0.01, 0.1)
 
-    # magnitudes of the negative grid point, for the asymmetric grid {-n_r, 0, +s_r}
-    def wi_scale_neg(self, expert: int) -> np.ndarray:
-        return uniform_f16(_seed(self.cfg_id, 9, expert), (self.d_ff,), 0.01, 0.1)
+    # (w_min, w_max) of each output row for the asymmetric grid: bfloat16 bits [rows, 2],
+    # w_min in (-0.1, -0.01], w_max in [0.01, 0.1), drawn apart
+    def wi_minmax(self, expert: int) -> np.ndarray:
+        return minmax_bf16(_seed(self.cfg_id, 9, expert), self.d_ff, 0.01, 0.1)
 
-    def wo_scale_neg(self, expert: int) -> np.ndarray:
-        return uniform_f16(_seed(self.cfg_id, 10, expert), (self.d_model,), 0.01, 0.1)
+    def wo_minmax(self, expert: int) -> np.ndarray:
+        return minmax_bf16(_seed(self.cfg_id, 10, expert), self.d_model, 0.01, 0.1)
 
-    # ---- routing and activations --------------------------------------
     def expert_idx(self) -> np.ndarray:
         E = self.n_experts
         if self.routing == "single":

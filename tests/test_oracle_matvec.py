@@ -147,8 +147,8 @@ def test_moe_layer_routing_invariance():
     assert np.array_equal(alone[0], full[t0][0])
 
 
-def _f16_bits(v):
-    return np.asarray(v, dtype=np.float16).view(np.uint16)
+def _minmax(w_min, w_max):
+    return np.stack([_bf16_bits(w_min), _bf16_bits(w_max)], axis=1)
 
 
 def test_asymmetric_grid_tiny_brute_force():
@@ -158,51 +158,65 @@ def test_asymmetric_grid_tiny_brute_force():
     t = rng.integers(-1, 2, (rows, cols)).astype(np.int8)
     xi = rng.integers(-3, 4, (batch, cols))
     x = _bf16_bits(xi.astype(np.float64))
-    # scales exact in binary16 and small powers of two times integers, so fp64 sums are exact in any order
-    pos = rng.integers(1, 8, rows) * 0.25
-    neg = rng.integers(1, 8, rows) * 0.125
-    y, bound = oracle.matvec(t, _f16_bits(pos), x, with_bound=True, scale_neg_f16=_f16_bits(neg))
+    # grid points exact in bfloat16 and small multiples of a power of two, so fp64 sums are exact in any order
+    w_max = rng.integers(1, 8, rows) * 0.25
+    w_min = -rng.integers(1, 8, rows) * 0.125
+    y, bound = oracle.matvec(t, None, x, with_bound=True, minmax_bf16=_minmax(w_min, w_max))
     for b in range(batch):
         for r in range(rows):
             acc = 0.0
             mag = 0.0
             for c in range(cols):
-                w = pos[r] if t[r, c] == 1 else (-neg[r] if t[r, c] == -1 else 0.0)
+                w = w_max[r] if t[r, c] == 1 else (w_min[r] if t[r, c] == -1 else 0.0)
                 acc += w * xi[b, c]
                 mag += abs(w * xi[b, c])
             assert y[b, r] == acc and bound[b, r] == mag
-    # sign convention: a lone -1 weight contributes -n * x, a lone +1 weight +s * x, whichever column it sits in
+    # which grid point goes with which symbol, whichever column it sits in; the pair's order in memory
     t1 = np.array([[0, -1, 0], [1, 0, 0]], dtype=np.int8)
-    got = oracle.matvec(t1, _f16_bits([0.5, 0.5]), _bf16_bits([[7.0, 3.0, 11.0]]), scale_neg_f16=_f16_bits([2.0, 2.0]))
+    mm = _minmax([-2.0, -2.0], [0.5, 0.5])
+    assert mm[0].tolist() == [0xC000, 0x3F00]
+    got = oracle.matvec(t1, None, _bf16_bits([[7.0, 3.0, 11.0]]), minmax_bf16=mm)
     assert got.tolist() == [[-6.0, 3.5]]
+    # no sign is assumed: a grid that lies wholly above zero
+    got = oracle.matvec(t1, None, _bf16_bits([[7.0, 3.0, 11.0]]), minmax_bf16=_minmax([0.25, 0.25], [4.0, 4.0]))
+    assert got.tolist() == [[0.75, 28.0]]
 
 
 def test_asymmetric_grid_special_cases():
     rows, cols, batch = 64, 300, 4
     t = synth.ternary(111, rows, cols, 0.85)
-    s = synth.uniform_f16(112, (rows,), 0.01, 0.1)
-    n = synth.uniform_f16(113, (rows,), 0.01, 0.1)
+    mm = synth.minmax_bf16(112, rows, 0.01, 0.1)
     x = synth.normal_bf16(114, (batch, cols))
-    xd, sd, nd = synth.bf16_to_f64(x), synth.f16_to_f64(s), synth.f16_to_f64(n)
-    y, bound = oracle.matvec(t, s, x, with_bound=True, scale_neg_f16=n)
+    xd, lo, hi = synth.bf16_to_f64(x), synth.bf16_to_f64(mm[:, 0]), synth.bf16_to_f64(mm[:, 1])
+    assert np.all(lo <= -0.01 + 1e-4) and np.all(lo > -0.1 - 1e-3) and np.all(hi >= 0.01 - 1e-4) and np.all(hi < 0.1 + 1e-3)
+    assert np.unique(lo).size > rows // 2 and not np.array_equal(-lo, hi)
+    y, bound = oracle.matvec(t, None, x, with_bound=True, minmax_bf16=mm)
     # against numpy on the dequantised matrix
-    w = np.where(t > 0, sd[:, None], 0.0) - np.where(t < 0, nd[:, None], 0.0)
+    w = np.where(t > 0, hi[:, None], 0.0) + np.where(t < 0, lo[:, None], 0.0)
     assert np.allclose(y, xd @ w.T, rtol=1e-12, atol=1e-15)
     assert np.allclose(bound, np.abs(xd) @ np.abs(w).T, rtol=1e-12)
-    assert not np.allclose(y, oracle.matvec(t, s, x), rtol=1e-3)  # the second scale really matters
-    # equal scales: the symmetric product (one signed sum against two sums: equal up to fp64 rounding)
-    sym = oracle.matvec(t, s, x)
-    assert np.allclose(oracle.matvec(t, s, x, scale_neg_f16=s), sym, rtol=1e-12, atol=1e-15)
-    # flipping every sign and swapping the two scales negates the output exactly
-    assert np.array_equal(oracle.matvec((-t).astype(np.int8), n, x, scale_neg_f16=s), -y)
-    # a row with only positive weights ignores the negative scale, and the other way round
+    # w_min = -w_max = -s with s exact in both formats: the symmetric product (one signed sum against
+    # two sums: equal up to fp64 rounding)
+    s16 = (np.arange(rows) % 7 + 1).astype(np.float16) / 64
+    sym = oracle.matvec(t, s16.view(np.uint16), x)
+    both = oracle.matvec(t, None, x, minmax_bf16=_minmax(-s16.astype(np.float64), s16.astype(np.float64)))
+    assert np.allclose(both, sym, rtol=1e-12, atol=1e-15)
+    assert not np.allclose(y, sym, rtol=1e-3)
+    # flipping every weight's sign and swapping the pair changes nothing
+    assert np.array_equal(oracle.matvec((-t).astype(np.int8), None, x, minmax_bf16=mm[:, ::-1]), y)
+    # a matrix without -1 weights never reads w_min, one without +1 weights never reads w_max
     tp = np.abs(t).astype(np.int8)
-    assert np.array_equal(oracle.matvec(tp, s, x, scale_neg_f16=n), oracle.matvec(tp, s, x, scale_neg_f16=s))
+    other = mm.copy()
+    other[:, 0] = _bf16_bits(np.full(rows, -3.0))
+    assert np.array_equal(oracle.matvec(tp, None, x, minmax_bf16=mm), oracle.matvec(tp, None, x, minmax_bf16=other))
+    other = mm.copy()
+    other[:, 1] = _bf16_bits(np.full(rows, 3.0))
     tn = (-tp).astype(np.int8)
-    assert np.array_equal(oracle.matvec(tn, s, x, scale_neg_f16=n), oracle.matvec(tn, n, x, scale_neg_f16=n))
-    # split into the two symmetric products it is made of
-    zero = np.zeros_like(s)
-    parts = oracle.matvec(t, s, x, scale_neg_f16=zero) + oracle.matvec(t, zero, x, scale_neg_f16=n)
+    assert np.array_equal(oracle.matvec(tn, None, x, minmax_bf16=mm), oracle.matvec(tn, None, x, minmax_bf16=other))
+    # the sum of its two one-sided products
+    zero = np.zeros(rows)
+    parts = (oracle.matvec(t, None, x, minmax_bf16=_minmax(zero, hi)) +
+             oracle.matvec(t, None, x, minmax_bf16=_minmax(lo, zero)))
     assert np.allclose(parts, y, rtol=1e-15, atol=0)
 
 
@@ -215,10 +229,13 @@ def test_asymmetric_ffn_token_and_layer():
     t0 = 4
     e = int(idx[t0])
     y, h, bound = full[t0]
-    pre = oracle.matvec(w.wi_ternary(e), w.wi_scale(e), x[t0][None, :], scale_neg_f16=w.wi_scale_neg(e))[0]
+    assert w.wi_minmax(e).shape == (96, 2) and w.wo_minmax(e).shape == (32, 2)
+    pre = oracle.matvec(w.wi_ternary(e), None, x[t0][None, :], minmax_bf16=w.wi_minmax(e))[0]
     hb = (h.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert (pre < 0).any() and (pre > 0).any()
     assert np.all(hb[pre <= 0] == 0.0) and np.all(np.abs(hb - np.maximum(pre, 0)) <= np.abs(pre) * 2.0 ** -8)
-    y2 = oracle.matvec(w.wo_ternary(e), w.wo_scale(e), h[None, :], scale_neg_f16=w.wo_scale_neg(e))[0]
-    assert np.array_equal(y, y2)
-    # the negative scales are drawn apart from the positive ones
-    assert not np.array_equal(w.wi_scale(e), w.wi_scale_neg(e)) and not np.array_equal(w.wo_scale(e), w.wo_scale_neg(e))
+    y2, b2 = oracle.matvec(w.wo_ternary(e), None, h[None, :], with_bound=True, minmax_bf16=w.wo_minmax(e))
+    assert np.array_equal(y, y2[0]) and np.array_equal(bound, b2[0])
+    # the gate scales output and bound
+    yg, _, bg = oracle.ffn_token(w.wi_ternary(e), None, w.wo_ternary(e), None, x[t0], 0.25, w.wi_minmax(e), w.wo_minmax(e))
+    assert np.array_equal(yg, 0.25 * y) and np.array_equal(bg, 0.25 * bound)

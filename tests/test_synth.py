@@ -46,3 +46,15 @@ def test_routing_recipes():
     assert cb.min() >= 1 and cb.max() <= 32 and 3500 < b.size < 5000
     shapes = {k: (v.d_model, v.d_ff) for k, v in synth.WORKLOADS.items()}
     assert shapes["switch_large128"] == (1024, 4096) and shapes["c2048"] == (2080, 6144)
+
+
+def test_bf16_pairs_round_like_torch():
+    import torch
+
+    v = np.random.default_rng(8).normal(size=2000).astype(np.float32)
+    want = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(synth.f64_to_bf16(v.astype(np.float64)), want)
+    mm = synth.minmax_bf16(5, 100, 0.01, 0.1)
+    assert mm.shape == (100, 2) and mm.dtype == np.uint16
+    assert np.all(mm[:, 0] & 0x8000) and not np.any(mm[:, 1] & 0x8000)
+    assert np.array_equal(mm, synth.minmax_bf16(5, 100, 0.01, 0.1))
