@@ -13,6 +13,7 @@ and the CPU oracle timed on a bounded sample.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -32,17 +33,19 @@ def log(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def build_layer(w, dd, gpu, workers, interchange_order=False):
-    """Generate and encode every expert (host threads), upload once."""
+def build_layer(w, dd, gpu, workers, interchange_order=False, minmax=False):
+    """Generate and encode every expert (host threads), upload once.  minmax: rows on the
+    asymmetric grid (a bf16 (w_min, w_max) pair per row in place of the binary16 scale)."""
     import paper_2310_16795_amd as q
     from paper_2310_16795_amd import device as dev
 
-    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu)
+    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax)
     q.qmoe_set_tuning("host_threads", 1)  # parallelism is across experts here
 
     def one(e):
         out = []
-        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_scale(e)), ("wo", w.wo_ternary(e), w.wo_scale(e))):
+        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_minmax(e) if minmax else w.wi_scale(e)),
+                                   ("wo", w.wo_ternary(e), w.wo_minmax(e) if minmax else w.wo_scale(e))):
             codes, row_off = q.qmoe_encode_host(dd.handle, tern)
             out.append((which, codes, row_off, scale))
         return e, out
@@ -80,8 +83,8 @@ def dense_bf16_experts(layer, dd, active, gpu, stats=None):
         out[which] = (rows, cols)
     def run():
         for which in ("wi", "wo"):
-            q.qmoe_decompress(dd.handle, layer.desc_dev[which], 1, layer.n_experts, out[which][0], out[which][1], 1,
-                              ptrs[which])
+            q.qmoe_decompress(dd.handle, layer.desc_dev[which], layer.format, layer.n_experts, out[which][0],
+                              out[which][1], 1, ptrs[which])
     ms, _ = time_steps(run, 3, 1)
     if stats is not None:
         written = 2 * len(active) * 2 * layer.d_model * layer.d_ff
@@ -107,7 +110,8 @@ def single_matvec(w, layer, dd, gpu, expert):
         x = torch.randn(1, cols, device=gpu).to(torch.bfloat16)
         y = torch.empty(1, rows, dtype=torch.float32, device=gpu)
         dense = torch.empty((rows, cols), dtype=torch.bfloat16, device=gpu)
-        q.qmoe_decompress(dd.handle, layer.desc_dev[which][40 * expert: 40 * expert + 40], 1, 1, rows, cols, 1,
+        one = ctypes.sizeof(q.qmoe_matrix)  # the descriptor of this expert alone
+        q.qmoe_decompress(dd.handle, layer.desc_dev[which][one * expert: one * (expert + 1)], layer.format, 1, rows, cols, 1,
                           torch.tensor([dense.data_ptr()], dtype=torch.int64, device=gpu))
         t_c, _ = time_steps(lambda: q.qmoe_decode_matvec(dd.handle, desc, x.view(torch.int16), y), 200, 20)
         t_b, _ = time_steps(lambda: torch.matmul(x, dense.T), 200, 20)
@@ -117,8 +121,13 @@ def single_matvec(w, layer, dd, gpu, expert):
     return out
 
 
+def row_meta_bytes(layer):
+    """Per output row: a 4-byte stream offset and the 2-byte scale (4-byte pair on the asymmetric grid)."""
+    return 8 if layer.minmax else 6
+
+
 def layer_bytes_of(layer, experts):
-    return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + 6 * (layer.d_ff + layer.d_model)
+    return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + row_meta_bytes(layer) * (layer.d_ff + layer.d_model)
                    for e in experts))
 
 
@@ -170,7 +179,7 @@ def time_phases(fn, steps):
             for i, (name, _) in enumerate(PHASES)}
 
 
-def cpu_baseline(w, idx, x_bits, active, budget_s=12.0):
+def cpu_baseline(w, idx, x_bits, active, budget_s=12.0, minmax=False):
     """The oracle (one thread, as it stands) on a bounded sample of the workload:
     decode both matrices of an expert and push its tokens through, expert after expert."""
     import oracle
@@ -179,7 +188,8 @@ def cpu_baseline(w, idx, x_bits, active, budget_s=12.0):
     t_used, n_bytes, n_experts, n_tokens = 0.0, 0, 0, 0
     for e in active:
         wi, wo = w.wi_ternary(e), w.wo_ternary(e)
-        wis, wos = w.wi_scale(e), w.wo_scale(e)
+        wis, wos = (None, None) if minmax else (w.wi_scale(e), w.wo_scale(e))
+        wim, wom = (w.wi_minmax(e), w.wo_minmax(e)) if minmax else (None, None)
         ci, ri = oracle.encode(od, wi)
         co, ro = oracle.encode(od, wo)
         toks = np.nonzero(idx == e)[0]
@@ -187,9 +197,9 @@ def cpu_baseline(w, idx, x_bits, active, budget_s=12.0):
         di = oracle.decode(od.words, ci, ri, *wi.shape)
         do = oracle.decode(od.words, co, ro, *wo.shape)
         for t in toks:
-            oracle.ffn_token(di, wis, do, wos, x_bits[t])
+            oracle.ffn_token(di, wis, do, wos, x_bits[t], 1.0, wim, wom)
         t_used += time.perf_counter() - t0
-        n_bytes += 2 * (ci.size + co.size) + 6 * (wi.shape[0] + wo.shape[0])
+        n_bytes += 2 * (ci.size + co.size) + (8 if minmax else 6) * (wi.shape[0] + wo.shape[0])
         n_experts += 1
         n_tokens += toks.size
         if t_used > budget_s:
@@ -213,6 +223,9 @@ def main():
     ap.add_argument("--dict-max-pairs", type=int, default=14, help="longest dictionary entry in pairs (the paper's is 14)")
     ap.add_argument("--interchange-order", action="store_true",
                     help="leave the codeword streams as encoded instead of renumbering them at load time")
+    ap.add_argument("--grid", choices=("scale", "minmax"), default="scale",
+                    help="per-row grid: {-s,0,+s} with one binary16 scale (the headline format) or the paper's "
+                         "{w_min,0,w_max} with a bf16 pair")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -244,7 +257,8 @@ def main():
                         device=gpu)
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
-    layer = build_layer(w, dd, gpu, workers, args.interchange_order)
+    minmax = args.grid == "minmax"
+    layer = build_layer(w, dd, gpu, workers, args.interchange_order, minmax)
     log(f"layer resident: {layer.compressed_bytes / 1e9:.3f} GB compressed, built in {time.time() - t0:.0f} s")
 
     x = torch.from_numpy(x_bits.view(np.int16).copy()).to(gpu)
@@ -269,7 +283,7 @@ def main():
     # expert's compressed matrix (codewords + 6 bytes of row metadata) once, activations in, results out
     n_params = 2 * w.d_model * w.d_ff
     def mat_bytes(which, rows, experts):
-        return int(sum(2 * layer.n_codes[which][e] + 6 * rows for e in experts))
+        return int(sum(2 * layer.n_codes[which][e] + row_meta_bytes(layer) * rows for e in experts))
     weight_bytes = mat_bytes("wi", w.d_ff, active) + mat_bytes("wo", w.d_model, active)
     n_codewords = int(sum(layer.n_codes["wi"][e] + layer.n_codes["wo"][e] for e in active))
     def kernel_bytes(which, experts):
@@ -278,11 +292,12 @@ def main():
             return mat_bytes("wi", w.d_ff, experts) + toks * w.d_model * 2 + toks * w.d_ff * 2
         return mat_bytes("wo", w.d_model, experts) + toks * w.d_ff * 2 + toks * w.d_model * 4
     dict_mode = "0|1" if args.interchange_order else "3"  # template argument: where the table is read from
+    g = 1 if minmax else 0                                # template argument: the grid
     kernels = {
-        "first_product_scalar": (f"k_product<{dict_mode}, 1> (first product, experts with few tokens)", kernel_bytes("wi", few)),
-        "second_product_scalar": (f"k_product<{dict_mode}, 0> (second product, experts with few tokens)", kernel_bytes("wo", few)),
-        "first_product_mfma": ("k_product_mm<1> (first product, crowded experts)", kernel_bytes("wi", crowded)),
-        "second_product_mfma": ("k_product_mm<0> (second product, crowded experts)", kernel_bytes("wo", crowded)),
+        "first_product_scalar": (f"k_product<{dict_mode}, 1, {g}> (first product, experts with few tokens)", kernel_bytes("wi", few)),
+        "second_product_scalar": (f"k_product<{dict_mode}, 0, {g}> (second product, experts with few tokens)", kernel_bytes("wo", few)),
+        "first_product_mfma": (f"k_product_mm<1, {g}> (first product, crowded experts)", kernel_bytes("wi", crowded)),
+        "second_product_mfma": (f"k_product_mm<0, {g}> (second product, crowded experts)", kernel_bytes("wo", crowded)),
     }
     dom_key = max(kernels, key=lambda k: kernel_ms[k])
     dom = (kernels[dom_key][0], kernel_ms[dom_key], kernels[dom_key][1])
@@ -299,7 +314,7 @@ def main():
     # (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for k_stream_copy)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not minmax:  # the committed counters are the headline format's
         with open(tpath) as f:
             traffic = json.load(f).get(dom_key)
 
@@ -311,6 +326,7 @@ def main():
                    "tokens": T, "experts_with_tokens": len(active), "routing": w.routing,
                    "zero_fraction": "0.80-0.97 per row" if w.p0_spread else w.p0,
                    "code_order": "interchange" if args.interchange_order else "device",
+                   "grid": "{w_min,0,w_max}, bf16 pair per row" if minmax else "{-s,0,+s}, binary16 scale per row",
                    "dict_entries": args.dict_entries, "dict_max_pairs": args.dict_max_pairs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
@@ -380,7 +396,7 @@ def main():
         del keep, dense
 
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(w, idx, x_bits, active)
+        result["cpu_baseline"] = cpu_baseline(w, idx, x_bits, active, minmax=minmax)
         result["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
 
     print(json.dumps(result), flush=True)

@@ -171,7 +171,13 @@ qmoe_status qmoe_encode_device(const qmoe_dict *d, const int8_t *ternary /*devic
 /* Device kernels (Section 4.3.3 "GPU Kernel")                                */
 /* ------------------------------------------------------------------------- */
 
-/* One compressed matrix.  All pointers are device memory owned by the caller. */
+/*
+ * One compressed matrix.  All pointers are device memory owned by the caller.
+ * The grid of a row is {-s_r, 0, +s_r} with s_r = scale_f16[r] (symbol 1 = -s_r, symbol 2 =
+ * +s_r), or, when minmax_bf16 is not NULL, the asymmetric {w_min, 0, w_max} of Section 4.1
+ * with one bfloat16 pair per row as in Listing 1 (symbol 1 = w_min, symbol 2 = w_max,
+ * "Ternary decoding" in Section 4.3.3; either may have any sign); scale_f16 is not read then.
+ */
 typedef struct qmoe_matrix {
     const uint16_t *codes;     /* [n_codes] codewords, rows back to back; 16-byte aligned,
                                   readable (any contents) up to the next 16-byte
@@ -182,7 +188,18 @@ typedef struct qmoe_matrix {
     uint32_t n_codes;          /* = row_off[rows]; offsets beyond it are clamped        */
     uint32_t code_order;       /* 0: interchange numbering (as encoded); 1: device
                                   numbering (after qmoe_codes_to_device_order)          */
+    const uint16_t *minmax_bf16; /* NULL, or [rows][2] bfloat16 (w_min, w_max) of each
+                                  output row, 4-byte aligned                            */
 } qmoe_matrix;
+
+/*
+ * Format bits for the calls whose matrix descriptors live in device memory (the host
+ * cannot look at them, so it is told): the `code_order` argument of qmoe_decompress,
+ * qmoe_moe_layer_forward and qmoe_moe_dispatch is 0 or an OR of these.
+ */
+#define QMOE_FORMAT_DEVICE_ORDER 1 /* every stream uses the device numbering              */
+#define QMOE_FORMAT_GRID_MINMAX 2  /* every matrix is on the asymmetric grid: the kernels
+                                      read minmax_bf16 (a NULL there decodes to zeros)    */
 
 /*
  * Rewrite a codeword stream in device memory, in place, from the interchange numbering
@@ -199,6 +216,7 @@ qmoe_status qmoe_codes_to_device_order(const qmoe_dict *d, uint16_t *codes /*dev
  * Fused decode + product (the paper's kernel, extended by an inner loop over
  * tokens as its Section 5.3 suggests):
  *   y[b][r] = s_r * sum_c T[r][c] * x[b][c],  b < batch
+ * (W->minmax_bf16 set: y[b][r] = w_max[r] * (sum of x under +1) + w_min[r] * (sum under -1))
  * W: host struct holding device pointers.  x: device bf16 [batch][cols].
  * y: device fp32 [batch][rows], overwritten.  fp32 accumulation.
  * Errors: INVALID_ARG (NULL, batch<1, odd cols), NO_DEVICE_DICT, LIMIT
@@ -222,9 +240,10 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
  * Decompress whole matrices (the codec of Section 4.3.3 without the product; the
  * "decompress, then a standard matrix product" alternative named in Section 5.3):
  * out[m] receives matrix mats[m], row-major rows x cols, as int8 in {-1, 0, +1}
- * (out_kind 0) or as bf16 with the row scale folded in, bf16(s_r) * w (out_kind 1).
+ * (out_kind 0) or as bf16 with the row scale folded in, bf16(s_r) * w (out_kind 1; with
+ * QMOE_FORMAT_GRID_MINMAX the row's own w_min / w_max, which are bf16 already).
  * mats: device array [n_mats] of qmoe_matrix, all rows x cols, device numbering
- * (code_order must be 1).  out: device array [n_mats] of device pointers, 16-byte
+ * (code_order must have QMOE_FORMAT_DEVICE_ORDER set).  out: device array [n_mats] of device pointers, 16-byte
  * aligned, NULL = skip that matrix.  cols must be a multiple of 8.  One launch for all
  * matrices; nothing is allocated.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, LIMIT (no device order; cols > 32768), HIP.
@@ -271,8 +290,9 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * is outside [0, n_experts) gets a zero row.  workspace: device, 256-byte
  * aligned, >= qmoe_moe_layer_workspace(...) bytes, contents need not be
  * initialised.  Experts without tokens are never touched (their qmoe_matrix
- * may hold anything).  code_order: the numbering of every expert's stream (0 or 1, as
- * in qmoe_matrix; the descriptors live in device memory, so the host is told).
+ * may hold anything).  code_order: QMOE_FORMAT_* bits: the numbering of every expert's
+ * stream (bit 0, as in qmoe_matrix) and whether the experts are on the asymmetric grid
+ * (QMOE_FORMAT_GRID_MINMAX; the descriptors live in device memory, so the host is told).
  * Enqueues a dispatch kernel and, per product, the scalar kernel for experts with few
  * tokens and (device-order streams, widths divisible by 8, x 16-byte aligned) the
  * matrix-core kernel for crowded ones: an expert's matrix is decoded once per tile of up

@@ -29,7 +29,12 @@ class QmoeError(RuntimeError):
 
 class qmoe_matrix(Structure):
     _fields_ = [("codes", c_void_p), ("row_off", c_void_p), ("scale_f16", c_void_p),
-                ("rows", c_int32), ("cols", c_int32), ("n_codes", c_uint32), ("code_order", c_uint32)]
+                ("rows", c_int32), ("cols", c_int32), ("n_codes", c_uint32), ("code_order", c_uint32),
+                ("minmax_bf16", c_void_p)]
+
+
+FORMAT_DEVICE_ORDER = 1
+FORMAT_GRID_MINMAX = 2
 
 
 class qmoe_ws_layout(Structure):

@@ -86,6 +86,7 @@ struct ProductArgs {
     int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
     int mm_row_blocks, mm_rows_per_block;  // matrix-core kernel: workgroups per matrix, rows each takes (<= 512)
     int mm_stagger;           // matrix-core kernel: the two wavefronts of a SIMD half a step apart
+    int minmax;               // rows on the grid {w_min, 0, w_max} (host side: which kernel to launch)
 };
 
 // ---------------------------------------------------------------- device helpers
@@ -251,9 +252,13 @@ __device__ __forceinline__ void lds_load_x(uint32_t xs_addr, uint32_t rec8, floa
 
 // acc[t] += sum over the entry's non-zeros of weight * x[t][column + position], the
 // column given as pos8 = 8 * column.  (The one-token run-table case has its own code
-// in consume8_one; this is the form every other case uses.)
-template <int TBI, int DICT>
-__device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uint32_t pos8, float (&acc)[TBI])
+// in consume8; this is the form every other case uses.)
+// ASYM (rows on the grid {w_min, 0, w_max}): a second set of sums, acc[TBI + t], takes the
+// same inputs with |weight|; the two grid points are applied when the row is written, as
+// y = (w_max - w_min)/2 * acc[t] + (w_max + w_min)/2 * acc[TBI + t].
+template <int TBI, int DICT, int ASYM = 0>
+__device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uint32_t pos8,
+                                           float (&acc)[TBI * (1 + ASYM)])
 {
     if constexpr (DICT != kDictWords) {
 #pragma unroll
@@ -265,6 +270,11 @@ __device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uin
             lds_load_x<TBI>(xs_addr, pos8 + (field & 0xF8u), xv);
 #pragma unroll
             for (int t = 0; t < TBI; t++) acc[t] = fmaf(w, xv[t], acc[t]);
+            if constexpr (ASYM) {
+                const float wa = (float)(wi & 1);
+#pragma unroll
+                for (int t = 0; t < TBI; t++) acc[TBI + t] = fmaf(wa, xv[t], acc[TBI + t]);
+            }
         }
     } else {
 #pragma unroll
@@ -280,15 +290,20 @@ __device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uin
                 lds_load_x<TBI>(xs_addr, pos8 + 8u * (uint32_t)(14 * h + (b >> 1)), xv);
 #pragma unroll
                 for (int t = 0; t < TBI; t++) acc[t] = fmaf(wt, xv[t], acc[t]);
+                if constexpr (ASYM) {
+                    const float wa = sym != 0 ? 1.0f : 0.0f;
+#pragma unroll
+                    for (int t = 0; t < TBI; t++) acc[TBI + t] = fmaf(wa, xv[t], acc[TBI + t]);
+                }
             }
         }
     }
 }
 
 // Per-lane decoder state for one item.
-template <int TBI>
+template <int TBI, int ASYM = 0>
 struct LaneState {
-    float acc[TBI];    // running sum since the last row that was written
+    float acc[TBI * (1 + ASYM)];  // running sums since the last row that was written (ASYM: see accumulate)
     uint32_t pos8;     // 8 * (column reached in the current row)
     int row, rb;       // current row, end of this lane's rows
 };
@@ -297,7 +312,7 @@ struct LaneState {
 // that closing a row never waits on global memory (which would also wait for the
 // stream and table prefetches in flight).
 struct RowSink {
-    lp_u16 scale_s;   // binary16 scales of the block's rows
+    lp_u16 scale_s;   // binary16 scales of the block's rows (asymmetric grid: bf16 (w_min, w_max) pairs, 4 bytes a row)
     int r0;           // first row of the block
     const __attribute__((address_space(3))) int *tok_ids;   // output token of each tile slot
     const __attribute__((address_space(3))) float *gate_s;  // gate of each tile slot
@@ -306,15 +321,24 @@ struct RowSink {
     int out_rows;     // rows of the block
 };
 
-template <int TBI, int EPI>
-__device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<TBI> &st, const float (&sum)[TBI],
-                                          const RowSink &rs)
+template <int TBI, int EPI, int ASYM = 0>
+__device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<TBI, ASYM> &st,
+                                          const float (&sum)[TBI * (1 + ASYM)], const RowSink &rs)
 {
-    const float scale = half_bits_to_float(rs.scale_s[st.row - rs.r0]);
+    float scale = 0.0f, mid = 0.0f;  // y = scale * (signed sum) + mid * (sum under |weight|)
+    if constexpr (ASYM) {
+        const uint32_t pair = ((lp_u32)rs.scale_s)[st.row - rs.r0];
+        const float w_min = __uint_as_float(pair << 16), w_max = __uint_as_float(pair & 0xFFFF0000u);
+        scale = 0.5f * (w_max - w_min);
+        mid = 0.5f * (w_max + w_min);
+    } else {
+        scale = half_bits_to_float(rs.scale_s[st.row - rs.r0]);
+    }
 #pragma unroll
     for (int t = 0; t < TBI; t++) {
         if (t < rs.ntok) {
-            const float v = sum[t] * scale;
+            float v = sum[t] * scale;
+            if constexpr (ASYM) v = fmaf(sum[TBI + t], mid, v);
             if constexpr (EPI == 0) {
                 if (rs.out_s) {
                     *(__attribute__((address_space(3))) float *)(uintptr_t)(
@@ -342,17 +366,17 @@ __device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<
 // General form: one decoded entry at a time, the row closed as soon as it is full.
 // Works for any width and any table; used for narrow matrices (several row ends may
 // fall into eight codewords) and for tables without run entries.
-template <int TBI, int DICT, int EPI>
-__device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI> &st, const Entry &e,
+template <int TBI, int DICT, int EPI, int ASYM>
+__device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI, ASYM> &st, const Entry &e,
                                          uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
 {
-    accumulate<TBI, DICT>(e, xs_addr, st.pos8, st.acc);
+    accumulate<TBI, DICT, ASYM>(e, xs_addr, st.pos8, st.acc);
     st.pos8 += 8u * (uint32_t)entry_len<DICT>(e);
     if (__any(st.pos8 >= cols8)) {
         if (st.pos8 >= cols8) {
-            if (st.row < st.rb) write_row<TBI, EPI>(a, st, st.acc, rs);
+            if (st.row < st.rb) write_row<TBI, EPI, ASYM>(a, st, st.acc, rs);
 #pragma unroll
-            for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
+            for (int t = 0; t < TBI * (1 + ASYM); t++) st.acc[t] = 0.0f;
             st.pos8 -= cols8;
             st.row += 1;
         }
@@ -366,10 +390,11 @@ __device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI> &s
 // One token: the activations are 8-byte records {0, +x, 0, -x} and an entry's field
 // is the byte offset of the wanted 16-bit slot from the record of the run's first
 // column (unused fields land on a zero), so a non-zero costs one add.
-template <int TBI, int DICT, int EPI>
-__device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &st, const Entry (&e)[8],
+template <int TBI, int DICT, int EPI, int ASYM>
+__device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, ASYM> &st, const Entry (&e)[8],
                                          uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
 {
+    constexpr int NA = TBI * (1 + ASYM);
     uint32_t pos[8];
     bool wrap[8];
     uint32_t p = st.pos8;
@@ -381,14 +406,15 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &s
         p = wrap[j] ? p - cols8 : p;
     }
     st.pos8 = p;
-    float snap[TBI];
+    float snap[NA];
     bool wrapped = false;
 #pragma unroll
-    for (int t = 0; t < TBI; t++) snap[t] = 0.0f;
+    for (int t = 0; t < NA; t++) snap[t] = 0.0f;
     if constexpr (TBI == 1) {
         // the three bf16 values of a codeword are added with two packed dot products
         // against (1, 1): two of them share a register, no widening shifts
         uint32_t x[24];
+        uint32_t xa[ASYM ? 24 : 1];  // asymmetric grid: the same inputs with their own sign (+x of each record)
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const uint32_t rec = xs_addr + pos[j];
@@ -396,6 +422,8 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &s
             for (int z = 0; z < 3; z++) {
                 const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
                 x[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)addr);
+                // the -x slot is 4 bytes after the +x slot; an unused field stays on the zero slot
+                if constexpr (ASYM) xa[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)(addr & ~4u));
             }
         }
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -411,22 +439,31 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI> &s
             st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, st.acc[0], false);
             st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p1, ones, st.acc[0], false);
             snap[0] = wrap[j] ? st.acc[0] : snap[0];
+            if constexpr (ASYM) {
+                const uint32_t pair_a = xa[3 * j] | (xa[3 * j + 1] << 16);
+                bf16x2 a2, a1;
+                __builtin_memcpy(&a2, &pair_a, 4);
+                __builtin_memcpy(&a1, &xa[3 * j + 2], 4);
+                st.acc[NA - 1] = __builtin_amdgcn_fdot2_f32_bf16(a2, ones, st.acc[NA - 1], false);
+                st.acc[NA - 1] = __builtin_amdgcn_fdot2_f32_bf16(a1, ones, st.acc[NA - 1], false);
+                snap[NA - 1] = wrap[j] ? st.acc[NA - 1] : snap[NA - 1];
+            }
             wrapped = wrapped || wrap[j];
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            accumulate<TBI, DICT>(e[j], xs_addr, pos[j], st.acc);
+            accumulate<TBI, DICT, ASYM>(e[j], xs_addr, pos[j], st.acc);
 #pragma unroll
-            for (int t = 0; t < TBI; t++) snap[t] = wrap[j] ? st.acc[t] : snap[t];
+            for (int t = 0; t < NA; t++) snap[t] = wrap[j] ? st.acc[t] : snap[t];
             wrapped = wrapped || wrap[j];
         }
     }
     if (__any(wrapped)) {
         if (wrapped) {
-            if (st.row < st.rb) write_row<TBI, EPI>(a, st, snap, rs);
+            if (st.row < st.rb) write_row<TBI, EPI, ASYM>(a, st, snap, rs);
 #pragma unroll
-            for (int t = 0; t < TBI; t++) st.acc[t] -= snap[t];
+            for (int t = 0; t < NA; t++) st.acc[t] -= snap[t];
             st.row += 1;
         }
     }
@@ -452,7 +489,7 @@ __device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp
 // no prefix sum across lanes, no reduction -- the running column index is a scalar
 // per lane, exactly the paper's sequential decoder, 64 of them per wavefront.  Table
 // entries are fetched eight codewords ahead of their use.
-template <int TBI, int DICT, int EPI>
+template <int TBI, int DICT, int EPI, int ASYM>
 __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_matrix &M, int blk,
                                               uint32_t xs_addr, const RowSink &rs, lp_u32 lds_run)
 {
@@ -481,9 +518,9 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     for (int d = 32; d > 0; d >>= 1) npieces = max(npieces, __shfl_xor(npieces, d, 64));
 
     const uint32_t cols8 = 8u * (uint32_t)a.cols;
-    LaneState<TBI> st;
+    LaneState<TBI, ASYM> st;
 #pragma unroll
-    for (int t = 0; t < TBI; t++) st.acc[t] = 0.0f;
+    for (int t = 0; t < TBI * (1 + ASYM); t++) st.acc[t] = 0.0f;
     st.pos8 = 0;
     st.row = ra;
     st.rb = rb;
@@ -501,13 +538,13 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
         // r: stream index (relative to K0) of the piece's first slot
         const bool whole = r >= 0 && (uint32_t)r + 8u <= n;  // all eight are this lane's codewords
         if (fast && __all(whole)) {
-            consume8<TBI, DICT, EPI>(a, st, e, cols8, xs_addr, rs);
+            consume8<TBI, DICT, EPI, ASYM>(a, st, e, cols8, xs_addr, rs);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 Entry ej = e[j];
                 if ((uint32_t)(r + j) >= n) { ej.e0 = 0u; ej.e1 = 0u; }  // not this lane's codeword
-                consume1<TBI, DICT, EPI>(a, st, ej, cols8, xs_addr, rs);
+                consume1<TBI, DICT, EPI, ASYM>(a, st, ej, cols8, xs_addr, rs);
             }
         }
     };
@@ -530,7 +567,8 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
 // EPI 1: bf16 out[slot][r]  = relu(s_r * acc)        (first product, writes the hidden vector)
 // LDS: activations | token ids | leading run entries.  Activations are bf16, for one
 // token as 8-byte records {0, +x, 0, -x} per column, for 2/4/8 tokens packed per column.
-template <int DICT, int EPI>
+// ASYM: rows on the grid {w_min, 0, w_max} (bf16 pair per row) instead of {-s, 0, +s}.
+template <int DICT, int EPI, int ASYM>
 __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -541,7 +579,7 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     float *gate_s = reinterpret_cast<float *>(x_rows + kMaxTokenTile);  // [kMaxTokenTile] gate
     int *next_item = reinterpret_cast<int *>(gate_s + kMaxTokenTile);   // [1]
     uint16_t *scale_w = reinterpret_cast<uint16_t *>(smem + xs_bytes + 128);  // [rows_per_item] row scales
-    const size_t scale_bytes = ((size_t)a.rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
+    const size_t scale_bytes = ((size_t)a.rows_per_item * (ASYM ? 4 : 2) + 15) / 16 * 16;
     uint32_t *lds_run_w = reinterpret_cast<uint32_t *>(smem + xs_bytes + 128 + scale_bytes);
     const size_t table_entries = DICT == kDictOrder ? (size_t)a.n_order : (DICT == kDictRunLds ? (size_t)a.lds_dict_entries : 0);
     uint16_t *out_w = reinterpret_cast<uint16_t *>(smem + xs_bytes + 128 + scale_bytes + ((table_entries * 4 + 15) & ~(size_t)15));
@@ -639,7 +677,13 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         const int gl0 = blk * (int)blockDim.x, gl1 = gl0 + (int)blockDim.x;
         const int r0 = gl0 * base_rows + min(gl0, extra);
         const int r1 = min(gl1 * base_rows + min(gl1, extra), r0 + a.rows_per_item);
-        for (int i = threadIdx.x; i < r1 - r0; i += blockDim.x) scale_w[i] = ((gp_u16)M.scale_f16)[r0 + i];
+        if constexpr (ASYM) {
+            // a matrix without a pair array decodes to zeros
+            for (int i = threadIdx.x; i < r1 - r0; i += blockDim.x)
+                reinterpret_cast<uint32_t *>(scale_w)[i] = M.minmax_bf16 ? ((gp_u32)M.minmax_bf16)[r0 + i] : 0u;
+        } else {
+            for (int i = threadIdx.x; i < r1 - r0; i += blockDim.x) scale_w[i] = ((gp_u16)M.scale_f16)[r0 + i];
+        }
         __syncthreads();
         RowSink rs;
         rs.scale_s = (lp_u16)scale_w;
@@ -652,10 +696,10 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         rs.out_s = staged ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)out_w : 0u;
         rs.out_rows = (r1 - r0 + 7) & ~7;
         switch (tbi) {
-        case 1: product_block<1, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
-        case 2: product_block<2, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
-        case 4: product_block<4, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
-        default: product_block<8, DICT, EPI>(a, M, blk, xs_addr, rs, lds_run); break;
+        case 1: product_block<1, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
+        case 2: product_block<2, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
+        case 4: product_block<4, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
+        default: product_block<8, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
         }
         if (staged) {
             // the block's results, staged in LDS, go out as whole 16-byte pieces
@@ -729,6 +773,22 @@ __device__ __forceinline__ bf16x8 mm_expand(uint32_t d0, uint32_t d1)
     return r;
 }
 
+// Asymmetric grid: the ring holds byte selectors (0: zero, 2: w_max, 6: w_min) and eight of
+// them pick the row's own bf16 grid points out of lo = w_max << 16, hi = w_min << 16 (bytes
+// 0..3 of the permute's source are lo, 4..7 hi; selector b takes the value's low byte,
+// b + 1 its high byte).
+__device__ __forceinline__ bf16x8 mm_expand_minmax(uint32_t d0, uint32_t d1, uint32_t hi, uint32_t lo)
+{
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d0, 0x01010000u) + 0x01000100u);
+    o.y = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d0, 0x03030202u) + 0x01000100u);
+    o.z = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d1, 0x01010000u) + 0x01000100u);
+    o.w = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d1, 0x03030202u) + 0x01000100u);
+    bf16x8 r;
+    __builtin_memcpy(&r, &o, 16);
+    return r;
+}
+
 using lw_u8 = __attribute__((address_space(3))) unsigned char *;
 using lw_u64 = __attribute__((address_space(3))) unsigned long long *;
 using lw_u32x4 = __attribute__((address_space(3))) u32x4 *;
@@ -796,7 +856,8 @@ __device__ __forceinline__ void lds_barrier()
 // has passed column kend = 64 (c + 1); lanes that are there already keep going while their
 // next codeword fits into the ring.  AFTER_WAIT runs right after the step's one wait for
 // global memory (a good place to issue loads that should stay in flight for a whole step).
-#define QMOE_RING_DECODE_STEP(c, AFTER_WAIT)                                                            \
+// A weight's ring byte is its two-bit field (2: +1, 6: -1) shifted left by BYTE_SHIFT.
+#define QMOE_RING_DECODE_STEP(c, AFTER_WAIT, BYTE_SHIFT)                                                          \
     const int kc = (c) * kMmKc, kend = kc + kMmKc;                                                      \
     _Pragma("unroll") for (int i_ = 0; i_ < kMmKc / 8; i_++)                                            \
         ((lw_u64)(uintptr_t)(wrow + (uint32_t)((((c) + 1) & 1) * kMmKc)))[i_] = 0ull;                   \
@@ -833,8 +894,8 @@ __device__ __forceinline__ void lds_barrier()
             _Pragma("unroll") for (int z_ = 0; z_ < kRunMaxNonzeros; z_++) {                            \
                 const uint32_t f_ = (ent_ >> (8 + 8 * z_)) & 0xFFu;                                     \
                 const uint32_t col_ = (base_ + (f_ >> 3)) & mask_;                                      \
-                /* 0, 0x40 (+2.0), 0xC0 (-2.0) */                                                       \
-                *(lw_u8)(uintptr_t)(wrow + col_) = (unsigned char)((f_ & 6u) << 5);                     \
+                /* shift 5: 0, 0x40 (+2.0), 0xC0 (-2.0) */                                              \
+                *(lw_u8)(uintptr_t)(wrow + col_) = (unsigned char)((f_ & 6u) << (BYTE_SHIFT));          \
             }                                                                                           \
             pos += (int)((ent_ & 0xFFu) >> 3);                                                          \
         }                                                                                               \
@@ -842,7 +903,7 @@ __device__ __forceinline__ void lds_barrier()
 
 // MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
 // rings and the two activation buffers.
-template <int MB, int EPI>
+template <int MB, int EPI, int ASYM>
 __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
                                         lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s,
                                         int lag)
@@ -893,6 +954,18 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 #pragma unroll
     for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
 
+    // asymmetric grid: the grid points of the two rows whose weights this lane feeds to the matrix cores
+    uint32_t g_hi[2] = {0u, 0u}, g_lo[2] = {0u, 0u};
+    if constexpr (ASYM) {
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++) {
+            const int rl = 64 * wave + 32 * nb + l32;
+            uint32_t pair = 0u;  // a row past the end, or a matrix without a pair array, multiplies as zeros
+            if (rl < a.mm_rows_per_block && r0 + rl < a.rows && M.minmax_bf16) pair = ((gp_u32)M.minmax_bf16)[r0 + rl];
+            g_hi[nb] = pair << 16;
+            g_lo[nb] = pair & 0xFFFF0000u;
+        }
+    }
     const uint32_t wfrag = wt + (uint32_t)((64 * wave + l32) * kMmWRowBytes + 8 * lhi);
     const uint32_t xfrag0 = xt + (uint32_t)(l32 * kMmXRowBytes + 16 * lhi);
     const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
@@ -913,7 +986,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
             int k_next = kend;
             asm volatile("" : "+s"(k_next));
             xr = load_x(k_next);
-        });
+        }, ASYM ? 0 : 5);
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -928,7 +1001,10 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 #pragma unroll
             for (int nb = 0; nb < 2; nb++) {
                 const unsigned long long d = *(lp_u64)(uintptr_t)(wf + (uint32_t)(nb * 32 * kMmWRowBytes + 16 * ks));
-                bw[nb] = mm_expand((uint32_t)d, (uint32_t)(d >> 32));
+                if constexpr (ASYM)
+                    bw[nb] = mm_expand_minmax((uint32_t)d, (uint32_t)(d >> 32), g_hi[nb], g_lo[nb]);
+                else
+                    bw[nb] = mm_expand((uint32_t)d, (uint32_t)(d >> 32));
             }
 #pragma unroll
             for (int mb = 0; mb < MB; mb++) {
@@ -959,14 +1035,15 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         const int rl = 64 * wave + 32 * nb + l32;
         const int r = r0 + rl;
         if (rl < a.mm_rows_per_block && r < a.rows) {
-            const float scale = half_bits_to_float(((gp_u16)M.scale_f16)[r]);
+            // symmetric grid: the weights were +-2; asymmetric: they were the grid points themselves
+            const float scale = ASYM ? 1.0f : 0.5f * half_bits_to_float(((gp_u16)M.scale_f16)[r]);
 #pragma unroll
             for (int mb = 0; mb < MB; mb++) {
 #pragma unroll
                 for (int v = 0; v < 16; v++) {
                     const int t = 32 * mb + 8 * (v / 4) + 4 * lhi + (v % 4);
                     if (t < ntok) {
-                        const float val = (acc[mb][nb][v] * 0.5f) * scale;  // the weights were +-2
+                        const float val = acc[mb][nb][v] * scale;
                         if constexpr (EPI == 0) {
                             reinterpret_cast<float *>(a.out)[(size_t)tok_ids[t] * a.ld_out + r] = gate_s[t] * val;
                         } else {
@@ -981,7 +1058,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     }
 }
 
-template <int EPI>
+template <int EPI, int ASYM>
 __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1036,10 +1113,10 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
         const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
         const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, xt_addr = (uint32_t)(uintptr_t)(lw_u8)xt;
         if (ntok <= 32)
-            mm_item<1, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+            mm_item<1, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
                             (lp_f32)gate_s, lag);
         else
-            mm_item<2, EPI>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+            mm_item<2, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
                             (lp_f32)gate_s, lag);
     }
 }
@@ -1055,7 +1132,7 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
 // the 16 partial sums are added in a fixed order at the row's end.  rows x 16 lanes keep the
 // whole GPU busy with one matrix.  The table is read from L2 (no 65 KB staging per
 // workgroup: the launch is over in microseconds).
-template <bool RUN>
+template <bool RUN, int ASYM>
 __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1098,24 +1175,38 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
         if (r >= a.rows) continue;
         const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
         const uint32_t kbeg = min(M.row_off[r], kend);
-        const float scale = half_bits_to_float(M.scale_f16[r]);
+        // y = scale * (signed sum) + mid * (sum under |weight|); mid = 0 on the symmetric grid
+        float scale, mid = 0.0f;
+        if constexpr (ASYM) {
+            const uint32_t pair = reinterpret_cast<const uint32_t *>(M.minmax_bf16)[r];
+            const float w_min = __uint_as_float(pair << 16), w_max = __uint_as_float(pair & 0xFFFF0000u);
+            scale = 0.5f * (w_max - w_min);
+            mid = 0.5f * (w_max + w_min);
+        } else {
+            scale = half_bits_to_float(M.scale_f16[r]);
+        }
         auto row = [&](auto tag) {
             constexpr int TBI = decltype(tag)::value;
-            float acc[TBI];
+            constexpr int NA = TBI * (1 + ASYM);
+            float acc[NA];
 #pragma unroll
-            for (int t = 0; t < TBI; t++) acc[t] = 0.0f;
+            for (int t = 0; t < NA; t++) acc[t] = 0.0f;
             int incl = 0;
             for (uint32_t kb = kbeg; kb < kend; kb += 16) {
                 const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl);
                 const Entry e{s.e0, s.e1};
-                accumulate<TBI, DICT>(e, xs_addr, 8u * (uint32_t)s.start, acc);
+                accumulate<TBI, DICT, ASYM>(e, xs_addr, 8u * (uint32_t)s.start, acc);
             }
 #pragma unroll
-            for (int t = 0; t < TBI; t++) acc[t] = row_sum16_to_last(acc[t]);
+            for (int t = 0; t < NA; t++) acc[t] = row_sum16_to_last(acc[t]);
             if (l16 == 15) {
 #pragma unroll
                 for (int t = 0; t < TBI; t++)
-                    if (t < ntok) reinterpret_cast<float *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] = acc[t] * scale;
+                    if (t < ntok) {
+                        float v = acc[t] * scale;
+                        if constexpr (ASYM) v = fmaf(acc[NA - TBI + t], mid, v);
+                        reinterpret_cast<float *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] = v;
+                    }
             }
         };
         switch (tbi) {
@@ -1145,7 +1236,9 @@ struct DecompressArgs {
     int n_groups, n_order;
 };
 
-template <int OUT>  // 0: int8 in {-1, 0, +1}; 1: bf16(scale of the row) with the weight's sign, or 0
+// OUT 0: int8 in {-1, 0, +1}; 1: bf16(scale of the row) with the weight's sign, or 0;
+// 2: the row's bf16 grid point w_max or w_min, or 0 (asymmetric grid)
+template <int OUT>
 __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1176,6 +1269,15 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
 
         // bf16 scale of the eight rows this lane writes out, in both halves of a register
         uint32_t s2[8];
+        if constexpr (OUT == 2) {
+            // the (w_min, w_max) pair as stored: w_min in the low half
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                s2[i] = 0u;
+                if (rl < a.rows_per_block && r0 + rl < a.rows && M.minmax_bf16) s2[i] = ((gp_u32)M.minmax_bf16)[r0 + rl];
+            }
+        }
         if constexpr (OUT == 1) {
 #pragma unroll
             for (int i = 0; i < 8; i++) {
@@ -1188,7 +1290,7 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
         }
 
         for (int c = 0; c < nsteps; c++) {
-            QMOE_RING_DECODE_STEP(c, {});
+            QMOE_RING_DECODE_STEP(c, {}, OUT == 2 ? 0 : 5);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int k = kc + 8 * seg;
@@ -1206,6 +1308,11 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
                         const uint32_t o0 = ((w0 >> 6) & 0x01010101u) | (((w0 >> 7) & 0x01010101u) * 0xFEu);
                         const uint32_t o1 = ((w1 >> 6) & 0x01010101u) | (((w1 >> 7) & 0x01010101u) * 0xFEu);
                         *reinterpret_cast<unsigned long long *>(out + at) = (unsigned long long)o0 | ((unsigned long long)o1 << 32);
+                    } else if constexpr (OUT == 2) {
+                        const bf16x8 v = mm_expand_minmax(w0, w1, s2[i] << 16, s2[i] & 0xFFFF0000u);
+                        u32x4 o;
+                        __builtin_memcpy(&o, &v, 16);
+                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
                     } else {
                         u32x4 o;
 #pragma unroll
@@ -1717,7 +1824,7 @@ struct ProductPlan {
 // Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
 // matrices with the lane-per-row kernel (compressed path).
 qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p,
-                         int n_order = 0, int force_blocks = 0, int stage_out_row_bytes = 0)
+                         int n_order = 0, int force_blocks = 0, int stage_out_row_bytes = 0, bool minmax = false)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
@@ -1794,7 +1901,8 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     // most rows a block can own under the even split of rows over lanes
     const long long all_lanes = (long long)best_b * best_t;
     p->rows_per_item = (int)std::min<long long>(rows, (long long)best_t * (rows / all_lanes + 1));
-    const size_t scale_bytes = ((size_t)p->rows_per_item * sizeof(uint16_t) + 15) / 16 * 16;
+    // binary16 scale, or bf16 (w_min, w_max) pair, of every row of a block
+    const size_t scale_bytes = ((size_t)p->rows_per_item * (minmax ? 4 : 2) + 15) / 16 * 16;
     if (lds_dict > 0 && n_order == 0) {
         // the row scales take their share of LDS from the table
         const size_t room = max_lds - xs_bytes(tb) - fixed - scale_bytes;
@@ -1870,14 +1978,20 @@ qmoe_status allow_lds(K kernel, size_t smem)
     return QMOE_OK;
 }
 
+template <int DICT, int EPI, int ASYM>
+qmoe_status launch_product_grid(const ProductArgs &a, const ProductPlan &p, hipStream_t s)
+{
+    const qmoe_status st = allow_lds(k_product<DICT, EPI, ASYM>, p.smem);
+    if (st != QMOE_OK) return st;
+    hipLaunchKernelGGL((k_product<DICT, EPI, ASYM>), dim3(p.grid), dim3(p.threads), p.smem, s, a);
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
+}
+
 template <int DICT, int EPI>
 qmoe_status launch_product_as(const ProductArgs &a, const ProductPlan &p, hipStream_t s)
 {
-    const qmoe_status st = allow_lds(k_product<DICT, EPI>, p.smem);
-    if (st != QMOE_OK) return st;
-    hipLaunchKernelGGL((k_product<DICT, EPI>), dim3(p.grid), dim3(p.threads), p.smem, s, a);
-    QMOE_HIP_TRY(hipGetLastError());
-    return QMOE_OK;
+    return a.minmax ? launch_product_grid<DICT, EPI, 1>(a, p, s) : launch_product_grid<DICT, EPI, 0>(a, p, s);
 }
 
 qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
@@ -1934,15 +2048,18 @@ qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
 {
     mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
     a.mm_stagger = tuning().mm_stagger > 0 ? 1 : 0;
-    if (a.epilogue) {
-        const qmoe_status st = allow_lds(k_product_mm<1>, mp.smem);
+    auto launch = [&](auto kernel) -> qmoe_status {
+        const qmoe_status st = allow_lds(kernel, mp.smem);
         if (st != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_product_mm<1>, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
-    } else {
-        const qmoe_status st = allow_lds(k_product_mm<0>, mp.smem);
-        if (st != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_product_mm<0>, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
-    }
+        hipLaunchKernelGGL(kernel, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
+        return QMOE_OK;
+    };
+    qmoe_status st;
+    if (a.minmax)
+        st = a.epilogue ? launch(k_product_mm<1, 1>) : launch(k_product_mm<0, 1>);
+    else
+        st = a.epilogue ? launch(k_product_mm<1, 0>) : launch(k_product_mm<0, 0>);
+    if (st != QMOE_OK) return st;
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }
@@ -1950,8 +2067,9 @@ qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
 qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
 {
     if (!d || !W) return QMOE_E_INVALID_ARG;
-    if (!W->codes || !W->row_off || !W->scale_f16 || W->rows < 1 || W->cols < 2 || (W->cols & 1))
+    if (!W->codes || !W->row_off || (!W->scale_f16 && !W->minmax_bf16) || W->rows < 1 || W->cols < 2 || (W->cols & 1))
         return QMOE_E_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(W->minmax_bf16) % 4) return QMOE_E_INVALID_ARG;  // pairs are read as one word
     if (W->cols > kMaxCols) return QMOE_E_LIMIT;
     if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
     return QMOE_OK;
@@ -1966,6 +2084,15 @@ void fill_tables(const qmoe_dict *d, ProductArgs *a, int code_order)
     a->n_groups = d->n_groups;
     a->n_order = (int)d->order_table.size();
     a->code_order = code_order;
+}
+
+// Splits a format argument (QMOE_FORMAT_* bits) into the numbering and the grid.
+qmoe_status split_format(int format, int *code_order, bool *minmax)
+{
+    if (format < 0 || (format & ~(QMOE_FORMAT_DEVICE_ORDER | QMOE_FORMAT_GRID_MINMAX))) return QMOE_E_INVALID_ARG;
+    *code_order = (format & QMOE_FORMAT_DEVICE_ORDER) ? 1 : 0;
+    *minmax = (format & QMOE_FORMAT_GRID_MINMAX) != 0;
+    return QMOE_OK;
 }
 
 qmoe_status check_code_order(const qmoe_dict *d, int code_order)
@@ -2124,13 +2251,17 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     const int grid = (int)std::min<long long>(items, 8LL * di.cus);
     const size_t smem = xs_bytes(std::max(tb, 4));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (run) {
-        if ((st = allow_lds(k_matvec_rows<true>, smem)) != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_matvec_rows<true>, dim3(grid), dim3(threads), smem, s, a);
-    } else {
-        if ((st = allow_lds(k_matvec_rows<false>, smem)) != QMOE_OK) return st;
-        hipLaunchKernelGGL(k_matvec_rows<false>, dim3(grid), dim3(threads), smem, s, a);
-    }
+    auto launch = [&](auto kernel) -> qmoe_status {
+        const qmoe_status lst = allow_lds(kernel, smem);
+        if (lst != QMOE_OK) return lst;
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), smem, s, a);
+        return QMOE_OK;
+    };
+    if (W->minmax_bf16)
+        st = run ? launch(k_matvec_rows<true, 1>) : launch(k_matvec_rows<false, 1>);
+    else
+        st = run ? launch(k_matvec_rows<true, 0>) : launch(k_matvec_rows<false, 0>);
+    if (st != QMOE_OK) return st;
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }
@@ -2166,6 +2297,11 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W, int8_t *
 qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats, int code_order, int n_mats, int rows,
                             int cols, int out_kind, void *const *out, void *stream)
 {
+    bool minmax = false;
+    {
+        const qmoe_status fst = split_format(code_order, &code_order, &minmax);
+        if (fst != QMOE_OK) return fst;
+    }
     if (!d || !mats || !out || n_mats < 1 || rows < 1 || cols < 2 || (out_kind != 0 && out_kind != 1))
         return QMOE_E_INVALID_ARG;
     if (cols % 8) return QMOE_E_INVALID_ARG;  // whole 8-column stores
@@ -2195,6 +2331,9 @@ qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats, int cod
     if (out_kind == 0) {
         if ((st = allow_lds(k_decompress<0>, smem)) != QMOE_OK) return st;
         hipLaunchKernelGGL(k_decompress<0>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    } else if (minmax) {
+        if ((st = allow_lds(k_decompress<2>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<2>, dim3(grid), dim3(kMmThreads), smem, s, a);
     } else {
         if ((st = allow_lds(k_decompress<1>, smem)) != QMOE_OK) return st;
         hipLaunchKernelGGL(k_decompress<1>, dim3(grid), dim3(kMmThreads), smem, s, a);
@@ -2236,6 +2375,8 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     if (!d || !expert_idx) return QMOE_E_INVALID_ARG;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
+    bool minmax = false;
+    if ((st = split_format(code_order, &code_order, &minmax)) != QMOE_OK) return st;
     if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
@@ -2244,11 +2385,11 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
                            tuning().blocks_first > 0 ? tuning().blocks_first : spread,
-                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread,
-                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0)) != QMOE_OK)
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax)) != QMOE_OK)
         return st;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
@@ -2267,6 +2408,8 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
+    bool minmax = false;
+    if ((st = split_format(code_order, &code_order, &minmax)) != QMOE_OK) return st;
     if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
@@ -2274,11 +2417,11 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
                            tuning().blocks_first > 0 ? tuning().blocks_first : spread,
-                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0)) != QMOE_OK)
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread,
-                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0)) != QMOE_OK)
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax)) != QMOE_OK)
         return st;
     MmPlan mp;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
@@ -2311,6 +2454,7 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     a.n_experts = n_experts;
     a.max_items = n_tokens;
     a.perm = lp.perm;
+    a.minmax = minmax ? 1 : 0;
     // first product: hidden[slot] = bf16(relu(Wi x[token]))
     ProductArgs a1 = a;
     a1.gate = nullptr;

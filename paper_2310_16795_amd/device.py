@@ -32,39 +32,56 @@ def _pad_to(a: np.ndarray, multiple: int) -> np.ndarray:
 class DeviceMatrix:
     """One compressed matrix in device memory and its qmoe_matrix descriptor."""
 
-    def __init__(self, codes: np.ndarray, row_off: np.ndarray, scale_f16: np.ndarray, rows: int, cols: int,
-                 device="cuda:0", device_order_of: "DeviceDict | None" = None):
-        assert row_off.shape == (rows + 1,) and scale_f16.shape == (rows,)
+    def __init__(self, codes: np.ndarray, row_off: np.ndarray, scale_f16: "np.ndarray | None", rows: int, cols: int,
+                 device="cuda:0", device_order_of: "DeviceDict | None" = None,
+                 minmax_bf16: "np.ndarray | None" = None):
+        """scale_f16 [rows] for the symmetric grid, or minmax_bf16 [rows, 2] = (w_min, w_max) for the asymmetric one."""
+        assert row_off.shape == (rows + 1,)
+        assert (scale_f16 is None) != (minmax_bf16 is None)
         self.codes = torch.from_numpy(_pad_to(codes.view(np.int16), 8).copy()).to(device)
         self.row_off = torch.from_numpy(row_off.astype(np.uint32).view(np.int32).copy()).to(device)
-        self.scale = torch.from_numpy(scale_f16.view(np.int16).copy()).to(device)
+        self.scale = self.minmax = None
+        if scale_f16 is not None:
+            assert scale_f16.shape == (rows,)
+            self.scale = torch.from_numpy(scale_f16.view(np.int16).copy()).to(device)
+        else:
+            assert minmax_bf16.shape == (rows, 2)
+            self.minmax = torch.from_numpy(np.ascontiguousarray(minmax_bf16).view(np.int16).copy()).to(device)
         order = 0
         if device_order_of is not None:  # renumber the stream for this dictionary, once
             B.qmoe_codes_to_device_order(device_order_of.handle, self.codes)
             order = 1
-        self.desc = B.qmoe_matrix(self.codes.data_ptr(), self.row_off.data_ptr(), self.scale.data_ptr(), rows,
-                                  cols, int(codes.size), order)
+        self.desc = B.qmoe_matrix(self.codes.data_ptr(), self.row_off.data_ptr(),
+                                  self.scale.data_ptr() if self.scale is not None else None, rows,
+                                  cols, int(codes.size), order,
+                                  self.minmax.data_ptr() if self.minmax is not None else None)
 
 
 class DeviceLayer:
     """All experts of one MoE layer: three big device buffers per projection and
     a device array of qmoe_matrix descriptors pointing into them."""
 
-    def __init__(self, n_experts: int, d_model: int, d_ff: int, device="cuda:0"):
+    def __init__(self, n_experts: int, d_model: int, d_ff: int, device="cuda:0", minmax: bool = False):
+        """minmax: the experts are on the asymmetric grid; set_expert then takes bf16 (w_min, w_max)
+        pairs [rows, 2] in place of the binary16 scales [rows]."""
         self.n_experts, self.d_model, self.d_ff, self.device = n_experts, d_model, d_ff, device
+        self.minmax = minmax
         self._host = {"wi": [None] * n_experts, "wo": [None] * n_experts}
         self.compressed_bytes = 0
         self.n_codes = {"wi": np.zeros(n_experts, dtype=np.int64), "wo": np.zeros(n_experts, dtype=np.int64)}
 
-    def set_expert(self, e: int, which: str, codes: np.ndarray, row_off: np.ndarray, scale_f16: np.ndarray):
+    def set_expert(self, e: int, which: str, codes: np.ndarray, row_off: np.ndarray, scale: np.ndarray):
         rows = self.d_ff if which == "wi" else self.d_model
-        assert row_off.shape == (rows + 1,) and scale_f16.shape == (rows,) and row_off[-1] == codes.size
-        self._host[which][e] = (codes, row_off.astype(np.uint32), scale_f16)
+        assert row_off.shape == (rows + 1,) and row_off[-1] == codes.size
+        assert scale.shape == ((rows, 2) if self.minmax else (rows,))
+        self._host[which][e] = (codes, row_off.astype(np.uint32), scale)
         self.n_codes[which][e] = codes.size
 
     def finalize(self, device_order_of: "DeviceDict | None" = None):
         """Upload everything; with device_order_of, renumber the streams for that dictionary."""
         self.code_order = 0 if device_order_of is None else 1
+        self.format = self.code_order | (B.FORMAT_GRID_MINMAX if self.minmax else 0)
+        per_row = 2 if self.minmax else 1  # 16-bit values of scale data per row
         self.bufs, self.desc_dev, self.desc_host = {}, {}, {}
         for which in ("wi", "wo"):
             rows = self.d_ff if which == "wi" else self.d_model
@@ -77,13 +94,13 @@ class DeviceLayer:
                     total += (p[0].size + 7) // 8 * 8  # 16-byte aligned start for every matrix
             codes = np.zeros(max(total, 8), dtype=np.uint16)
             row_off = np.zeros((self.n_experts, rows + 1), dtype=np.uint32)
-            scale = np.zeros((self.n_experts, rows), dtype=np.uint16)
+            scale = np.zeros((self.n_experts, rows * per_row), dtype=np.uint16)
             for e, p in enumerate(parts):
                 if p is None:
                     continue
                 codes[code_off[e]: code_off[e] + p[0].size] = p[0]
                 row_off[e] = p[1]
-                scale[e] = p[2]
+                scale[e] = p[2].reshape(-1)
             d_codes = torch.from_numpy(codes.view(np.int16)).to(self.device)
             if device_order_of is not None:
                 B.qmoe_codes_to_device_order(device_order_of.handle, d_codes)
@@ -93,14 +110,16 @@ class DeviceLayer:
             for e, p in enumerate(parts):
                 if p is None:
                     continue  # stays all-zero: never touched unless a token is routed there
+                at = d_scale.data_ptr() + 2 * e * rows * per_row
                 descs[e] = B.qmoe_matrix(d_codes.data_ptr() + 2 * code_off[e],
                                          d_row.data_ptr() + 4 * e * (rows + 1),
-                                         d_scale.data_ptr() + 2 * e * rows, rows, cols, int(p[0].size), self.code_order)
+                                         None if self.minmax else at, rows, cols, int(p[0].size), self.code_order,
+                                         at if self.minmax else None)
             raw = np.frombuffer(bytes(descs), dtype=np.uint8).copy()
             self.bufs[which] = (d_codes, d_row, d_scale)
             self.desc_host[which] = descs
             self.desc_dev[which] = torch.from_numpy(raw).to(self.device)
-            self.compressed_bytes += sum(2 * p[0].size + 6 * rows for p in parts if p is not None)
+            self.compressed_bytes += sum(2 * p[0].size + (4 + 2 * per_row) * rows for p in parts if p is not None)
         self._host = None
         return self
 
@@ -110,7 +129,7 @@ class DeviceLayer:
 
     def forward(self, dd: DeviceDict, x_bf16: torch.Tensor, expert_idx: torch.Tensor, y: torch.Tensor,
                 workspace: torch.Tensor, gate: torch.Tensor | None = None, stream=None):
-        B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.code_order, self.n_experts,
+        B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.format, self.n_experts,
                                  self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, workspace, stream)
 
 

@@ -37,10 +37,12 @@ def ddict(gpu, oracle_dict):
     dd.close()
 
 
-def _upload(oracle_dict, tern, scale, gpu, order_of=None):
-    """order_of: renumber the stream to the device order of that dictionary (None: as encoded)."""
+def _upload(oracle_dict, tern, scale, gpu, order_of=None, minmax=None):
+    """order_of: renumber the stream to the device order of that dictionary (None: as encoded).
+    minmax: bf16 (w_min, w_max) pairs [rows, 2] for the asymmetric grid (then scale is None)."""
     codes, row_off = oracle.encode(oracle_dict, tern)
-    return dev.DeviceMatrix(codes, row_off, scale, *tern.shape, device=gpu, device_order_of=order_of)
+    return dev.DeviceMatrix(codes, row_off, scale, *tern.shape, device=gpu, device_order_of=order_of,
+                            minmax_bf16=minmax)
 
 
 def _to_dev16(bits, gpu):
@@ -195,10 +197,11 @@ def test_dispatch_bit_exact(gpu, E, T, seed, order):
     dd.close()
 
 
-def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None):
-    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu)
+def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None, minmax=False):
+    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax)
     for e in (range(w.n_experts) if experts is None else experts):
-        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_scale(e)), ("wo", w.wo_ternary(e), w.wo_scale(e))):
+        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_minmax(e) if minmax else w.wi_scale(e)),
+                                   ("wo", w.wo_ternary(e), w.wo_minmax(e) if minmax else w.wo_scale(e))):
             if encoder == "oracle":
                 codes, row_off = oracle.encode(oracle_dict, tern)
             else:
@@ -217,18 +220,28 @@ def _run_layer(layer, ddict, x_bits, idx, gpu, gate=None):
     return y.cpu().numpy(), dev.read_workspace(ws, layer.n_experts, layer.d_model, layer.d_ff, T)
 
 
-def _check_layer(w, idx, x_bits, y_gpu, wsout, tokens, gate=None):
-    ref = oracle.moe_layer(w, idx, x_bits, gate=gate, tokens=tokens)
+def _check_layer(w, idx, x_bits, y_gpu, wsout, tokens, gate=None, asym=False):
+    ref = oracle.moe_layer(w, idx, x_bits, gate=gate, tokens=tokens, asym=asym)
     slot_of = {int(t): s for s, t in enumerate(wsout["perm"][: wsout["counters"][0]])}
     flips = total = 0
     for t in tokens:
         y_ref, h_ref, bound = ref[t]
-        _check_product(y_gpu[t][None, :], y_ref[None, :], bound[None, :], f"token {t}")
         h_gpu = wsout["hidden"][slot_of[t]]
         diff = h_gpu.astype(np.int32) - h_ref.astype(np.int32)
         assert np.all(np.abs(diff) <= 1), "hidden vector differs by more than one bf16 ulp"
         flips += int((diff != 0).sum())
         total += diff.size
+        if diff.any():
+            # A hidden value that sat on a rounding boundary went the other way (fp32 against
+            # fp64 sums): the second product is checked on the hidden vector it actually read.
+            # One such value moves an output by 2^-8 of one term, more than the tolerance on a
+            # sum of a few terms.
+            e = int(idx[t])
+            g = 1.0 if gate is None else float(gate[t])
+            y2, b2 = oracle.matvec(w.wo_ternary(e), None if asym else w.wo_scale(e), h_gpu[None, :], with_bound=True,
+                                   minmax_bf16=w.wo_minmax(e) if asym else None)
+            y_ref, bound = g * y2[0], abs(g) * b2[0]
+        _check_product(y_gpu[t][None, :], y_ref[None, :], bound[None, :], f"token {t}")
     assert flips <= max(2, total * 2e-3), f"{flips} of {total} hidden values rounded differently"
 
 
@@ -555,16 +568,18 @@ def test_bf16_comparator_close_to_the_compressed_layer(gpu, ddict, oracle_dict):
 # own dictionary and encoder, device-order streams, sampled tokens checked one
 # by one against the oracle (which regenerates and multiplies the expert densely).
 
-def _full_layer(w, gpu):
+def _full_layer(w, gpu, minmax=False):
+    """minmax: the same streams on the asymmetric grid (bf16 pairs in place of the scales)."""
     import os
     from concurrent.futures import ThreadPoolExecutor
     dd = dev.DeviceDict(device=gpu)
-    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu)
+    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax)
     q.qmoe_set_tuning("host_threads", 1)
 
     def one(e):
         out = []
-        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_scale(e)), ("wo", w.wo_ternary(e), w.wo_scale(e))):
+        for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_minmax(e) if minmax else w.wi_scale(e)),
+                                   ("wo", w.wo_ternary(e), w.wo_minmax(e) if minmax else w.wo_scale(e))):
             codes, row_off = q.qmoe_encode_host(dd.handle, tern)
             out.append((which, codes, row_off, scale))
         return e, out
@@ -618,4 +633,149 @@ def test_c2048_ragged_layer_full_size_sampled(gpu, oracle_dict):
     y, wsout = _run_layer(layer, dd, x, idx, gpu)
     assert np.isfinite(y).all()
     _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts, per_class=3))
+    dd.close()
+
+
+# ---------------------------------------------------------------- the asymmetric grid {w_min, 0, w_max}
+#
+# Same streams, one bf16 (w_min, w_max) pair per row in place of the scale; the oracle multiplies
+# with the dequantised matrix.  The bound is |w_max| * sum |x under +1| + |w_min| * sum |x under -1|.
+
+@pytest.mark.parametrize("rows,cols,p0,seed", [SHAPES[0], SHAPES[1], SHAPES[2], SHAPES[3], SHAPES[5], SHAPES[6]])
+@pytest.mark.parametrize("batch", [1, 3, 8, 19])
+@pytest.mark.parametrize("order", [0, 1])
+def test_decode_matvec_minmax_against_oracle(gpu, ddict, oracle_dict, rows, cols, p0, seed, batch, order):
+    tern = synth.ternary(seed, rows, cols, p0)
+    mm = synth.minmax_bf16(seed + 3000, rows, 0.01, 0.1)
+    x = synth.normal_bf16(seed + 2000, (batch, cols))
+    M = _upload(oracle_dict, tern, None, gpu, ddict if order else None, minmax=mm)
+    y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
+    q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
+    torch.cuda.synchronize()
+    y_ref, bound = oracle.matvec(tern, None, x, with_bound=True, minmax_bf16=mm)
+    _check_product(y.cpu().numpy(), y_ref, bound, f"{rows}x{cols} batch {batch}")
+
+
+def test_matvec_minmax_integer_inputs_are_exact(gpu, ddict, oracle_dict):
+    """Small integers and grid points that are small multiples of 1/4, of either sign: every partial
+    sum is exact in fp32, so a swapped pair, a wrong sign or a dropped term shows as a wrong integer."""
+    rows, cols = 64, 280
+    tern = synth.ternary(312, rows, cols, 0.85)
+    rng = np.random.default_rng(2)
+    w_min = rng.integers(-6, 3, rows) * 0.25
+    w_max = rng.integers(-1, 7, rows) * 0.25
+    mm = np.stack([synth.f64_to_bf16(w_min), synth.f64_to_bf16(w_max)], axis=1)
+    xi = rng.integers(-4, 5, (5, cols)).astype(np.float32)
+    x = torch.from_numpy(xi).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for order in (None, ddict):
+        M = _upload(oracle_dict, tern, None, gpu, order, minmax=mm)
+        y = torch.empty((5, rows), dtype=torch.float32, device=gpu)
+        q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), oracle.matvec(tern, None, x, minmax_bf16=mm))
+
+
+@pytest.mark.parametrize("d_model,d_ff,order", [(96, 200, 0), (96, 200, 1), (260, 300, 1), (450, 228, 0)])
+def test_small_layer_minmax_every_token(gpu, ddict, oracle_dict, d_model, d_ff, order):
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=12, d_model=d_model, d_ff=d_ff, n_tokens=70)
+    idx, x = w.expert_idx(), w.tokens()
+    idx[5:40] = 3      # one expert with many tokens (several tiles)
+    idx[idx == 7] = 8  # at least one expert without tokens
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict if order else None, minmax=True)
+    gate = np.random.default_rng(7).uniform(0.2, 1.0, idx.size)
+    y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
+    _check_layer(w, idx, x, y, wsout, list(range(idx.size)), gate, asym=True)
+    y2, _ = _run_layer(layer, ddict, x, idx, gpu, gate)
+    assert np.array_equal(y, y2)
+    # the pairs really are in use: the symmetric layer gives other numbers
+    sym = oracle.moe_layer(w, idx, x, gate=gate, tokens=[0])[0][0]
+    assert not np.allclose(y[0], sym, rtol=1e-2)
+    # tiles of one, two and eight tokens as well
+    for tile in (1, 2, 8):
+        q.qmoe_set_tuning("token_tile", tile)
+        try:
+            yt, wst = _run_layer(layer, ddict, x, idx, gpu, gate)
+        finally:
+            q.qmoe_set_tuning("token_tile", 0)
+        _check_layer(w, idx, x, yt, wst, list(range(idx.size)), gate, asym=True)
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(136, 600), (520, 72)])
+def test_crowded_experts_minmax_on_the_matrix_cores(gpu, ddict, oracle_dict, d_model, d_ff):
+    counts = [130, 65, 64, 33, 32, 31, 8, 7, 1, 0]
+    idx = np.concatenate([np.full(n, e, dtype=np.int32) for e, n in enumerate(counts)])
+    np.random.default_rng(11).shuffle(idx)
+    idx = np.concatenate([idx, np.array([-1], dtype=np.int32)])
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=len(counts), d_model=d_model, d_ff=d_ff,
+                                                 n_tokens=idx.size)
+    x = w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict, minmax=True)
+    gate = np.random.default_rng(12).uniform(0.2, 1.0, idx.size)
+    good = [t for t in range(idx.size) if idx[t] >= 0]
+    for min_tokens, n_mm in ((8, 10), (2, 11), (-1, 0)):
+        q.qmoe_set_tuning("mfma_min_tokens", min_tokens)
+        try:
+            y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
+            y_again, _ = _run_layer(layer, ddict, x, idx, gpu, gate)
+        finally:
+            q.qmoe_set_tuning("mfma_min_tokens", 0)
+        assert wsout["counters"][7] == n_mm
+        assert not y[-1].any() and np.array_equal(y, y_again)
+        _check_layer(w, idx, x, y, wsout, good, gate, asym=True)
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(136, 600), (1024, 72)])
+def test_decompress_minmax_bit_exact(gpu, ddict, oracle_dict, d_model, d_ff):
+    """bf16 output on the asymmetric grid is the row's own w_max / w_min / 0, bit for bit; int8 output
+    does not depend on the grid."""
+    w = synth.WORKLOADS["c2048_ragged256"].scaled(n_experts=4, d_model=d_model, d_ff=d_ff, n_tokens=8)
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict, minmax=True)
+    for which, rows, cols in (("wi", d_ff, d_model), ("wo", d_model, d_ff)):
+        for kind, dt in ((0, torch.int8), (1, torch.int16)):
+            outs = [torch.full((rows, cols), 77, dtype=dt, device=gpu) for _ in range(w.n_experts)]
+            ptrs = torch.tensor([o.data_ptr() for o in outs], dtype=torch.int64, device=gpu)
+            q.qmoe_decompress(ddict.handle, layer.desc_dev[which], layer.format, w.n_experts, rows, cols, kind, ptrs)
+            torch.cuda.synchronize()
+            for e in range(w.n_experts):
+                tern = w.wi_ternary(e) if which == "wi" else w.wo_ternary(e)
+                mm = w.wi_minmax(e) if which == "wi" else w.wo_minmax(e)
+                got = outs[e].cpu().numpy()
+                if kind == 0:
+                    assert np.array_equal(got, tern), f"{which} expert {e}"
+                else:
+                    want = np.where(tern == 0, np.uint16(0), np.where(tern > 0, mm[:, 1:2], mm[:, 0:1]))
+                    assert np.array_equal(got.view(np.uint16), want.astype(np.uint16)), f"{which} expert {e}"
+
+
+def test_minmax_format_errors(gpu, ddict, oracle_dict):
+    tern = synth.ternary(5, 8, 30, 0.8)
+    mm = synth.minmax_bf16(6, 8, 0.01, 0.1)
+    M = _upload(oracle_dict, tern, None, gpu, None, minmax=mm)
+    x = _to_dev16(synth.normal_bf16(7, (1, 30)), gpu)
+    y = torch.empty((1, 8), dtype=torch.float32, device=gpu)
+    bad = q.qmoe_matrix(M.desc.codes, M.desc.row_off, None, 8, 30, M.desc.n_codes, 0, M.desc.minmax_bf16 + 2)
+    with pytest.raises(q.QmoeError):  # pairs are read as one 32-bit word
+        q.qmoe_decode_matvec(ddict.handle, bad, x, y)
+    neither = q.qmoe_matrix(M.desc.codes, M.desc.row_off, None, 8, 30, M.desc.n_codes, 0, None)
+    with pytest.raises(q.QmoeError):
+        q.qmoe_decode_matvec(ddict.handle, neither, x, y)
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=2, d_model=32, d_ff=64, n_tokens=4)
+    layer = _build_layer(w, oracle_dict, gpu, minmax=True)
+    yl = torch.empty((4, 32), dtype=torch.float32, device=gpu)
+    with pytest.raises(q.QmoeError):  # unknown format bit
+        q.qmoe_moe_layer_forward(ddict.handle, layer.desc_dev["wi"], layer.desc_dev["wo"], 4, 2, 32, 64,
+                                 _to_dev16(w.tokens(), gpu), torch.from_numpy(w.expert_idx()).to(gpu), None, yl,
+                                 layer.workspace(4))
+    torch.cuda.synchronize()
+
+
+def test_c2048_ragged_minmax_full_size_sampled(gpu, oracle_dict):
+    """The ragged full-size layer on the asymmetric grid: scalar and matrix-core kernels side by side."""
+    w = synth.WORKLOADS["c2048_ragged256"]
+    idx, x = w.expert_idx(), w.tokens()
+    dd, layer = _full_layer(w, gpu, minmax=True)
+    y, wsout = _run_layer(layer, dd, x, idx, gpu)
+    assert np.isfinite(y).all()
+    assert wsout["counters"][7] > 0  # crowded experts went to the matrix cores
+    _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts, per_class=3), asym=True)
     dd.close()

@@ -33,7 +33,8 @@ def test_library_exports_every_declared_symbol():
     L = q.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert ctypes.sizeof(q.qmoe_matrix) == 40
+    assert ctypes.sizeof(q.qmoe_matrix) == 48 and q.qmoe_matrix.minmax_bf16.offset == 40
+    assert (q.FORMAT_DEVICE_ORDER, q.FORMAT_GRID_MINMAX) == (1, 2)
     assert L.qmoe_strerror(0) == b"ok" and L.qmoe_strerror(-4) == b"corrupt codeword stream"
     # run entries, interchange words, device-order table and map, then the encoder's trie (2^17 nodes)
     assert q.qmoe_dict_device_bytes() == 65536 * 4 + 65536 * 8 + 20480 * 4 + 65536 * 2 + (9 + 1) * 4 * (1 << 17)
@@ -194,6 +195,14 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     W = q.qmoe_matrix(256, 256, 256, 4, 8, 0, 0)
     assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -9     # not uploaded
     assert L.qmoe_decode_dense(lib_dict, ctypes.byref(W), 256, 0, None) == -9
+    W = q.qmoe_matrix(256, 256, None, 4, 8, 0, 0, 258)
+    assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -1     # pair array not 4-byte aligned
+    W = q.qmoe_matrix(256, 256, None, 4, 8, 0, 0, None)
+    assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -1     # neither scales nor pairs
+    W = q.qmoe_matrix(256, 256, None, 4, 8, 0, 0, 256)
+    assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -9     # pairs alone are enough
+    assert L.qmoe_moe_dispatch(lib_dict, 4, 256, 4, 4, 8, 16, 256, 1 << 30, None) == -1  # unknown format bit
+    assert L.qmoe_decompress(lib_dict, 256, 5, 2, 8, 16, 0, 256, None) == -1
     assert L.qmoe_moe_layer_forward(lib_dict, 256, 256, 0, 4, 8, 16, 256, 256, None, 4, 256, None, 0, None) == -9
     assert L.qmoe_codes_to_device_order(lib_dict, 256, 10, None) == -9
     assert L.qmoe_codes_to_device_order(lib_dict, None, 10, None) == -1
