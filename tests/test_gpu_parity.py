@@ -779,3 +779,25 @@ def test_c2048_ragged_minmax_full_size_sampled(gpu, oracle_dict):
     assert wsout["counters"][7] > 0  # crowded experts went to the matrix cores
     _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts, per_class=3), asym=True)
     dd.close()
+
+
+@pytest.mark.parametrize("minmax", [False, True])
+def test_layer_at_the_densest_natural_sparsity(gpu, ddict, oracle_dict, minmax):
+    """76.5 % zeros (the paper's natural sparsity of its 2-bit c2048 model): more than twice the codewords
+    per row of the 90 % workloads, most entries with two or three non-zeros.  Scalar kernel, then the
+    matrix-core kernel for every expert with two tokens or more."""
+    counts = [70, 33, 9, 4, 2, 1, 1, 0]
+    idx = np.concatenate([np.full(n, e, dtype=np.int32) for e, n in enumerate(counts)])
+    np.random.default_rng(21).shuffle(idx)
+    w = synth.WORKLOADS["c2048_sparsity765"].scaled(n_experts=len(counts), d_model=264, d_ff=520, n_tokens=idx.size)
+    assert abs((w.wi_ternary(0) == 0).mean() - 0.765) < 0.01
+    x = w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict, minmax=minmax)
+    for min_tokens in (-1, 2):
+        q.qmoe_set_tuning("mfma_min_tokens", min_tokens)
+        try:
+            y, wsout = _run_layer(layer, ddict, x, idx, gpu)
+        finally:
+            q.qmoe_set_tuning("mfma_min_tokens", 0)
+        assert (wsout["counters"][7] > 0) == (min_tokens == 2)
+        _check_layer(w, idx, x, y, wsout, list(range(idx.size)), asym=minmax)
