@@ -102,13 +102,16 @@ size_t qmoe_dict_device_bytes(void);
  * parameter and the set of runs are unchanged.
  *   code_map [65536]   interchange code -> device code
  *   table    [n_table] entry of group g at table[g] (both free signs positive), entry of
- *                      single code 4*n_groups + i at table[n_groups + i]; each entry is
+ *                      single code c = 4*n_groups + i at table[n_groups + i], stored with the
+ *                      toggles of c's own two low bits (below) applied; each entry is
  *                      byte 0 = 8 * run length, bytes 1..3 = one field per non-zero:
  *                      (position << 3) | (weight as 2-bit signed integer << 1), 0 = unused;
  *                      the fields are right-aligned (k non-zeros fill bytes 4-k..3 in
  *                      ascending position), so unused fields always come first
- * Device code c < 4*n_groups decodes to table[c >> 2] with bit 2 of field 1 set if c & 1
- * and bit 2 of field 2 set if c & 2 (which turns weight +1 into -1).
+ * Device code c decodes to table[c < 4*n_groups ? c >> 2 : c - 3*n_groups] with bit 2 of
+ * field 1 toggled if c & 1 and bit 2 of field 2 toggled if c & 2 (in a group that turns
+ * weight +1 into -1; for a single code it undoes the stored toggles), so a kernel treats
+ * every code alike.
  * code_map and table are NULL (n_table = 0) when the dictionary has no device order.
  */
 qmoe_status qmoe_dict_device_order(const qmoe_dict *d, const uint16_t **code_map, const uint32_t **table,

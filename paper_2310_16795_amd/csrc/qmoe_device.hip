@@ -145,16 +145,18 @@ using lp_u32 = const __attribute__((address_space(3))) uint32_t *;
 using lp_u16 = const __attribute__((address_space(3))) uint16_t *;
 
 // Entry of a device-order code from the group/single table (see qmoe_internal.h):
-// codes below 4 * n_groups share table[code >> 2] and flip the signs of fields 1 and 2
-// with their two low bits; the rest are single entries.
+// codes below 4 * n_groups share table[code >> 2], the rest are single entries at
+// table[code - 3 * n_groups]; the index is the larger of the two expressions (the
+// subtraction saturating at zero): they cross exactly at code = 4 * n_groups.  The two low
+// bits of every code flip the sign bits of fields 1 and 2; the single entries are stored
+// with those flips already applied once, so that the second application restores them
+// and no case distinction is needed.
 template <typename TablePtr>
 __device__ __forceinline__ uint32_t order_entry(TablePtr table, uint32_t code, uint32_t n_groups, uint32_t n_order)
 {
-    const bool grouped = code < 4u * n_groups;
-    const uint32_t u = grouped ? (code >> 2) : code - 3u * n_groups;
-    const uint32_t s = grouped ? (code & 3u) : 0u;
-    const uint32_t flips = (s * ((1u << 18) | (1u << 25))) & ((1u << 18) | (1u << 26));
-    return table[min(u, n_order - 1u)] | flips;
+    const uint32_t u = max(code >> 2, __builtin_elementwise_sub_sat(code, 3u * n_groups));
+    const uint32_t flips = ((code & 3u) * ((1u << 18) | (1u << 25))) & ((1u << 18) | (1u << 26));
+    return table[min(u, n_order - 1u)] ^ flips;
 }
 
 // Decode one step (one codeword per lane) and return this lane's run:
@@ -395,17 +397,21 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
                                          uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
 {
     constexpr int NA = TBI * (1 + ASYM);
+    // One token: positions are kept as LDS addresses of the column's record (the base is
+    // added once for the eight entries, not once per entry); tiles: 8 * column.
+    const uint32_t base = TBI == 1 ? xs_addr : 0u;
+    const uint32_t lim = cols8 + base;
     uint32_t pos[8];
     bool wrap[8];
-    uint32_t p = st.pos8;
+    uint32_t p = st.pos8 + base;
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         pos[j] = p;
         p += e[j].e0 & 0xFFu;
-        wrap[j] = p >= cols8;
+        wrap[j] = p >= lim;
         p = wrap[j] ? p - cols8 : p;
     }
-    st.pos8 = p;
+    st.pos8 = p - base;
     float snap[NA];
     bool wrapped = false;
 #pragma unroll
@@ -417,7 +423,7 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
         uint32_t xa[ASYM ? 24 : 1];  // asymmetric grid: the same inputs with their own sign (+x of each record)
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const uint32_t rec = xs_addr + pos[j];
+            const uint32_t rec = pos[j];
 #pragma unroll
             for (int z = 0; z < 3; z++) {
                 const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);

@@ -52,6 +52,14 @@ void pack_words(uint64_t syms, int npairs, uint32_t *w)
 
 // Device numbering of the codewords: group the sign variants of the last two non-zeros
 // of each run under one table entry (see qmoe_internal.h).
+// What the two low bits of a device code toggle in its table entry: the sign bits of
+// fields 1 and 2.  The kernels apply it to every code; single entries are stored with it
+// applied once already.
+inline uint32_t order_flips(uint32_t code)
+{
+    return ((code & 1u) << 18) | ((code & 2u) << 25);
+}
+
 void build_device_order(qmoe_dict *d)
 {
     d->order_table.clear();
@@ -102,12 +110,12 @@ void build_device_order(qmoe_dict *d)
         // fields right-aligned like those of the groups: unused ones (0) come first
         uint32_t e = d->run[k];
         while ((e >> 8) != 0u && (e >> 24) == 0u) e = (e & 0xFFu) | ((e & 0xFFFFFF00u) << 8);
-        table.push_back(e);
+        table.push_back(e ^ order_flips((uint32_t)device_of[k]));
     }
     int absent = -1;  // codes that name no entry all map to one empty single entry
     if (n < kTableEntries) {
         absent = next++;
-        table.push_back(0u);
+        table.push_back(0u ^ order_flips((uint32_t)absent));
     }
     if ((int)table.size() > kMaxOrderTable || next > kTableEntries) return;
     d->order_map.assign(kTableEntries, (uint16_t)(absent >= 0 ? absent : 0));

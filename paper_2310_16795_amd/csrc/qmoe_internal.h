@@ -34,7 +34,9 @@ constexpr int kRunMaxNonzeros = 3;
 // their common entry is table[g] with those two signs positive; the two low code bits
 // then flip the sign bits of fields 1 and 2.  Entries that have no complete group of
 // four (at most one non-zero, or variants missing from the dictionary) follow as
-// "single" codes, device code = 4 * n_groups + i, entry table[n_groups + i].  A stream is
+// "single" codes, device code = 4 * n_groups + i, entry table[n_groups + i], stored with the
+// flips of its own code's two low bits applied (a kernel flips every code alike and so
+// restores them).  A stream is
 // rewritten once, in place, when it is loaded; its length and the set of runs it can
 // express are unchanged.
 constexpr int kMaxOrderTable = 20480;  // entries (80 KiB); larger tables keep the interchange numbering

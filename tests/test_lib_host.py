@@ -221,14 +221,13 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
 
 def _decode_device_code(code, table, n_groups):
     """Symbols of a device-order code, decoded the way include/qmoe.h describes it."""
-    if code < 4 * n_groups:
-        e = int(table[code >> 2])
-        if code & 1:
-            e |= 1 << 18
-        if code & 2:
-            e |= 1 << 26
-    else:
-        e = int(table[n_groups + code - 4 * n_groups])
+    e = int(table[code >> 2 if code < 4 * n_groups else code - 3 * n_groups])
+    if code & 1:
+        e ^= 1 << 18
+    if code & 2:
+        e ^= 1 << 26
+    # the kernels' branch-free index: the two expressions cross at 4 * n_groups
+    assert max(code >> 2, max(code - 3 * n_groups, 0)) == (code >> 2 if code < 4 * n_groups else code - 3 * n_groups)
     length = (e & 0xFF) >> 3
     syms = [0] * length
     for j in range(3):
