@@ -222,6 +222,10 @@ qmoe_status qmoe_codes_to_device_order(const qmoe_dict *d, uint16_t *codes /*dev
  * (W->minmax_bf16 set: y[b][r] = w_max[r] * (sum of x under +1) + w_min[r] * (sum under -1))
  * W: host struct holding device pointers.  x: device bf16 [batch][cols].
  * y: device fp32 [batch][rows], overwritten.  fp32 accumulation.
+ * One launch.  A small batch runs on a kernel that puts 16 lanes on every row (latency of a
+ * single product); from a few dozen tokens on (device-order stream, cols divisible by 8, x
+ * 16-byte aligned; the switch is a cost estimate, "mfma_min_tokens" overrides it) the matrix
+ * is decoded once per 64 tokens and multiplied on the matrix cores.
  * Errors: INVALID_ARG (NULL, batch<1, odd cols), NO_DEVICE_DICT, LIMIT
  * (cols > 32768), HIP.
  */
@@ -342,8 +346,8 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
  * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
  * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
  * "grid_per_cu", "blocks_first" / "blocks_second" (workgroups that share one pass over a
- * matrix in the first or only / the second product), "mfma_min_tokens" (experts with at
- * least this many tokens use the matrix-core kernel; -1 = never), "overlap" (-1 = no side
+ * matrix in the first or only / the second product), "mfma_min_tokens" (experts -- or, in
+ * qmoe_decode_matvec, batches -- with at least this many tokens use the matrix-core kernel; -1 = never), "overlap" (-1 = no side
  * stream: all kernels of a layer one after the other on the caller's stream),
  * "host_threads" (encoder
  * threads),

@@ -1076,9 +1076,13 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     float *gate_s = reinterpret_cast<float *>(tok_ids + kMmTokens);   // [64]
     int *next_item = reinterpret_cast<int *>(gate_s + kMmTokens);     // [1]
 
-    const int n_items = min(*a.n_items_dev, a.max_items);
+    // A layer call brings a list of (expert, token tile) items and a device counter that hands
+    // them out; the single-matrix call has neither: its items are the tiles of 64 consecutive
+    // tokens of `single`, dealt out round robin.
+    const bool listed = a.items != nullptr;
+    const int n_items = listed ? min(*a.n_items_dev, a.max_items) : (a.batch + kMmTokens - 1) / kMmTokens;
     const int total = (int)min((long long)n_items * a.mm_row_blocks, 0x7FFFFFFFLL);
-    if (total <= 0) return;
+    if (total <= 0 || (!listed && (int)blockIdx.x >= total)) return;
     for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
 
     // Order of arrival of this wavefront on its SIMD (SIMD_ID: bits 5:4 of HW_ID): the
@@ -1095,18 +1099,27 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
         lag = __builtin_amdgcn_readfirstlane(rank) & 1;
     }
 
+    int g_static = (int)blockIdx.x;
     for (;;) {
         __syncthreads();  // everyone is done with the previous item
         if (threadIdx.x == 0) {
-            const int g = atomicAdd(a.work_counter, 1);
+            const int g = listed ? atomicAdd(a.work_counter, 1) : g_static;
             *next_item = g < total ? g : -1;
         }
+        g_static += (int)gridDim.x;
         __syncthreads();
         const int g = *next_item;
         if (g < 0) break;
         const int idx = g / a.mm_row_blocks;
         const int blk = g - idx * a.mm_row_blocks;
-        const Item it = a.items[idx];
+        Item it;
+        if (listed) {
+            it = a.items[idx];
+        } else {
+            it.expert = 0;
+            it.slot0 = idx * kMmTokens;
+            it.ntok = a.batch - idx * kMmTokens;
+        }
         const int expert = it.expert, slot0 = it.slot0;
         const int ntok = min(it.ntok, kMmTokens);
         if (expert < 0 || expert >= a.n_experts || ntok < 1) continue;
@@ -2050,9 +2063,16 @@ qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, i
     return QMOE_OK;
 }
 
-qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
+// rows_per_block: 0 = as few workgroups per matrix as possible (a layer call has many
+// matrices); otherwise a multiple of 64 up to 512.
+qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s, int rows_per_block = 0)
 {
-    mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
+    if (rows_per_block > 0) {
+        a.mm_rows_per_block = rows_per_block;
+        a.mm_row_blocks = (a.rows + rows_per_block - 1) / rows_per_block;
+    } else {
+        mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
+    }
     a.mm_stagger = tuning().mm_stagger > 0 ? 1 : 0;
     auto launch = [&](auto kernel) -> qmoe_status {
         const qmoe_status st = allow_lds(kernel, mp.smem);
@@ -2252,11 +2272,44 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     a.rows = W->rows;
     a.cols = W->cols;
     a.tb_max = tb;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Many tokens: the matrix-core kernel decodes the matrix once per 64 tokens instead of once
+    // per 8.  One matrix has few row blocks of 512, so the blocks are made as small as they can
+    // be with all of them resident at once (every block still decodes only its own rows; a
+    // block's time is set by the length of a row, not by how many rows it has).
+    {
+        const Tuning &tu = tuning();
+        const int n_order = (int)d->order_table.size();
+        if (code_order == 1 && run && n_order > 0 && tu.mfma_min_tokens >= 0 && W->cols % 8 == 0 &&
+            reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0 && mm_lds_bytes(n_order) <= (size_t)di.max_lds) {
+            const int tiles = (batch + kMmTokens - 1) / kMmTokens;
+            int rpb = 64;
+            while (rpb < kMmThreads && (long long)tiles * ((W->rows + rpb - 1) / rpb) > di.cus) rpb += 64;
+            const long long blocks = (long long)tiles * ((W->rows + rpb - 1) / rpb);
+            // Measured on this GPU (microseconds): a round of the matrix-core kernel takes about
+            // 8 + 0.0225 per column; the other kernel works through tiles of eight tokens at 0.62
+            // million weights per microsecond with one workgroup resident per compute unit (long
+            // rows: the tile's activations fill the LDS), 1.6 with four, 2.5-3 with eight.
+            const double rounds = std::ceil((double)blocks / di.cus);
+            const double t_mm = rounds * (8.0 + 0.0225 * W->cols);
+            const int resident = (int)std::max<size_t>(1, std::min<size_t>(8, (size_t)di.max_lds / xs_bytes(8)));
+            const double rate = 0.62e6 * (1.0 + 0.55 * (resident - 1));
+            const double t_rows = std::max(8.5, 4.0 + std::ceil(batch / 8.0) * (double)W->rows * W->cols / rate);
+            const bool take = tu.mfma_min_tokens > 0 ? batch >= tu.mfma_min_tokens : t_mm < t_rows;
+            if (take) {
+                a.minmax = W->minmax_bf16 ? 1 : 0;
+                a.epilogue = 0;
+                MmPlan mp;
+                mp.smem = mm_lds_bytes(n_order);
+                mp.grid = (int)std::min<long long>(blocks, di.cus);
+                return launch_product_mm(a, mp, s, rpb);
+            }
+        }
+    }
     const int threads = 256;  // 16 rows at a time
     const long long items = (long long)((batch + tb - 1) / tb) * ((W->rows + threads / 16 - 1) / (threads / 16));
     const int grid = (int)std::min<long long>(items, 8LL * di.cus);
     const size_t smem = xs_bytes(std::max(tb, 4));
-    hipStream_t s = static_cast<hipStream_t>(stream);
     auto launch = [&](auto kernel) -> qmoe_status {
         const qmoe_status lst = allow_lds(kernel, smem);
         if (lst != QMOE_OK) return lst;

@@ -801,3 +801,45 @@ def test_layer_at_the_densest_natural_sparsity(gpu, ddict, oracle_dict, minmax):
             q.qmoe_set_tuning("mfma_min_tokens", 0)
         assert (wsout["counters"][7] > 0) == (min_tokens == 2)
         _check_layer(w, idx, x, y, wsout, list(range(idx.size)), asym=minmax)
+
+
+@pytest.mark.parametrize("rows,cols,p0,seed", [(3072, 768, 0.90, 401), (200, 2080, 0.885, 402), (70, 6144, 0.97, 403),
+                                               (1000, 136, 0.80, 404)])
+@pytest.mark.parametrize("batch", [64, 65, 200])
+@pytest.mark.parametrize("minmax", [False, True])
+def test_decode_matvec_large_batch_on_the_matrix_cores(gpu, ddict, oracle_dict, rows, cols, p0, seed, batch, minmax):
+    """A device-order matrix with many tokens goes through the matrix-core kernel (tiles of 64 tokens
+    made up by the kernel itself, row blocks as small as fit the GPU in one round; forced here from 64
+    tokens on, by default a cost estimate decides); with the matrix cores switched off the
+    16-lanes-per-row kernel must give the same numbers to the tolerance."""
+    tern = synth.ternary(seed, rows, cols, p0)
+    scale = None if minmax else synth.uniform_f16(seed + 1000, (rows,), 0.01, 0.1)
+    mm = synth.minmax_bf16(seed + 3000, rows, 0.01, 0.1) if minmax else None
+    x = synth.normal_bf16(seed + 2000, (batch, cols))
+    M = _upload(oracle_dict, tern, scale, gpu, ddict, minmax=mm)
+    y_ref, bound = oracle.matvec(tern, scale, x, with_bound=True, minmax_bf16=mm)
+    xd = _to_dev16(x, gpu)
+    for setting in (64, -1):
+        q.qmoe_set_tuning("mfma_min_tokens", setting)
+        try:
+            y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
+            q.qmoe_decode_matvec(ddict.handle, M.desc, xd, y)
+            torch.cuda.synchronize()
+        finally:
+            q.qmoe_set_tuning("mfma_min_tokens", 0)
+        _check_product(y.cpu().numpy(), y_ref, bound, f"{rows}x{cols} batch {batch} setting {setting}")
+    # a small batch forced onto the matrix cores, and an activation pointer that is not 16-byte
+    # aligned (falls back to the other kernel): same answers
+    q.qmoe_set_tuning("mfma_min_tokens", 2)
+    try:
+        y = torch.full((5, rows), float("nan"), dtype=torch.float32, device=gpu)
+        q.qmoe_decode_matvec(ddict.handle, M.desc, xd[:5], y)
+        shifted = torch.empty(batch * cols + 1, dtype=torch.int16, device=gpu)
+        shifted[1:] = xd.reshape(-1)
+        y_un = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
+        q.qmoe_decode_matvec(ddict.handle, M.desc, shifted[1:].view(batch, cols), y_un)
+        torch.cuda.synchronize()
+    finally:
+        q.qmoe_set_tuning("mfma_min_tokens", 0)
+    _check_product(y.cpu().numpy(), y_ref[:5], bound[:5], "forced small batch")
+    _check_product(y_un.cpu().numpy(), y_ref, bound, "unaligned activations")
