@@ -227,7 +227,8 @@ qmoe_status qmoe_codes_to_device_order(const qmoe_dict *d, uint16_t *codes /*dev
  * 16-byte aligned; the switch is a cost estimate, "mfma_min_tokens" overrides it) the matrix
  * is decoded once per 64 tokens and multiplied on the matrix cores.
  * Errors: INVALID_ARG (NULL, batch<1, odd cols), NO_DEVICE_DICT, LIMIT
- * (cols > 32768), HIP.
+ * (cols > 32768, or four tokens' activations, 8 bytes per column, do not fit the LDS: cols
+ * above 20448 on a GPU with 160 KB), HIP.
  */
 qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
                                const uint16_t *x_bf16 /*device*/, int batch, float *y /*device*/,
@@ -309,7 +310,10 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * before the call's work ends, so that later work on `stream` sees y complete as usual;
  * calls on one device must not be issued concurrently from several host threads.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
- * n_tokens > 2^20, d_model or d_ff > 32768; code_order 1 without a device order), HIP.
+ * n_tokens > 2^20, d_model or d_ff > 32768, or too wide for the LDS: a token's activations
+ * take 8 bytes per column and, with the device numbering, share the LDS with the whole table
+ * -- with 160 KB and the 2^16-entry table of the paper that is 10022 columns, about 20400 with
+ * the interchange numbering; code_order 1 without a device order), HIP.
  */
 qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*device*/,
                                    const qmoe_matrix *wo /*device*/, int code_order, int n_experts,

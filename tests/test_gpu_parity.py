@@ -843,3 +843,46 @@ def test_decode_matvec_large_batch_on_the_matrix_cores(gpu, ddict, oracle_dict, 
         q.qmoe_set_tuning("mfma_min_tokens", 0)
     _check_product(y.cpu().numpy(), y_ref[:5], bound[:5], "forced small batch")
     _check_product(y_un.cpu().numpy(), y_ref, bound, "unaligned activations")
+
+
+# ---------------------------------------------------------------- widest inputs the kernels take
+#
+# The activations of a tile sit in LDS (160 KB), 8 bytes per column for up to four tokens, next to
+# the table when the stream uses the device numbering; beyond that the calls refuse (LIMIT).
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_decode_matvec_at_the_widest_row(gpu, ddict, oracle_dict, order):
+    rows, cols = 24, 20448
+    tern = synth.ternary(501, rows, cols, 0.93)
+    scale = synth.uniform_f16(502, (rows,), 0.01, 0.1)
+    M = _upload(oracle_dict, tern, scale, gpu, ddict if order else None)
+    for batch in (1, 6):  # six tokens: a tile of eight does not fit, tiles of four do
+        x = synth.normal_bf16(503 + batch, (batch, cols))
+        y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
+        q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
+        torch.cuda.synchronize()
+        y_ref, bound = oracle.matvec(tern, scale, x, with_bound=True)
+        _check_product(y.cpu().numpy(), y_ref, bound, f"batch {batch}")
+    # two columns more: refused, nothing launched
+    wide = q.qmoe_matrix(M.desc.codes, M.desc.row_off, M.desc.scale_f16, rows, cols + 2, M.desc.n_codes, order, None)
+    xw = torch.zeros((1, cols + 2), dtype=torch.int16, device=gpu)
+    yw = torch.zeros((1, rows), dtype=torch.float32, device=gpu)
+    with pytest.raises(q.QmoeError) as ei:
+        q.qmoe_decode_matvec(ddict.handle, wide, xw, yw)
+    assert ei.value.status == -10
+
+
+@pytest.mark.parametrize("order,d_ff,ok", [(1, 10016, True), (1, 10080, False), (0, 20400, True), (0, 20480, False)])
+def test_layer_at_the_widest_hidden_size(gpu, ddict, oracle_dict, order, d_ff, ok):
+    """The second product stages d_ff activations per token; with the device numbering the whole table
+    shares the LDS with them."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=3, d_model=64, d_ff=d_ff, n_tokens=7)
+    idx, x = w.expert_idx(), w.tokens()
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict if order else None)
+    if ok:
+        y, wsout = _run_layer(layer, ddict, x, idx, gpu)
+        _check_layer(w, idx, x, y, wsout, list(range(idx.size)))
+    else:
+        with pytest.raises(q.QmoeError) as ei:
+            _run_layer(layer, ddict, x, idx, gpu)
+        assert ei.value.status == -10
