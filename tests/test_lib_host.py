@@ -273,3 +273,13 @@ def test_device_order_of_small_and_dense_dictionaries():
     assert len(set(code_map[3000:].tolist())) == 1
     assert _decode_device_code(int(code_map[3000]), table, n_groups) == ()
     q.qmoe_dict_destroy(d)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N above 1 exits with a message that says so, before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and r.stdout.strip() == ""
+    assert "one GPU" in r.stderr
