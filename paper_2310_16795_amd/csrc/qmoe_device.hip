@@ -1432,13 +1432,61 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int &total)
     return base + incl - v;
 }
 
+// The same for N values per thread at once (three barriers for all of them).
+// `tmp` holds >= 17 * N ints.
+template <int N>
+__device__ __forceinline__ void block_exclusive_scan_n(const int (&v)[N], int *tmp, int (&excl)[N], int (&total)[N])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = (blockDim.x + 63) >> 6;
+    int incl[N];
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        incl[k] = v[k];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl[k], d, 64);
+            if (lane >= d) incl[k] += up;
+        }
+        if (lane == 63) tmp[wave * N + k] = incl[k];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // lane l: value l % N of wavefront l / N, for up to 64 / N wavefronts a turn
+        for (int w0 = 0; w0 < nwaves; w0 += 64 / N) {
+            const int k = lane % N, w = w0 + lane / N;
+            const bool live = lane < (64 / N) * N && w < nwaves;
+            const int mine = live ? tmp[w * N + k] : 0;
+            int run = mine;  // inclusive over the wavefronts of this turn, same k: stride N lanes
+#pragma unroll
+            for (int d = N; d < 64; d <<= 1) {
+                const int up = __shfl_up(run, d, 64);
+                if (lane >= d) run += up;
+            }
+            const int carry = w0 ? tmp[16 * N + k] : 0;  // total of the turns before
+            if (live) tmp[w * N + k] = carry + run - mine;
+            __builtin_amdgcn_wave_barrier();
+            // the last live wavefront of the turn leaves the running total
+            const int last_w = min(nwaves, w0 + 64 / N) - 1;
+            if (live && w == last_w) tmp[16 * N + k] = carry + run;
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        excl[k] = tmp[wave * N + k] + incl[k] - v[k];
+        total[k] = tmp[16 * N + k];
+    }
+    __syncthreads();
+}
+
 // One workgroup of 1024 threads groups the tokens by expert (stable) and writes
 // the work lists of both products.
 __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
 {
     extern __shared__ int sm[];
     int *cnt = sm;                 // [E] token count, later the write cursor of each expert
-    int *tmp = sm + a.n_experts;   // [32]
+    int *tmp = sm + a.n_experts;   // [256] scan scratch, then two arrays of one round of tokens
     const int E = a.n_experts, T = a.n_tokens;
     const int tid = threadIdx.x, nthr = blockDim.x;
 
@@ -1479,19 +1527,20 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
             if (n % a.tb_wo) s_wo[tile_class(n % a.tb_wo)]++;
         }
     }
-    int tot_tok, tot_act, tot_mm, tot_drop;
-    int p_tok = block_exclusive_scan(s_tok, tmp, tot_tok);
-    block_exclusive_scan(s_act, tmp, tot_act);
-    int p_mm = block_exclusive_scan(s_mm, tmp, tot_mm);
-    block_exclusive_scan(dropped, tmp, tot_drop);
+    // all twelve sums in one scan
+    const int sums[12] = {s_tok, s_act, s_mm, dropped, s_wi[0], s_wi[1], s_wi[2], s_wi[3],
+                          s_wo[0], s_wo[1], s_wo[2], s_wo[3]};
+    int before[12], all[12];
+    block_exclusive_scan_n<12>(sums, tmp, before, all);
+    int p_tok = before[0], p_mm = before[2];
+    const int tot_tok = all[0], tot_act = all[1], tot_mm = all[2], tot_drop = all[3];
     int p_wi[4], p_wo[4], tot_wi = 0, tot_wo = 0;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-        int t_wi, t_wo;
-        p_wi[k] = tot_wi + block_exclusive_scan(s_wi[k], tmp, t_wi);
-        p_wo[k] = tot_wo + block_exclusive_scan(s_wo[k], tmp, t_wo);
-        tot_wi += t_wi;
-        tot_wo += t_wo;
+        p_wi[k] = tot_wi + before[4 + k];
+        p_wo[k] = tot_wo + before[8 + k];
+        tot_wi += all[4 + k];
+        tot_wo += all[8 + k];
     }
     for (int e = e0; e < e1; e++) {
         const int n = cnt[e];
@@ -1527,9 +1576,14 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
     __syncthreads();
 
     // Stable scatter.  A wavefront takes 64 consecutive tokens; inside it a token's
-    // rank among equal experts is counted by broadcasting every lane once.  The
-    // wavefronts then append their tokens one after the other, in token order.
+    // rank among equal experts is counted by broadcasting every lane once.  The chunks of
+    // 64 tokens must then take their places one after the other, in token order: one
+    // wavefront walks the chunks of a round (no workgroup barrier between them), reads each
+    // token's expert cursor and moves the cursors on; after that every thread stores its
+    // own token.
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthr >> 6;
+    int *tok_e = tmp + 256;          // [nthr] expert of the round's tokens (-1: none)
+    int *tok_rs = tok_e + nthr;      // [nthr] rank | same << 8, later the token's slot
     for (int base = 0; base < T; base += nthr) {
         const int t = base + tid;
         int e = -1;
@@ -1538,20 +1592,35 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
             if (e < 0 || e >= E) e = -1;
         }
         int rank = 0, same = 0;
+#pragma unroll 8
         for (int j = 0; j < 64; j++) {
-            const int ej = __shfl(e, j, 64);
+            const int ej = __builtin_amdgcn_readlane(e, j);  // j is uniform: a scalar read, no LDS crossbar
             const int m = (ej == e) ? 1 : 0;
             same += m;
             rank += (j < lane) ? m : 0;
         }
-        for (int w = 0; w < nwaves; w++) {
-            if (w == wave && e >= 0) {
-                const int cur = cnt[e];
-                a.perm[cur + rank] = t;
-                if (rank == same - 1) cnt[e] = cur + same;
+        tok_e[tid] = e;
+        tok_rs[tid] = rank | (same << 8);
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = 0; w < nwaves; w++) {
+                const int ew = tok_e[64 * w + lane], rs = tok_rs[64 * w + lane];
+                const int rk = rs & 0xFF, sm_ = rs >> 8;
+                int cur = 0;
+                if (ew >= 0) cur = cnt[ew];
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();  // every lane has read its cursor
+                if (ew >= 0) {
+                    tok_rs[64 * w + lane] = cur + rk;
+                    if (rk == sm_ - 1) cnt[ew] = cur + sm_;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();  // the cursors are moved before the next chunk reads them
             }
-            __syncthreads();
         }
+        __syncthreads();
+        if (e >= 0) a.perm[tok_rs[tid]] = t;
+        __syncthreads();  // the round's arrays are free again
     }
 }
 
@@ -2170,7 +2239,8 @@ qmoe_status launch_dispatch(const int32_t *expert_idx, int n_tokens, int n_exper
     da.mm_min = mm_min;
     da.y = y;
     da.d_model = d_model;
-    const size_t smem = sizeof(int) * ((size_t)n_experts + 32);
+    // token counts, scan scratch (17 x 12, rounded up), two arrays of one round of tokens
+    const size_t smem = sizeof(int) * ((size_t)n_experts + 256 + 2 * 1024);
     const qmoe_status st = allow_lds(k_dispatch, smem);
     if (st != QMOE_OK) return st;
     hipLaunchKernelGGL(k_dispatch, dim3(1), dim3(1024), smem, s, da);
