@@ -144,6 +144,27 @@ using gp_u32x4 = const __attribute__((address_space(1))) u32x4 *;
 using lp_u32 = const __attribute__((address_space(3))) uint32_t *;
 using lp_u16 = const __attribute__((address_space(3))) uint16_t *;
 
+// Copy n 32-bit words from global memory to LDS with the whole workgroup (both 16-byte
+// aligned): 16 bytes per lane and up to eight loads in flight per lane before the first
+// store.  (A plain word-by-word loop waits for every load before it issues the next; for the
+// 65 KB table that was 20-60 us at the start of every workgroup.)
+__device__ __forceinline__ void stage_words(uint32_t *dst_lds, const uint32_t *src, int n)
+{
+    const int n4 = n >> 2;  // whole 16-byte pieces
+    gp_u32x4 s4 = (gp_u32x4)src;
+    u32x4 *d4 = reinterpret_cast<u32x4 *>(dst_lds);
+    const int step = (int)blockDim.x;
+    for (int i0 = (int)threadIdx.x; i0 < n4; i0 += 8 * step) {
+        u32x4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) v[k] = s4[min(i0 + k * step, n4 - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; k++)
+            if (i0 + k * step < n4) d4[i0 + k * step] = v[k];
+    }
+    for (int i = 4 * n4 + (int)threadIdx.x; i < n; i += step) dst_lds[i] = ((gp_u32)src)[i];
+}
+
 // Entry of a device-order code from the group/single table (see qmoe_internal.h):
 // codes below 4 * n_groups share table[code >> 2], the rest are single entries at
 // table[code - 3 * n_groups]; the index is the larger of the two expressions (the
@@ -608,9 +629,9 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     if (!a.work_counter && g_static >= g_static_end) return;
 
     if constexpr (DICT == kDictRunLds) {
-        for (int i = threadIdx.x; i < a.lds_dict_entries; i += blockDim.x) lds_run_w[i] = ((gp_u32)a.run)[i];
+        stage_words(lds_run_w, a.run, a.lds_dict_entries);
     } else if constexpr (DICT == kDictOrder) {
-        for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) lds_run_w[i] = ((gp_u32)a.order_table)[i];
+        stage_words(lds_run_w, a.order_table, a.n_order);
     }
 
     gp_u16 xg = (gp_u16)a.x;
@@ -1083,7 +1104,7 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     const int n_items = listed ? min(*a.n_items_dev, a.max_items) : (a.batch + kMmTokens - 1) / kMmTokens;
     const int total = (int)min((long long)n_items * a.mm_row_blocks, 0x7FFFFFFFLL);
     if (total <= 0 || (!listed && (int)blockIdx.x >= total)) return;
-    for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
+    stage_words(table_w, a.order_table, a.n_order);
 
     // Order of arrival of this wavefront on its SIMD (SIMD_ID: bits 5:4 of HW_ID): the
     // first and the second wavefront of a SIMD take opposite halves of the step.  (The
@@ -1263,7 +1284,7 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
     extern __shared__ __align__(16) unsigned char smem[];
     const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
     uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
-    for (int i = threadIdx.x; i < a.n_order; i += blockDim.x) table_w[i] = ((gp_u32)a.order_table)[i];
+    stage_words(table_w, a.order_table, a.n_order);
     __syncthreads();
     lp_u32 table = (lp_u32)table_w;
     const uint32_t wt = (uint32_t)(uintptr_t)(lw_u8)(smem + table_bytes);
