@@ -886,3 +886,43 @@ def test_layer_at_the_widest_hidden_size(gpu, ddict, oracle_dict, order, d_ff, o
         with pytest.raises(q.QmoeError) as ei:
             _run_layer(layer, ddict, x, idx, gpu)
         assert ei.value.status == -10
+
+
+def test_decode_matvec_in_a_hip_graph(gpu, ddict, oracle_dict):
+    """Both kernels of the single-matrix call (a few tokens; many tokens on the matrix cores) captured into
+    one HIP graph and replayed: neither needs anything that a capture forbids."""
+    rows, cols = 300, 520
+    tern = synth.ternary(601, rows, cols, 0.9)
+    scale = synth.uniform_f16(602, (rows,), 0.01, 0.1)
+    M = _upload(oracle_dict, tern, scale, gpu, ddict)
+    x_few, x_many = synth.normal_bf16(603, (3, cols)), synth.normal_bf16(604, (80, cols))
+    d_few, d_many = _to_dev16(x_few, gpu), _to_dev16(x_many, gpu)
+    y_few = torch.zeros((3, rows), dtype=torch.float32, device=gpu)
+    y_many = torch.zeros((80, rows), dtype=torch.float32, device=gpu)
+    q.qmoe_set_tuning("mfma_min_tokens", 64)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            q.qmoe_decode_matvec(ddict.handle, M.desc, d_few, y_few, stream=side.cuda_stream)
+            q.qmoe_decode_matvec(ddict.handle, M.desc, d_many, y_many, stream=side.cuda_stream)
+            torch.cuda.synchronize()
+            eager = (y_few.clone(), y_many.clone())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                q.qmoe_decode_matvec(ddict.handle, M.desc, d_few, y_few, stream=side.cuda_stream)
+                q.qmoe_decode_matvec(ddict.handle, M.desc, d_many, y_many, stream=side.cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            y_few.fill_(float("nan"))
+            y_many.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_few, eager[0]) and torch.equal(y_many, eager[1]), f"replay {rep}"
+            (y_many * 2).sum().item()
+    finally:
+        q.qmoe_set_tuning("mfma_min_tokens", 0)
+    for y, x in ((y_few, x_few), (y_many, x_many)):
+        y_ref, bound = oracle.matvec(tern, scale, x, with_bound=True)
+        _check_product(y.cpu().numpy(), y_ref, bound, f"batch {x.shape[0]}")
