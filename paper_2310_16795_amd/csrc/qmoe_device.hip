@@ -165,6 +165,60 @@ __device__ __forceinline__ void stage_words(uint32_t *dst_lds, const uint32_t *s
     for (int i = 4 * n4 + (int)threadIdx.x; i < n; i += step) dst_lds[i] = ((gp_u32)src)[i];
 }
 
+// ---- activations of a tile into LDS (whole workgroup).  The loads of eight columns (one
+// token) or of all the tile's tokens (tiles) are issued before the first store: a loop that
+// loads and stores one value at a time waits for every load in turn.
+//
+// One token: 8-byte records {0, +x, 0, -x} (with_neg) or {0, x, 0, 0}; columns cols ..
+// cols + kPadCols - 1, and everything when `live` is false, are zero records.
+__device__ __forceinline__ void stage_x_one(uint16_t *xs_w, const uint16_t *xrow, int cols, bool live, bool with_neg)
+{
+    const int n = cols + kPadCols, step = (int)blockDim.x;
+    gp_u16 x = (gp_u16)xrow;
+    for (int c0 = (int)threadIdx.x; c0 < n; c0 += 8 * step) {
+        uint32_t v[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) v[k] = x[min(c0 + k * step, cols - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int c = c0 + k * step;
+            if (c < n) {
+                const bool in = live && c < cols;
+                const uint32_t pos = in ? v[k] : 0u, neg = (in && with_neg) ? (v[k] ^ 0x8000u) : 0u;
+                reinterpret_cast<uint2 *>(xs_w)[c] = make_uint2(pos << 16, neg << 16);
+            }
+        }
+    }
+}
+
+// TBI tokens (2, 4, 8): bf16 [column][TBI]; token t of the tile is row x_rows[t] of x (tokens
+// from ntok on are zeros).  x_rows holds at least one valid row.
+template <int TBI, typename RowOf>
+__device__ __forceinline__ void stage_x_tile(uint16_t *xs_w, const uint16_t *xbase, RowOf row_of, int ntok, int ldx,
+                                             int cols)
+{
+    const int n = cols + kPadCols, step = (int)blockDim.x;
+    gp_u16 x = (gp_u16)xbase;
+    size_t off[TBI];
+#pragma unroll
+    for (int t = 0; t < TBI; t++) off[t] = (size_t)row_of(min(t, ntok - 1)) * (size_t)ldx;
+    for (int c = (int)threadIdx.x; c < n; c += step) {
+        const int cc = min(c, cols - 1);
+        uint32_t v[TBI];
+#pragma unroll
+        for (int t = 0; t < TBI; t++) v[t] = x[off[t] + cc];
+        uint32_t w[TBI / 2];
+#pragma unroll
+        for (int t = 0; t < TBI; t += 2) {
+            const uint32_t lo = (c < cols && t < ntok) ? v[t] : 0u, hi = (c < cols && t + 1 < ntok) ? v[t + 1] : 0u;
+            w[t / 2] = lo | (hi << 16);
+        }
+        uint32_t *dst = reinterpret_cast<uint32_t *>(xs_w) + (size_t)c * (TBI / 2);
+#pragma unroll
+        for (int i = 0; i < TBI / 2; i++) dst[i] = w[i];
+    }
+}
+
 // Entry of a device-order code from the group/single table (see qmoe_internal.h):
 // codes below 4 * n_groups share table[code >> 2], the rest are single entries at
 // table[code - 3 * n_groups]; the index is the larger of the two expressions (the
@@ -634,7 +688,6 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         stage_words(lds_run_w, a.order_table, a.n_order);
     }
 
-    gp_u16 xg = (gp_u16)a.x;
     int cur_pass = -1, ntok = 0, slot0 = 0, expert = 0, tbi = 1;
     for (;;) {
         __syncthreads();  // everyone is done with the previous item (activations, token ids, next_item)
@@ -676,22 +729,12 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
                 gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
             }
             __syncthreads();
-            if (tbi == 1) {
-                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
-                    uint32_t v = 0;
-                    if (c < a.cols && ntok > 0) v = xg[(size_t)x_rows[0] * a.ldx + c];
-                    // {0, +x, 0, -x}; past the last column and for a missing token all four are 0
-                    const uint32_t neg = (c < a.cols && ntok > 0) ? (v ^ 0x8000u) : 0u;
-                    reinterpret_cast<uint2 *>(xs_w)[c] = make_uint2(v << 16, neg << 16);
-                }
-            } else {
-                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
-                    for (int t = 0; t < tbi; t++) {
-                        uint16_t v = 0;
-                        if (c < a.cols && t < ntok) v = xg[(size_t)x_rows[t] * a.ldx + c];
-                        xs_w[(size_t)c * tbi + t] = v;
-                    }
-                }
+            auto row_of = [&](int t) { return x_rows[t]; };
+            switch (tbi) {
+            case 1: stage_x_one(xs_w, a.x + (size_t)x_rows[0] * a.ldx, a.cols, ntok > 0, true); break;
+            case 2: stage_x_tile<2>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            case 4: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            default: stage_x_tile<8>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             }
             __syncthreads();
             cur_pass = pass;
@@ -1184,7 +1227,6 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
     const int row_blocks = (a.rows + ngrp - 1) / ngrp;
     const int n_tiles = (a.batch + a.tb_max - 1) / a.tb_max;
     const long long total = (long long)n_tiles * row_blocks;
-    gp_u16 xg = (gp_u16)a.x;
     int cur_tile = -1, ntok = 0, slot0 = 0, tbi = 1;
     for (long long g = blockIdx.x; g < total; g += gridDim.x) {
         const int tile = (int)(g / row_blocks);
@@ -1194,19 +1236,12 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
             slot0 = tile * a.tb_max;
             ntok = min(a.tb_max, a.batch - slot0);
             tbi = ntok <= 1 ? 1 : (ntok <= 2 ? 2 : (ntok <= 4 ? 4 : 8));
-            if (tbi == 1) {
-                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x) {
-                    uint32_t v = 0;
-                    if (c < a.cols) v = xg[(size_t)slot0 * a.ldx + c];
-                    reinterpret_cast<uint2 *>(xs_w)[c] = make_uint2(v << 16, 0u);  // {0, x, 0, 0}: lds_load_x<1> reads the second slot
-                }
-            } else {
-                for (int c = threadIdx.x; c < a.cols + kPadCols; c += blockDim.x)
-                    for (int t = 0; t < tbi; t++) {
-                        uint16_t v = 0;
-                        if (c < a.cols && t < ntok) v = xg[(size_t)(slot0 + t) * a.ldx + c];
-                        xs_w[(size_t)c * tbi + t] = v;
-                    }
+            auto row_of = [&](int t) { return slot0 + t; };
+            switch (tbi) {
+            case 1: stage_x_one(xs_w, a.x + (size_t)slot0 * a.ldx, a.cols, true, false); break;  // lds_load_x<1> reads the +x slot
+            case 2: stage_x_tile<2>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            case 4: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            default: stage_x_tile<8>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             }
             __syncthreads();
             cur_tile = tile;
