@@ -311,9 +311,9 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * calls on one device must not be issued concurrently from several host threads.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
  * n_tokens > 2^20, d_model or d_ff > 32768, or too wide for the LDS: a token's activations
- * take 8 bytes per column and, with the device numbering, share the LDS with the whole table
- * -- with 160 KB and the 2^16-entry table of the paper that is 10022 columns, about 20400 with
- * the interchange numbering; code_order 1 without a device order), HIP.
+ * take 8 bytes per column, about 20400 columns with 160 KB (with the device numbering the
+ * table shares the LDS with them up to 10022 columns and is read from L2, at about half the
+ * speed, beyond that); code_order 1 without a device order), HIP.
  */
 qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*device*/,
                                    const qmoe_matrix *wo /*device*/, int code_order, int n_experts,
@@ -358,7 +358,8 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
  * "phases" (bit mask of the layer's kernels to enqueue: 1 dispatch, 2 / 4 scalar kernel of
  * the first / second product, 8 / 16 matrix-core kernel of the first / second product --
  * lets a benchmark time one kernel on a workspace a full call has filled).  value 0
- * restores the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2.
+ * restores the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2 (either numbering), a
+ * positive value forces it into LDS.
  * Unknown key: INVALID_ARG.
  */
 qmoe_status qmoe_set_tuning(const char *key, int value);

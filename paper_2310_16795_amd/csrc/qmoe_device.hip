@@ -265,7 +265,9 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     return s;
 }
 
-enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2, kDictOrder = 3 };
+// where a codeword's entry comes from: run-entry table in L2 | its head in LDS, the rest in L2 |
+// interchange words in L2 | device-order table in LDS | device-order table in L2
+enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2, kDictOrder = 3, kDictOrderL2 = 4 };
 
 struct Entry {
     uint32_t e0, e1;  // run entry (e0), or the two interchange words (e0, e1)
@@ -287,6 +289,8 @@ __device__ __forceinline__ Entry lookup_entry(const ProductArgs &a, uint32_t cod
         e.e0 = in_lds ? from_lds : from_l2;
     } else if constexpr (DICT == kDictOrder) {
         e.e0 = order_entry(lds_run, code, (uint32_t)a.n_groups, (uint32_t)a.n_order);  // whole table in LDS
+    } else if constexpr (DICT == kDictOrderL2) {
+        e.e0 = order_entry((gp_u32)a.order_table, code, (uint32_t)a.n_groups, (uint32_t)a.n_order);
     } else {
         const unsigned long long w = ((gp_u64)a.words)[code];
         e.e0 = (uint32_t)w; e.e1 = (uint32_t)(w >> 32);
@@ -1962,6 +1966,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct ProductPlan {
     int threads, rows_per_item, blocks_per_pass, tb_max, lds_dict_entries, grid;
     int stage_out;  // results of a block staged in LDS (first product of a layer, LDS permitting)
+    int order_l2;   // device-order streams: the table is read from L2 instead of being staged in LDS
     size_t smem;
 };
 
@@ -1990,10 +1995,22 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     // tiles of eight tokens cost more per token than two tiles of four (16-byte LDS gathers,
     // register pressure), so four is the default
     int tb = 4;
+    // Device-order streams: the whole table goes to LDS and the tile takes what is left; only a
+    // call whose activations leave no room for the table reads it from L2 (measured: that is
+    // slower even for the smallest workload, where one 65 KB copy per workgroup looked like
+    // the price to avoid: 0.126 against 0.102 ms).
+    p->order_l2 = 0;
     if (n_order > 0) {
-        // device-order streams: the whole table goes to LDS, the tile takes what is left
-        if (xs_bytes(1) + fixed + 4 * (size_t)n_order + 16384 > max_lds) return QMOE_E_LIMIT;
+        const bool fits = xs_bytes(1) + fixed + 4 * (size_t)n_order + 16384 <= max_lds;
+        if (tu.lds_dict_entries < 0 || !fits) {
+            p->order_l2 = 1;
+            n_order = 0;
+        }
+    }
+    if (n_order > 0) {
         while (tb > 4 && xs_bytes(tb) + fixed + 4 * (size_t)n_order + 16384 > max_lds) tb >>= 1;
+    } else if (p->order_l2) {
+        while (tb > 4 && xs_bytes(tb) + fixed > max_lds / 2) tb >>= 1;
     } else if (lds_table) {
         while (tb > 4 && xs_bytes(tb) > 36 * 1024) tb >>= 1;
     } else {
@@ -2140,6 +2157,8 @@ qmoe_status launch_product_as(const ProductArgs &a, const ProductPlan &p, hipStr
 
 qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s)
 {
+    if (a.code_order && p.order_l2)
+        return a.epilogue ? launch_product_as<kDictOrderL2, 1>(a, p, s) : launch_product_as<kDictOrderL2, 0>(a, p, s);
     if (a.code_order)
         return a.epilogue ? launch_product_as<kDictOrder, 1>(a, p, s) : launch_product_as<kDictOrder, 0>(a, p, s);
     if (!run) return a.epilogue ? launch_product_as<kDictWords, 1>(a, p, s) : launch_product_as<kDictWords, 0>(a, p, s);

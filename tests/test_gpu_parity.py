@@ -872,10 +872,11 @@ def test_decode_matvec_at_the_widest_row(gpu, ddict, oracle_dict, order):
     assert ei.value.status == -10
 
 
-@pytest.mark.parametrize("order,d_ff,ok", [(1, 10016, True), (1, 10080, False), (0, 20400, True), (0, 20480, False)])
+@pytest.mark.parametrize("order,d_ff,ok", [(1, 10016, True), (1, 10080, True), (1, 20400, True), (1, 20480, False),
+                                           (0, 20400, True), (0, 20480, False)])
 def test_layer_at_the_widest_hidden_size(gpu, ddict, oracle_dict, order, d_ff, ok):
     """The second product stages d_ff activations per token; with the device numbering the whole table
-    shares the LDS with them."""
+    shares the LDS with them up to 10022 columns, beyond that it is read from L2."""
     w = synth.WORKLOADS["switch_base128"].scaled(n_experts=3, d_model=64, d_ff=d_ff, n_tokens=7)
     idx, x = w.expert_idx(), w.tokens()
     layer = _build_layer(w, oracle_dict, gpu, order_of=ddict if order else None)
