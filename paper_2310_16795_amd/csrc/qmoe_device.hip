@@ -1550,7 +1550,13 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
     const int E = a.n_experts, T = a.n_tokens;
     const int tid = threadIdx.x, nthr = blockDim.x;
 
+    // Tokens without an expert get a zero output row.  They are collected in a list (the two
+    // arrays the scatter uses later) and their rows are cleared by whole wavefronts; a thread
+    // clears a row alone only when the list is full.
+    int *bad_list = tmp + 256, *n_bad = tmp + 255;
+    const int bad_cap = 2 * nthr;
     for (int e = tid; e < E; e += nthr) cnt[e] = 0;
+    if (tid == 0) *n_bad = 0;
     __syncthreads();
     int dropped = 0;
     for (int t = tid; t < T; t += nthr) {
@@ -1559,11 +1565,25 @@ __global__ __launch_bounds__(1024) void k_dispatch(const DispatchArgs a)
             atomicAdd(&cnt[e], 1);
         } else {
             dropped++;
-            if (a.y)
-                for (int c = 0; c < a.d_model; c++) a.y[(size_t)t * a.d_model + c] = 0.0f;
+            if (a.y) {
+                const int slot = atomicAdd(n_bad, 1);
+                if (slot < bad_cap) {
+                    bad_list[slot] = t;
+                } else {
+                    for (int c = 0; c < a.d_model; c++) a.y[(size_t)t * a.d_model + c] = 0.0f;
+                }
+            }
         }
     }
     __syncthreads();
+    if (a.y) {
+        const int nb = min(*n_bad, bad_cap);
+        for (int i = tid >> 6; i < nb; i += nthr >> 6) {
+            float *row = a.y + (size_t)bad_list[i] * a.d_model;
+            for (int c = tid & 63; c < a.d_model; c += 64) row[c] = 0.0f;
+        }
+        __syncthreads();  // the list's memory is used again below
+    }
 
     // each thread owns a contiguous chunk of experts
     const int chunk = (E + nthr - 1) / nthr;

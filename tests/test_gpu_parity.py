@@ -472,6 +472,23 @@ def test_layer_with_every_token_dropped(gpu, ddict, oracle_dict):
     assert wsout["counters"][3] == 0 and wsout["counters"][4] == 0 and wsout["counters"][7] == 0
 
 
+def test_layer_with_thousands_of_dropped_tokens(gpu, ddict, oracle_dict):
+    """More dropped tokens than the dispatch kernel's list of them holds (2048): the rest are cleared one
+    row per thread; the kept tokens, scattered among them, still come out right."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=4, d_model=72, d_ff=96, n_tokens=5000)
+    x = w.tokens()
+    idx = np.full(5000, -1, dtype=np.int32)
+    keep = np.random.default_rng(31).choice(5000, size=40, replace=False)
+    idx[keep] = np.random.default_rng(32).integers(0, 4, size=40).astype(np.int32)
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    y, wsout = _run_layer(layer, ddict, x, idx, gpu)
+    assert wsout["counters"][0] == 40 and wsout["counters"][1] == 4960
+    dropped = np.ones(5000, dtype=bool)
+    dropped[keep] = False
+    assert not y[dropped].any()
+    _check_layer(w, idx, x, y, wsout, sorted(int(t) for t in keep))
+
+
 def test_dispatch_many_tokens(gpu):
     """100 000 tokens on 2048 experts, Zipf-like crowding: the single-workgroup dispatch at scale."""
     rng = np.random.default_rng(9)
