@@ -684,7 +684,7 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
     const int per = (total + (int)gridDim.x - 1) / (int)gridDim.x;
     int g_static = per * (int)blockIdx.x;
     const int g_static_end = min(total, g_static + per);
-    if (!a.work_counter && g_static >= g_static_end) return;
+    if (total <= 0 || (!a.work_counter && g_static >= g_static_end)) return;
 
     if constexpr (DICT == kDictRunLds) {
         stage_words(lds_run_w, a.run, a.lds_dict_entries);
