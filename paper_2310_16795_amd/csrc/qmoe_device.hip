@@ -234,6 +234,34 @@ __device__ __forceinline__ uint32_t order_entry(TablePtr table, uint32_t code, u
     return table[min(u, n_order - 1u)] ^ flips;
 }
 
+// The same look-up for the two codewords held in one 32-bit word of the stream.  The
+// flip masks of both come out of one packed 16-bit multiply (per half: bit 0 -> bit 2,
+// bit 1 -> bit 10, which are bits 18 and 26 of an entry once the half sits on top), and
+// the index is the median of the two candidates and the last entry: the larger of the
+// two for every code the table knows; for a code it does not know, the last entry or the
+// smaller candidate (at most code >> 2 < 16384, inside the space reserved for the table in
+// the device blob; in LDS, at worst other bytes of the workgroup's own allocation).
+template <typename TablePtr>
+__device__ __forceinline__ void order_entry2(TablePtr table, uint32_t w, uint32_t n_groups3, uint32_t last,
+                                             uint32_t &e_lo, uint32_t &e_hi)
+{
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const uint32_t two = w & 0x00030003u;
+    u16x2 t, k = {0x0204, 0x0204};
+    __builtin_memcpy(&t, &two, 4);
+    t = t * k;
+    uint32_t f;
+    __builtin_memcpy(&f, &t, 4);
+    const uint32_t c_lo = w & 0xFFFFu, c_hi = w >> 16;
+    const uint32_t s_lo = __builtin_elementwise_sub_sat(c_lo, n_groups3);
+    const uint32_t s_hi = __builtin_elementwise_sub_sat(c_hi, n_groups3);
+    uint32_t i_lo, i_hi;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(i_lo) : "v"(c_lo >> 2), "v"(s_lo), "s"(last));
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(i_hi) : "v"(c_hi >> 2), "v"(s_hi), "s"(last));
+    e_lo = table[i_lo] ^ ((f << 16) & 0x04040000u);
+    e_hi = table[i_hi] ^ (f & 0x04040000u);
+}
+
 // Decode one step (one codeword per lane) and return this lane's run:
 // `len` values starting at column `start` (absolute, clamped to cols).
 struct Step {
@@ -387,6 +415,7 @@ struct LaneState {
     float acc[TBI * (1 + ASYM)];  // running sums since the last row that was written (ASYM: see accumulate)
     uint32_t pos8;     // 8 * (column reached in the current row)
     int row, rb;       // current row, end of this lane's rows
+    uint32_t sraw;     // one-token tiles: the current row's scale (or grid pair) as stored, read when the row began
 };
 
 // What a lane needs to write a finished row; everything it reads sits in LDS, so
@@ -400,7 +429,16 @@ struct RowSink {
     int ntok, slot0;
     uint32_t out_s;   // LDS byte address of the block's staged results [tile][out_rows] (bf16 or fp32), 0 = none
     int out_rows;     // rows of the block
+    float gate0;      // gate of tile slot 0
 };
+
+// the scale (binary16) or grid pair (two bf16) of the block's row i, as stored
+template <int ASYM>
+__device__ __forceinline__ uint32_t row_scale_raw(const RowSink &rs, int i)
+{
+    if constexpr (ASYM) return ((lp_u32)rs.scale_s)[i];
+    else return (uint32_t)rs.scale_s[i];
+}
 
 template <int TBI, int EPI, int ASYM = 0>
 __device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<TBI, ASYM> &st,
@@ -460,6 +498,30 @@ __device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI, AS
             for (int t = 0; t < TBI * (1 + ASYM); t++) st.acc[t] = 0.0f;
             st.pos8 -= cols8;
             st.row += 1;
+            if constexpr (TBI == 1) st.sraw = row_scale_raw<ASYM>(rs, min(st.row, st.rb) - rs.r0);
+        }
+    }
+}
+
+// One token, the block's results staged in LDS: write the lane's current row from the sums
+// `snap`.  The row's scale was read when the row began, so nothing here waits on a read.
+template <int EPI, int ASYM>
+__device__ __forceinline__ void stage_row_one(const LaneState<1, ASYM> &st, const float (&snap)[1 + ASYM], const RowSink &rs)
+{
+    {
+        float v;
+        if constexpr (ASYM) {
+            const float w_min = __uint_as_float(st.sraw << 16), w_max = __uint_as_float(st.sraw & 0xFFFF0000u);
+            v = fmaf(snap[1], 0.5f * (w_max + w_min), snap[0] * (0.5f * (w_max - w_min)));
+        } else {
+            v = snap[0] * half_bits_to_float((uint16_t)st.sraw);
+        }
+        const uint32_t i = (uint32_t)(st.row - rs.r0);
+        if constexpr (EPI == 0) {
+            *(__attribute__((address_space(3))) float *)(uintptr_t)(rs.out_s + 4u * i) = rs.gate0 * v;
+        } else {
+            *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)(rs.out_s + 2u * i) =
+                float_to_bf16_bits(v > 0.0f ? v : 0.0f);
         }
     }
 }
@@ -476,25 +538,24 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
                                          uint32_t cols8, uint32_t xs_addr, const RowSink &rs)
 {
     constexpr int NA = TBI * (1 + ASYM);
-    // One token: positions are kept as LDS addresses of the column's record (the base is
-    // added once for the eight entries, not once per entry); tiles: 8 * column.
-    const uint32_t base = TBI == 1 ? xs_addr : 0u;
-    const uint32_t lim = cols8 + base;
-    uint32_t pos[8];
-    bool wrap[8];
-    uint32_t p = st.pos8 + base;
+    // Where each of the eight runs begins, as 8 * column.  Past the row's end the position
+    // falls back by the row's width: p - cols8 wraps around to a huge number for every p
+    // below cols8, so the smaller of the two is the position either way.  Eight runs span
+    // at most 8 * 28 columns <= cols, so the position after the eight is at or below the one
+    // before them exactly when a row ended among them, and a run ended its row exactly when
+    // the next one begins before it.
+    uint32_t pos[9];
+    uint32_t p = st.pos8;
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         pos[j] = p;
         p += e[j].e0 & 0xFFu;
-        wrap[j] = p >= lim;
-        p = wrap[j] ? p - cols8 : p;
+        p = min(p, p - cols8);
     }
-    st.pos8 = p - base;
-    float snap[NA];
-    bool wrapped = false;
-#pragma unroll
-    for (int t = 0; t < NA; t++) snap[t] = 0.0f;
+    pos[8] = p;
+    const bool wrapped = p <= st.pos8;
+    st.pos8 = p;
+    float part[8][NA];  // the sums after each of the eight
     if constexpr (TBI == 1) {
         // the three bf16 values of a codeword are added with two packed dot products
         // against (1, 1): two of them share a register, no widening shifts
@@ -502,7 +563,7 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
         uint32_t xa[ASYM ? 24 : 1];  // asymmetric grid: the same inputs with their own sign (+x of each record)
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const uint32_t rec = pos[j];
+            const uint32_t rec = pos[j];  // the activations begin at LDS address 0 (the caller checks)
 #pragma unroll
             for (int z = 0; z < 3; z++) {
                 const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
@@ -523,7 +584,7 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
             __builtin_memcpy(&p1, &x[3 * j + 2], 4);
             st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, st.acc[0], false);
             st.acc[0] = __builtin_amdgcn_fdot2_f32_bf16(p1, ones, st.acc[0], false);
-            snap[0] = wrap[j] ? st.acc[0] : snap[0];
+            part[j][0] = st.acc[0];
             if constexpr (ASYM) {
                 const uint32_t pair_a = xa[3 * j] | (xa[3 * j + 1] << 16);
                 bf16x2 a2, a1;
@@ -531,25 +592,41 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
                 __builtin_memcpy(&a1, &xa[3 * j + 2], 4);
                 st.acc[NA - 1] = __builtin_amdgcn_fdot2_f32_bf16(a2, ones, st.acc[NA - 1], false);
                 st.acc[NA - 1] = __builtin_amdgcn_fdot2_f32_bf16(a1, ones, st.acc[NA - 1], false);
-                snap[NA - 1] = wrap[j] ? st.acc[NA - 1] : snap[NA - 1];
+                part[j][NA - 1] = st.acc[NA - 1];
             }
-            wrapped = wrapped || wrap[j];
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             accumulate<TBI, DICT, ASYM>(e[j], xs_addr, pos[j], st.acc);
 #pragma unroll
-            for (int t = 0; t < NA; t++) snap[t] = wrap[j] ? st.acc[t] : snap[t];
-            wrapped = wrapped || wrap[j];
+            for (int t = 0; t < NA; t++) part[j][t] = st.acc[t];
         }
     }
     if (__any(wrapped)) {
         if (wrapped) {
-            if (st.row < st.rb) write_row<TBI, EPI, ASYM>(a, st, snap, rs);
+            float snap[NA];
+#pragma unroll
+            for (int t = 0; t < NA; t++) snap[t] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const bool ended = pos[j + 1] < pos[j];
+#pragma unroll
+                for (int t = 0; t < NA; t++) snap[t] = ended ? part[j][t] : snap[t];
+            }
 #pragma unroll
             for (int t = 0; t < NA; t++) st.acc[t] -= snap[t];
+            if (st.row < st.rb) {
+                if constexpr (TBI == 1) {
+                    if (rs.out_s) stage_row_one<EPI, ASYM>(st, snap, rs);
+                    else write_row<TBI, EPI, ASYM>(a, st, snap, rs);
+                } else {
+                    write_row<TBI, EPI, ASYM>(a, st, snap, rs);
+                }
+            }
             st.row += 1;
+            // the next row's scale is asked for now and not needed before that row ends
+            if constexpr (TBI == 1) st.sraw = row_scale_raw<ASYM>(rs, min(st.row, st.rb) - rs.r0);
         }
     }
 }
@@ -558,10 +635,20 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
 template <int DICT>
 __device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp_u32 lds_run, Entry (&e)[8])
 {
+    if constexpr (DICT == kDictOrder || DICT == kDictOrderL2) {
+        const uint32_t n_groups3 = 3u * (uint32_t)a.n_groups, last = (uint32_t)a.n_order - 1u;
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-        e[2 * j] = lookup_entry<DICT>(a, v[j] & 0xFFFFu, lds_run);
-        e[2 * j + 1] = lookup_entry<DICT>(a, v[j] >> 16, lds_run);
+        for (int j = 0; j < 4; j++) {
+            e[2 * j].e1 = 0u; e[2 * j + 1].e1 = 0u;
+            if constexpr (DICT == kDictOrder) order_entry2(lds_run, v[j], n_groups3, last, e[2 * j].e0, e[2 * j + 1].e0);
+            else order_entry2((gp_u32)a.order_table, v[j], n_groups3, last, e[2 * j].e0, e[2 * j + 1].e0);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            e[2 * j] = lookup_entry<DICT>(a, v[j] & 0xFFFFu, lds_run);
+            e[2 * j + 1] = lookup_entry<DICT>(a, v[j] >> 16, lds_run);
+        }
     }
 }
 
@@ -609,11 +696,13 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     st.pos8 = 0;
     st.row = ra;
     st.rb = rb;
+    st.sraw = 0u;
+    if constexpr (TBI == 1) st.sraw = row_scale_raw<ASYM>(rs, min(ra, rb) - rs.r0);
 
     // Piece p + 2 is being loaded and the entries of piece p + 1 looked up while piece p
     // is applied.
     const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(my_pieces - 1, 0);
-    const bool fast = DICT != kDictWords && a.cols >= 224;
+    const bool fast = DICT != kDictWords && a.cols >= 224 && (TBI != 1 || xs_addr == 0u);
     auto load_piece = [&](int p) -> u32x4 {
         // lanes past their own end re-read their last piece (its slots are masked out below)
         const uintptr_t at = chunk + 16u * (uintptr_t)p;
@@ -769,6 +858,7 @@ __global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
         const bool staged = a.stage_out && (r0 % 8) == 0;
         rs.out_s = staged ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)out_w : 0u;
         rs.out_rows = (r1 - r0 + 7) & ~7;
+        rs.gate0 = gate_s[0];
         switch (tbi) {
         case 1: product_block<1, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
         case 2: product_block<2, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
