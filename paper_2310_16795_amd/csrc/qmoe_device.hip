@@ -526,7 +526,7 @@ __device__ __forceinline__ void stage_row_one(const LaneState<1, ASYM> &st, cons
     }
 }
 
-// Fast form for run tables and rows of at least 224 values (at most one row end per
+// Fast form for run tables and rows of more than 224 values (at most one row end per
 // eight codewords): the eight entries are applied without a branch in between, so
 // their LDS gathers overlap; the running sum is never reset inside, a row end only
 // records the sum reached (`snap`), and the row is written once after the eight.
@@ -541,9 +541,10 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
     // Where each of the eight runs begins, as 8 * column.  Past the row's end the position
     // falls back by the row's width: p - cols8 wraps around to a huge number for every p
     // below cols8, so the smaller of the two is the position either way.  Eight runs span
-    // at most 8 * 28 columns <= cols, so the position after the eight is at or below the one
+    // at most 8 * 28 columns < cols, so the position after the eight is below the one
     // before them exactly when a row ended among them, and a run ended its row exactly when
-    // the next one begins before it.
+    // the next one begins before it.  (Empty entries, which stand for slots that are not
+    // the lane's, move nothing.)
     uint32_t pos[9];
     uint32_t p = st.pos8;
 #pragma unroll
@@ -553,7 +554,7 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
         p = min(p, p - cols8);
     }
     pos[8] = p;
-    const bool wrapped = p <= st.pos8;
+    const bool wrapped = p < st.pos8;
     st.pos8 = p;
     float part[8][NA];  // the sums after each of the eight
     if constexpr (TBI == 1) {
@@ -702,16 +703,25 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     // Piece p + 2 is being loaded and the entries of piece p + 1 looked up while piece p
     // is applied.
     const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(my_pieces - 1, 0);
-    const bool fast = DICT != kDictWords && a.cols >= 224 && (TBI != 1 || xs_addr == 0u);
+    const bool fast = DICT != kDictWords && a.cols > 224 && (TBI != 1 || xs_addr == 0u);
     auto load_piece = [&](int p) -> u32x4 {
         // lanes past their own end re-read their last piece (its slots are masked out below)
         const uintptr_t at = chunk + 16u * (uintptr_t)p;
         return *(gp_u32x4)(at < last_piece ? at : last_piece);
     };
-    auto apply = [&](const Entry (&e)[8], int r) {
+    auto apply = [&](Entry (&e)[8], int r) {
         // r: stream index (relative to K0) of the piece's first slot
         const bool whole = r >= 0 && (uint32_t)r + 8u <= n;  // all eight are this lane's codewords
-        if (fast && __all(whole)) {
+        if (fast) {
+            // Slots that are not this lane's codewords (before its first, after its last, and
+            // everything once the lane is done while others in the wavefront are not) become
+            // empty entries: no columns, no non-zeros.  The wavefront stays on the branch-free
+            // form from its first piece to its last.
+            if (!__all(whole)) {
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    if ((uint32_t)(r + j) >= n) e[j].e0 = 0u;
+            }
             consume8<TBI, DICT, EPI, ASYM>(a, st, e, cols8, xs_addr, rs);
         } else {
 #pragma unroll
