@@ -245,9 +245,11 @@ def _check_layer(w, idx, x_bits, y_gpu, wsout, tokens, gate=None, asym=False):
     assert flips <= max(2, total * 2e-3), f"{flips} of {total} hidden values rounded differently"
 
 
-@pytest.mark.parametrize("d_model,d_ff,order", [(96, 200, 0), (96, 200, 1), (260, 300, 1), (450, 228, 0)])
+@pytest.mark.parametrize("d_model,d_ff,order",
+                         [(96, 200, 0), (96, 200, 1), (260, 300, 1), (450, 228, 0), (224, 226, 1), (226, 224, 1)])
 def test_small_layer_every_token(gpu, ddict, oracle_dict, d_model, d_ff, order):
-    """Widths on both sides of 224 (the row length from which eight codewords hold at most one row end)."""
+    """Widths on both sides of 224 (rows longer than that hold at most one row end in eight codewords and take
+    the branch-free form; 224 itself is the widest row of the general form, 226 the narrowest of the other)."""
     w = synth.WORKLOADS["switch_base128"].scaled(n_experts=12, d_model=d_model, d_ff=d_ff, n_tokens=70)
     idx, x = w.expert_idx(), w.tokens()
     idx[5:40] = 3      # one expert with many tokens (several tiles)
