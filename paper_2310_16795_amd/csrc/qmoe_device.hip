@@ -295,6 +295,8 @@ __device__ __forceinline__ Step decode_step(const ProductArgs &a, const uint16_t
     return s;
 }
 
+constexpr int kProductMaxThreads = 768;  // largest workgroup of k_product
+
 // where a codeword's entry comes from: run-entry table in L2 | its head in LDS, the rest in L2 |
 // interchange words in L2 | device-order table in LDS | device-order table in L2
 enum DictMode { kDictRun = 0, kDictRunLds = 1, kDictWords = 2, kDictOrder = 3, kDictOrderL2 = 4 };
@@ -754,8 +756,10 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
 // LDS: activations | token ids | leading run entries.  Activations are bf16, for one
 // token as 8-byte records {0, +x, 0, -x} per column, for 2/4/8 tokens packed per column.
 // ASYM: rows on the grid {w_min, 0, w_max} (bf16 pair per row) instead of {-s, 0, +s}.
+// At most kProductMaxThreads lanes per workgroup: three wavefronts per SIMD, which leaves
+// each of them 168 vector registers (a bound of 1024 would cap them at 128).
 template <int DICT, int EPI, int ASYM>
-__global__ __launch_bounds__(1024) void k_product(const ProductArgs a)
+__global__ __launch_bounds__(kProductMaxThreads) void k_product(const ProductArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *xs_w = reinterpret_cast<uint16_t *>(smem);
@@ -2175,7 +2179,7 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
         }
     }
     if (tu.threads > 0) {
-        best_t = std::max(64, std::min(1024, tu.threads / 64 * 64));
+        best_t = std::max(64, std::min(kProductMaxThreads, tu.threads / 64 * 64));
         const int rpl = tu.rows_per_item > 0 ? tu.rows_per_item : want_rpl;
         best_b = std::max(1, (int)((rows + (long long)best_t * rpl - 1) / ((long long)best_t * rpl)));
     }
