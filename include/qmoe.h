@@ -348,7 +348,8 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
 
 /*
  * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
- * "threads" (workgroup size), "rows_per_item", "token_tile", "lds_dict_entries",
+ * "threads" (workgroup size of the scalar product kernel, a multiple of 64 up to 768),
+ * "rows_per_item", "token_tile", "lds_dict_entries",
  * "grid_per_cu", "blocks_first" / "blocks_second" (workgroups that share one pass over a
  * matrix in the first or only / the second product), "mfma_min_tokens" (experts -- or, in
  * qmoe_decode_matvec, batches -- with at least this many tokens use the matrix-core kernel; -1 = never), "overlap" (-1 = no side

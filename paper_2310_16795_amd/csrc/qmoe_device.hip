@@ -512,21 +512,19 @@ __device__ __forceinline__ void consume1(const ProductArgs &a, LaneState<TBI, AS
 template <int EPI, int ASYM>
 __device__ __forceinline__ void stage_row_one(const LaneState<1, ASYM> &st, const float (&snap)[1 + ASYM], const RowSink &rs)
 {
-    {
-        float v;
-        if constexpr (ASYM) {
-            const float w_min = __uint_as_float(st.sraw << 16), w_max = __uint_as_float(st.sraw & 0xFFFF0000u);
-            v = fmaf(snap[1], 0.5f * (w_max + w_min), snap[0] * (0.5f * (w_max - w_min)));
-        } else {
-            v = snap[0] * half_bits_to_float((uint16_t)st.sraw);
-        }
-        const uint32_t i = (uint32_t)(st.row - rs.r0);
-        if constexpr (EPI == 0) {
-            *(__attribute__((address_space(3))) float *)(uintptr_t)(rs.out_s + 4u * i) = rs.gate0 * v;
-        } else {
-            *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)(rs.out_s + 2u * i) =
-                float_to_bf16_bits(v > 0.0f ? v : 0.0f);
-        }
+    float v;
+    if constexpr (ASYM) {
+        const float w_min = __uint_as_float(st.sraw << 16), w_max = __uint_as_float(st.sraw & 0xFFFF0000u);
+        v = fmaf(snap[1], 0.5f * (w_max + w_min), snap[0] * (0.5f * (w_max - w_min)));
+    } else {
+        v = snap[0] * half_bits_to_float((uint16_t)st.sraw);
+    }
+    const uint32_t i = (uint32_t)(st.row - rs.r0);
+    if constexpr (EPI == 0) {
+        *(__attribute__((address_space(3))) float *)(uintptr_t)(rs.out_s + 4u * i) = rs.gate0 * v;
+    } else {
+        *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)(rs.out_s + 2u * i) =
+            float_to_bf16_bits(v > 0.0f ? v : 0.0f);
     }
 }
 
