@@ -1173,11 +1173,17 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         // are fetched right after the window's wait, so that a whole step hides the latency
         // of both loads (the empty asm keeps the compiler from moving the load up, in front
         // of that wait)
+        // The arbiter serves the older wavefront of a SIMD first, so the older four finish a
+        // step's decoding early and wait at the step's barrier (a quarter of their time) for
+        // the younger four; the younger ones decode at a raised priority (2-3 %, measured;
+        // raising it for all eight helps the second product only, alternating it hurts).
+        if (wave >= kMmThreads / 128) __builtin_amdgcn_s_setprio(1);
         QMOE_RING_DECODE_STEP(c, {
             int k_next = kend;
             asm volatile("" : "+s"(k_next));
             xr = load_x(k_next);
         }, ASYM ? 0 : 5);
+        __builtin_amdgcn_s_setprio(0);
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
