@@ -735,27 +735,59 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
         }
     };
     Entry ea[8], eb[8];
-    u32x4 cb = load_piece(1);
-    lookup8<DICT>(a, load_piece(0), lds_run, ea);
     // Issue priorities that take turns: of the three wavefronts that share a SIMD (workgroups
-    // of 768 lanes), one runs the first piece of a loop round at high priority and the second
+    // of 768 lanes), one runs the first piece of a pair at high priority and the second
     // at low, one the other way round, one stays in the middle.  The wavefronts of a SIMD then
     // sit in different stretches of the loop (vector arithmetic only / throttled by the LDS
     // queue) more of the time: 2 % on the c2048 layer, measured; fixed priorities, or three
     // that rotate, gain nothing.
     const int turn = ((int)threadIdx.x >> 8) % 3;
     if (turn == 2) __builtin_amdgcn_s_setprio(1);
-    for (int p = 0; p < npieces; p += 2) {
+    // Four pieces (64 bytes of a lane's stream) are asked for together and stay in flight for
+    // a whole loop round, so that a 128-byte line is visited twice or three times instead of
+    // eight times, a round apart each time (the lanes of a workgroup keep more lines in use
+    // than the first-level cache holds, so every visit is a request to L2).
+    // (One-token tiles only: with the registers of a token tile on top, the pieces in flight
+    // would spill.)
+    if constexpr (TBI != 1) {
+        u32x4 cb = load_piece(1);
+        lookup8<DICT>(a, load_piece(0), lds_run, ea);
+        for (int p = 0; p < npieces; p += 2) {
+            if (turn == 0) __builtin_amdgcn_s_setprio(2);
+            else if (turn == 1) __builtin_amdgcn_s_setprio(0);
+            const u32x4 cc = load_piece(p + 2);
+            lookup8<DICT>(a, cb, lds_run, eb);
+            apply(ea, rel + 8 * p);
+            if (turn == 0) __builtin_amdgcn_s_setprio(0);
+            else if (turn == 1) __builtin_amdgcn_s_setprio(2);
+            cb = load_piece(p + 3);
+            lookup8<DICT>(a, cc, lds_run, ea);
+            apply(eb, rel + 8 * p + 8);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        return;
+    }
+    u32x4 q0 = load_piece(0), q1 = load_piece(1), q2 = load_piece(2), q3 = load_piece(3);
+    lookup8<DICT>(a, q0, lds_run, ea);
+    for (int p = 0; p < npieces; p += 4) {
+        const u32x4 n0 = load_piece(p + 4), n1 = load_piece(p + 5), n2 = load_piece(p + 6), n3 = load_piece(p + 7);
         if (turn == 0) __builtin_amdgcn_s_setprio(2);
         else if (turn == 1) __builtin_amdgcn_s_setprio(0);
-        const u32x4 cc = load_piece(p + 2);
-        lookup8<DICT>(a, cb, lds_run, eb);
+        lookup8<DICT>(a, q1, lds_run, eb);
         apply(ea, rel + 8 * p);
         if (turn == 0) __builtin_amdgcn_s_setprio(0);
         else if (turn == 1) __builtin_amdgcn_s_setprio(2);
-        cb = load_piece(p + 3);
-        lookup8<DICT>(a, cc, lds_run, ea);
+        lookup8<DICT>(a, q2, lds_run, ea);
         apply(eb, rel + 8 * p + 8);
+        if (turn == 0) __builtin_amdgcn_s_setprio(2);
+        else if (turn == 1) __builtin_amdgcn_s_setprio(0);
+        lookup8<DICT>(a, q3, lds_run, eb);
+        apply(ea, rel + 8 * p + 16);
+        if (turn == 0) __builtin_amdgcn_s_setprio(0);
+        else if (turn == 1) __builtin_amdgcn_s_setprio(2);
+        lookup8<DICT>(a, n0, lds_run, ea);
+        apply(eb, rel + 8 * p + 24);
+        q1 = n1; q2 = n2; q3 = n3;
     }
     __builtin_amdgcn_s_setprio(0);
 }
