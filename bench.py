@@ -170,10 +170,10 @@ def time_phases(fn, steps):
     for s in range(steps):
         ev[s][0].record()
         for i, (_, mask) in enumerate(PHASES):
-            q.qmoe_set_tuning("phases", mask)
+            q.qmoe_hook_set("phases", mask)
             fn()
             ev[s][i + 1].record()
-    q.qmoe_set_tuning("phases", 0)
+    q.qmoe_hook_set("phases", 0)
     torch.cuda.synchronize()
     return {name: float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)]))
             for i, (name, _) in enumerate(PHASES)}

@@ -349,17 +349,13 @@ qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense /*device [n_
 /*
  * Launch tuning (process-wide, not thread-safe against running calls).  Keys:
  * "threads" (workgroup size of the scalar product kernel, a multiple of 64 up to 768),
- * "rows_per_item", "token_tile", "lds_dict_entries",
- * "grid_per_cu", "blocks_first" / "blocks_second" (workgroups that share one pass over a
- * matrix in the first or only / the second product), "mfma_min_tokens" (experts -- or, in
- * qmoe_decode_matvec, batches -- with at least this many tokens use the matrix-core kernel; -1 = never), "overlap" (-1 = no side
- * stream: all kernels of a layer one after the other on the caller's stream),
- * "host_threads" (encoder
- * threads),
- * "phases" (bit mask of the layer's kernels to enqueue: 1 dispatch, 2 / 4 scalar kernel of
- * the first / second product, 8 / 16 matrix-core kernel of the first / second product --
- * lets a benchmark time one kernel on a workspace a full call has filled).  value 0
- * restores the built-in heuristic; lds_dict_entries = -1 keeps the whole table in L2 (either numbering), a
+ * "rows_per_item", "token_tile", "lds_dict_entries", "grid_per_cu",
+ * "blocks_first" / "blocks_second" (workgroups that share one pass over a matrix in the
+ * first or only / the second product), "mfma_min_tokens" (experts -- or, in
+ * qmoe_decode_matvec, batches -- with at least this many tokens use the matrix-core kernel;
+ * -1 = never), "overlap" (-1 = no side stream: all kernels of a layer one after the other on
+ * the caller's stream), "host_threads" (encoder threads).  Value 0 restores the built-in
+ * heuristic; lds_dict_entries = -1 keeps the whole table in L2 (either numbering), a
  * positive value forces it into LDS.
  * Unknown key: INVALID_ARG.
  */

@@ -47,16 +47,20 @@ EXPORTS = [
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
     "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
-    "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device",
+    "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device", "qmoe_hook_set",
 ]
 
 
 def lib():
-    """Load the library (building it first only if no built copy exists)."""
+    """Load the library.  It is built first when no built copy exists; a copy older than any of
+    its sources or headers is refused (run `python paper_2310_16795_amd/build.py`, or
+    __graft_entry__.build(), after editing them): figures from a stale binary describe old code."""
     global _lib
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build_library()
+        elif _build.stale():
+            raise RuntimeError(f"{_build.LIB} is older than its sources: rebuild it (python paper_2310_16795_amd/build.py)")
         L = ctypes.CDLL(_build.LIB)
         vp, sz, i = c_void_p, c_size_t, c_int
         L.qmoe_strerror.argtypes, L.qmoe_strerror.restype = [i], c_char_p
@@ -82,6 +86,7 @@ def lib():
         L.qmoe_encode_device.argtypes = [vp, vp, i, i, vp, sz, vp, vp, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
+        L.qmoe_hook_set.argtypes = [c_char_p, i]
         L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
@@ -282,6 +287,11 @@ def qmoe_bf16_layer_forward(wi_ptrs, wo_ptrs, n_experts: int, d_model: int, d_ff
 
 def qmoe_set_tuning(key: str, value: int) -> None:
     _check(lib().qmoe_set_tuning(key.encode(), int(value)), "qmoe_set_tuning")
+
+
+def qmoe_hook_set(key: str, value: int) -> None:
+    """Measurement hooks (include/qmoe_hooks.h): not part of the product ABI."""
+    _check(lib().qmoe_hook_set(key.encode(), int(value)), "qmoe_hook_set")
 
 
 def qmoe_stream_copy(dst, src, stream=None) -> None:

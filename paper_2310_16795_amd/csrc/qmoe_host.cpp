@@ -12,6 +12,7 @@
 #include <thread>
 
 #include "qmoe_internal.h"
+#include "qmoe_hooks.h"
 
 namespace qmoe {
 
@@ -430,10 +431,17 @@ qmoe_status qmoe_set_tuning(const char *key, int value)
     else if (!std::strcmp(key, "blocks_first")) t.blocks_first = value;
     else if (!std::strcmp(key, "blocks_second")) t.blocks_second = value;
     else if (!std::strcmp(key, "mfma_min_tokens")) t.mfma_min_tokens = value;
-    else if (!std::strcmp(key, "mm_stagger")) t.mm_stagger = value;
     else if (!std::strcmp(key, "overlap")) t.overlap = value;
+    else return QMOE_E_INVALID_ARG;
+    return QMOE_OK;
+}
+
+qmoe_status qmoe_hook_set(const char *key, int value)
+{
+    if (!key) return QMOE_E_INVALID_ARG;
+    Tuning &t = tuning();
+    if (!std::strcmp(key, "phases")) t.phases = value;
     else if (!std::strcmp(key, "stage_out")) t.stage_out = value;
-    else if (!std::strcmp(key, "phases")) t.phases = value;
     else return QMOE_E_INVALID_ARG;
     return QMOE_OK;
 }

@@ -66,11 +66,11 @@ struct Tuning {
     int host_threads = 0;
     int blocks_first = 0;   // forced blocks per matrix pass, first / single product
     int blocks_second = 0;  // same, second product of a layer
-    int mm_stagger = 0;  // 1 = the two wavefronts of a SIMD half a step apart in the matrix-core kernel (slower when measured)
     int stage_out = 0;  // -1 = the first product writes its hidden values straight to global memory
     int overlap = 0;  // -1 = all kernels of a layer on the caller's stream, one after the other
     int mfma_min_tokens = 0;  // 0 = heuristic, -1 = never use the matrix-core kernel
-    int phases = 0;  // bit 0 dispatch, bit 1 first product, bit 2 second product; 0 = all
+    int phases = 0;  // kernels of a layer call to enqueue: bit 0 dispatch, bits 1 / 2 scalar kernel of the first / second
+                     // product, bits 3 / 4 matrix-core kernel of the first / second product; 0 = all
 };
 Tuning &tuning();
 

@@ -1,0 +1,568 @@
+// Kernels built on the ring decoder: the matrix-core product for crowded experts
+// (Section 5.3 of the paper proposes decoding once for several tokens) and the
+// decompression of whole matrices (Section 4.3.3 mentions it as a variant).
+#include "qmoe_dev.h"
+
+namespace qmoe {
+namespace {
+
+// ---------------------------------------------------------------- matrix-core product for crowded experts
+//
+// An expert with many tokens is a dense contraction once its ternary weights are
+// in hand: y[token][row] = sum_k x[token][k] * W[row][k].  The scalar kernel above
+// would decode the matrix again for every few tokens; this one decodes it once per
+// tile of up to 64 tokens.  A workgroup owns up to 512 rows (one lane per row) and
+// walks the columns 64 at a time.  Every lane keeps a ring of 128 one-byte columns
+// of its row in LDS and decodes its codewords into it sequentially, as far ahead as
+// the ring allows (so the lanes of a wavefront, whose codewords end at different
+// columns, seldom wait for each other); then each wavefront multiplies the 64
+// columns that are complete, for the 64 rows its own lanes decoded, with the
+// tokens' activations (staged in LDS, shared by all wavefronts) on the matrix
+// cores: D[token][row] += X[token][k] * W^T[k][row], fp32 accumulators in
+// registers.  The ring holds the weights as the high byte of bf16 +-2.0 (0x40 /
+// 0xC0, low byte zero), expanded to bf16 by a byte permute when a fragment is
+// read; the factor 2 is taken out again, exactly, when a row is written.
+// Only device-order streams (whole table in LDS) take this path.
+
+constexpr int kMmKc = 64;                      // columns per step
+constexpr int kMmRing = 2 * kMmKc;             // columns a lane's ring holds
+constexpr int kMmAhead = kMmRing - 28;         // a codeword may start this far past the step's first column
+constexpr int kMmWRowBytes = kMmRing + 8;      // 34 banks per row: 16 consecutive rows read 8 bytes each without conflict
+constexpr int kMmXRowBytes = 2 * kMmKc + 16;   // 36 banks per row: 8 consecutive rows read 16 bytes each without conflict
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+
+// eight ring bytes (high bytes of bf16) -> eight bf16
+__device__ __forceinline__ bf16x8 mm_expand(uint32_t d0, uint32_t d1)
+{
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(0u, d0, 0x010c000cu);
+    o.y = __builtin_amdgcn_perm(0u, d0, 0x030c020cu);
+    o.z = __builtin_amdgcn_perm(0u, d1, 0x010c000cu);
+    o.w = __builtin_amdgcn_perm(0u, d1, 0x030c020cu);
+    bf16x8 r;
+    __builtin_memcpy(&r, &o, 16);
+    return r;
+}
+
+// Asymmetric grid: the ring holds byte selectors (0: zero, 2: w_max, 6: w_min) and eight of
+// them pick the row's own bf16 grid points out of lo = w_max << 16, hi = w_min << 16 (bytes
+// 0..3 of the permute's source are lo, 4..7 hi; selector b takes the value's low byte,
+// b + 1 its high byte).
+__device__ __forceinline__ bf16x8 mm_expand_minmax(uint32_t d0, uint32_t d1, uint32_t hi, uint32_t lo)
+{
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d0, 0x01010000u) + 0x01000100u);
+    o.y = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d0, 0x03030202u) + 0x01000100u);
+    o.z = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d1, 0x01010000u) + 0x01000100u);
+    o.w = __builtin_amdgcn_perm(hi, lo, __builtin_amdgcn_perm(0u, d1, 0x03030202u) + 0x01000100u);
+    bf16x8 r;
+    __builtin_memcpy(&r, &o, 16);
+    return r;
+}
+
+using lw_u8 = __attribute__((address_space(3))) unsigned char *;
+using lw_u64 = __attribute__((address_space(3))) unsigned long long *;
+using lw_u32x4 = __attribute__((address_space(3))) u32x4 *;
+using lp_u64 = const __attribute__((address_space(3))) unsigned long long *;
+using lp_u32x4 = const __attribute__((address_space(3))) u32x4 *;
+using lp_i32 = const __attribute__((address_space(3))) int *;
+using lp_f32 = const __attribute__((address_space(3))) float *;
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global
+// memory, which makes every wavefront wait for all its loads in flight: the prefetches
+// of codewords and activations would then be exposed at every step.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// ---- the ring decoder shared by the matrix-core product and the decompression kernel ----
+// (macros rather than a struct with member functions: the decoder's state has to stay in
+// plain scalar registers, and the compiler keeps it there only when it sees scalars.)
+//
+// QMOE_RING_ROW_SETUP declares the state for one lane = one row: `left` codewords to go,
+// the stream in 16-byte pieces (eight codewords) -- c0..c3 and n0..n3 are the window the
+// decoder picks codewords from (index sub = 0..15), `fut` is in flight; pieces past the
+// lane's last one re-read the last (never used: `left` runs out first) -- and `pos`, the
+// column where the next codeword starts.
+#define QMOE_RING_ROW_SETUP(M, row, row_live)                                                           \
+    uint32_t left = 0;                                                                                  \
+    uintptr_t pp = reinterpret_cast<uintptr_t>((M).codes), last = pp;                                   \
+    uint32_t sub = 0;                                                                                   \
+    if (row_live) {                                                                                     \
+        gp_u32 row_off_ = (gp_u32)(M).row_off;                                                          \
+        const uint32_t cap_ = min((M).n_codes, kMaxCodes);                                              \
+        const uint32_t K1_ = min(row_off_[(row) + 1], cap_);                                            \
+        const uint32_t K0_ = min(row_off_[(row)], K1_);                                                 \
+        left = K1_ - K0_;                                                                               \
+        /* a row without codewords reads the matrix's first piece, never past the stream's end */      \
+        const uintptr_t first_byte_ =                                                                   \
+            reinterpret_cast<uintptr_t>((M).codes) + (left ? 2 * (uintptr_t)K0_ : (uintptr_t)0);        \
+        const uint32_t lead_ = (uint32_t)(first_byte_ & 15u);                                           \
+        pp = first_byte_ - lead_;                                                                       \
+        sub = lead_ >> 1;                                                                               \
+        last = pp + 16u * (uintptr_t)(left ? ((lead_ + 2u * left + 15u) >> 4) - 1u : 0u);               \
+    }                                                                                                   \
+    uint32_t c0, c1, c2, c3, n0, n1, n2, n3;                                                            \
+    {                                                                                                   \
+        const u32x4 a0_ = *(gp_u32x4)pp, a1_ = *(gp_u32x4)(pp + 16u < last ? pp + 16u : last);          \
+        c0 = a0_.x; c1 = a0_.y; c2 = a0_.z; c3 = a0_.w;                                                 \
+        n0 = a1_.x; n1 = a1_.y; n2 = a1_.z; n3 = a1_.w;                                                 \
+    }                                                                                                   \
+    u32x4 fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                         \
+    int pos = 0
+
+// Table entry of the codeword at index `at` (0..15) of the window (anything when at > 15:
+// not used then).
+#define QMOE_MM_ENTRY_AT(dst, at)                                                                       \
+    do {                                                                                                \
+        const bool hi8_ = ((at) & 8u) != 0u, hi4_ = ((at) & 4u) != 0u;                                  \
+        const uint32_t lo_ = hi8_ ? (hi4_ ? n2 : n0) : (hi4_ ? c2 : c0);                                \
+        const uint32_t hi_ = hi8_ ? (hi4_ ? n3 : n1) : (hi4_ ? c3 : c1);                                \
+        /* bytes 2s, 2s+1 of {hi, lo}: selector 0x0c0c0100 + 0x0202 * s */                              \
+        const uint32_t code_ = __builtin_amdgcn_perm(hi_, lo_, 0x0c0c0100u + 0x0202u * ((at) & 3u));    \
+        (dst) = order_entry(table, code_, (uint32_t)a.n_groups, (uint32_t)a.n_order);                   \
+    } while (0)
+
+// Decode step c of the ring at LDS byte address `wrow` (128 one-byte columns + 8 spare
+// bytes): clear the half that becomes columns kend .. kend+63, then decode until every lane
+// has passed column kend = 64 (c + 1); lanes that are there already keep going while their
+// next codeword fits into the ring.  AFTER_WAIT runs right after the step's one wait for
+// global memory (a good place to issue loads that should stay in flight for a whole step).
+// A weight's ring byte is its two-bit field (2: +1, 6: -1) shifted left by BYTE_SHIFT.
+#define QMOE_RING_DECODE_STEP(c, AFTER_WAIT, BYTE_SHIFT)                                                          \
+    const int kc = (c) * kMmKc, kend = kc + kMmKc;                                                      \
+    _Pragma("unroll") for (int i_ = 0; i_ < kMmKc / 8; i_++)                                            \
+        ((lw_u64)(uintptr_t)(wrow + (uint32_t)((((c) + 1) & 1) * kMmKc)))[i_] = 0ull;                   \
+    do {                                                                                                \
+        /* Slide the window by one piece where its first half is used up (once per step as a */        \
+        /* rule; the loop comes back only for lanes that use up a whole window in one step). */        \
+        /* The other lanes fetch the piece they already wait for again, so that the load is */         \
+        /* unconditional and stays in flight until the next slide. */                                   \
+        {                                                                                               \
+            const bool s8_ = sub >= 8u;                                                                 \
+            sub -= s8_ ? 8u : 0u;                                                                       \
+            pp += s8_ ? 16u : 0u;                                                                       \
+            const uint32_t f0_ = fut.x, f1_ = fut.y, f2_ = fut.z, f3_ = fut.w;                          \
+            c0 = s8_ ? n0 : c0; c1 = s8_ ? n1 : c1; c2 = s8_ ? n2 : c2; c3 = s8_ ? n3 : c3;             \
+            n0 = s8_ ? f0_ : n0; n1 = s8_ ? f1_ : n1; n2 = s8_ ? f2_ : n2; n3 = s8_ ? f3_ : n3;         \
+            fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                       \
+        }                                                                                               \
+        AFTER_WAIT                                                                                      \
+        /* No branches inside the inner loop: a lane that sits out decodes an empty entry into */      \
+        /* the spare bytes after its ring.  The look-up of the next codeword is issued before */       \
+        /* the current one is applied. */                                                               \
+        uint32_t ent_next_;                                                                             \
+        QMOE_MM_ENTRY_AT(ent_next_, sub);                                                               \
+        while (__any(left != 0u && pos < kend && sub < 16u)) {                                          \
+            const bool go_ = left != 0u && pos <= kc + kMmAhead && sub < 16u;                           \
+            const uint32_t ent_ = go_ ? ent_next_ : 0u;                                                 \
+            left -= go_ ? 1u : 0u;                                                                      \
+            sub += go_ ? 1u : 0u;                                                                       \
+            QMOE_MM_ENTRY_AT(ent_next_, sub);                                                           \
+            const uint32_t base_ = go_ ? (uint32_t)pos : (uint32_t)kMmRing;                             \
+            const uint32_t mask_ = go_ ? (uint32_t)(kMmRing - 1) : 0xFFu;                               \
+            /* fields are right-aligned in device-order entries: an unused one (0) comes first */      \
+            /* and writes a zero at the run's first column, before any real weight */                   \
+            _Pragma("unroll") for (int z_ = 0; z_ < kRunMaxNonzeros; z_++) {                            \
+                const uint32_t f_ = (ent_ >> (8 + 8 * z_)) & 0xFFu;                                     \
+                const uint32_t col_ = (base_ + (f_ >> 3)) & mask_;                                      \
+                /* shift 5: 0, 0x40 (+2.0), 0xC0 (-2.0) */                                              \
+                *(lw_u8)(uintptr_t)(wrow + col_) = (unsigned char)((f_ & 6u) << (BYTE_SHIFT));          \
+            }                                                                                           \
+            pos += (int)((ent_ & 0xFFu) >> 3);                                                          \
+        }                                                                                               \
+    } while (__any(left != 0u && pos < kend))
+
+// MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
+// rings and the two activation buffers.
+template <int MB, int EPI, int ASYM>
+__device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
+                                        lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // this thread's part of the activation tile: token tx, columns 8*seg .. 8*seg+7 of each step
+    const int tx = tid >> 3, seg = tid & 7;
+    const bool x_live = tx < ntok;
+    size_t xrow = 0;
+    if (x_live) {
+        const int tok = a.perm ? a.perm[slot0 + tx] : slot0 + tx;
+        xrow = a.x_by_slot ? (size_t)(slot0 + tx) : (size_t)tok;
+    }
+    // Loads are unconditional (a lane without a token, or past the last column, reads a
+    // valid address and drops the value when it stages it): a load under a branch would
+    // be waited for at the end of the branch instead of staying in flight.
+    const bool x_ok = x_live && 8 * seg + 8 <= a.cols;
+    const uintptr_t xsrc =
+        reinterpret_cast<uintptr_t>(a.x) + (x_ok ? 2 * (xrow * (size_t)a.ldx + 8 * (size_t)seg) : (size_t)0);
+    const int x_last = x_ok ? a.cols - 8 * seg - 8 : 0;  // last column offset this thread may read at
+    auto load_x = [&](int kc) -> u32x4 { return *(gp_u32x4)(xsrc + 2 * (uintptr_t)min(kc, x_last)); };
+    auto keep_x = [&](const u32x4 &v, int kc) -> u32x4 {
+        return (x_ok && kc <= x_last) ? v : u32x4{0u, 0u, 0u, 0u};
+    };
+    const uint32_t x_slot = xt + (uint32_t)(tx * kMmXRowBytes + 16 * seg);  // in buffer 0
+
+    // this lane's row and its codewords
+    const int r0 = blk * a.mm_rows_per_block;
+    const int row = r0 + tid;
+    const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
+    QMOE_RING_ROW_SETUP(M, row, row_live);
+    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
+
+    f32x16 acc[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[mb][nb][v] = 0.0f;
+
+    // Activations: step c is read from LDS buffer c & 1; step c + 1 is in flight to a
+    // register during step c and staged at its end.
+    *(lw_u32x4)(uintptr_t)x_slot = keep_x(load_x(0), 0);
+    u32x4 xr = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+
+    // asymmetric grid: the grid points of the two rows whose weights this lane feeds to the matrix cores
+    uint32_t g_hi[2] = {0u, 0u}, g_lo[2] = {0u, 0u};
+    if constexpr (ASYM) {
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++) {
+            const int rl = 64 * wave + 32 * nb + l32;
+            uint32_t pair = 0u;  // a row past the end, or a matrix without a pair array, multiplies as zeros
+            if (rl < a.mm_rows_per_block && r0 + rl < a.rows && M.minmax_bf16) pair = ((gp_u32)M.minmax_bf16)[r0 + rl];
+            g_hi[nb] = pair << 16;
+            g_lo[nb] = pair & 0xFFFF0000u;
+        }
+    }
+    const uint32_t wfrag = wt + (uint32_t)((64 * wave + l32) * kMmWRowBytes + 8 * lhi);
+    const uint32_t xfrag0 = xt + (uint32_t)(l32 * kMmXRowBytes + 16 * lhi);
+    const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+
+    __syncthreads();  // token ids, gates and the first activation step are in place
+    for (int c = 0; c < nsteps; c++) {
+        // ---- decode step c; the next step's activations, staged after this step's product,
+        // are fetched right after the window's wait, so that a whole step hides the latency
+        // of both loads (the empty asm keeps the compiler from moving the load up, in front
+        // of that wait)
+        // The arbiter serves the older wavefront of a SIMD first, so the older four finish a
+        // step's decoding early and wait at the step's barrier (a quarter of their time) for
+        // the younger four; the younger ones decode at a raised priority (2-3 %, measured;
+        // raising it for all eight helps the second product only, alternating it hurts).
+        if (wave >= kMmThreads / 128) __builtin_amdgcn_s_setprio(1);
+        QMOE_RING_DECODE_STEP(c, {
+            int k_next = kend;
+            asm volatile("" : "+s"(k_next));
+            xr = load_x(k_next);
+        }, ASYM ? 0 : 5);
+        __builtin_amdgcn_s_setprio(0);
+        // the rows this wavefront multiplies are the ones its own lanes wrote
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- multiply step c
+        const uint32_t xf = xfrag0 + (uint32_t)((c & 1) * kMmTokens * kMmXRowBytes);
+        const uint32_t wf = wfrag + (uint32_t)((c & 1) * kMmKc);
+#pragma unroll
+        for (int ks = 0; ks < kMmKc / 16; ks++) {
+            bf16x8 bw[2], ax[MB];
+#pragma unroll
+            for (int nb = 0; nb < 2; nb++) {
+                const unsigned long long d = *(lp_u64)(uintptr_t)(wf + (uint32_t)(nb * 32 * kMmWRowBytes + 16 * ks));
+                if constexpr (ASYM)
+                    bw[nb] = mm_expand_minmax((uint32_t)d, (uint32_t)(d >> 32), g_hi[nb], g_lo[nb]);
+                else
+                    bw[nb] = mm_expand((uint32_t)d, (uint32_t)(d >> 32));
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++) {
+                const u32x4 t = *(lp_u32x4)(uintptr_t)(xf + (uint32_t)(mb * 32 * kMmXRowBytes + 32 * ks));
+                __builtin_memcpy(&ax[mb], &t, 16);
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+                for (int nb = 0; nb < 2; nb++)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[mb], bw[nb], acc[mb][nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- stage this thread's part of step c + 1 of the activations: the buffer held
+        // step c - 1, which every wavefront has finished by now, and nobody reads step c + 1
+        // before the barrier below
+        *(lw_u32x4)(uintptr_t)(x_slot + (uint32_t)(((c + 1) & 1) * kMmTokens * kMmXRowBytes)) =
+            keep_x(xr, kend);
+        lds_barrier();
+    }
+
+    // accumulator v of lane l: token 32*mb + 8*(v/4) + 4*(l/32) + v%4, row 32*nb + l%32 of the wavefront's 64
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++) {
+        const int rl = 64 * wave + 32 * nb + l32;
+        const int r = r0 + rl;
+        if (rl < a.mm_rows_per_block && r < a.rows) {
+            // symmetric grid: the weights were +-2; asymmetric: they were the grid points themselves
+            const float scale = ASYM ? 1.0f : 0.5f * half_bits_to_float(((gp_u16)M.scale_f16)[r]);
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++) {
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int t = 32 * mb + 8 * (v / 4) + 4 * lhi + (v % 4);
+                    if (t < ntok) {
+                        const float val = acc[mb][nb][v] * scale;
+                        if constexpr (EPI == 0) {
+                            reinterpret_cast<float *>(a.out)[(size_t)tok_ids[t] * a.ld_out + r] = gate_s[t] * val;
+                        } else {
+                            const float h = val > 0.0f ? val : 0.0f;
+                            reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] =
+                                float_to_bf16_bits(h);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int EPI, int ASYM>
+__global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
+    uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
+    unsigned char *wt = smem + table_bytes;                           // [512][kMmWRowBytes]
+    unsigned char *xt = wt + (size_t)kMmThreads * kMmWRowBytes;       // 2 x [64][kMmXRowBytes]
+    int *tok_ids = reinterpret_cast<int *>(xt + 2 * (size_t)kMmTokens * kMmXRowBytes);  // [64]
+    float *gate_s = reinterpret_cast<float *>(tok_ids + kMmTokens);   // [64]
+    int *next_item = reinterpret_cast<int *>(gate_s + kMmTokens);     // [1]
+
+    // A layer call brings a list of (expert, token tile) items and a device counter that hands
+    // them out; the single-matrix call has neither: its items are the tiles of 64 consecutive
+    // tokens of `single`, dealt out round robin.
+    const bool listed = a.items != nullptr;
+    const int n_items = listed ? min(*a.n_items_dev, a.max_items) : (a.batch + kMmTokens - 1) / kMmTokens;
+    const int total = (int)min((long long)n_items * a.mm_row_blocks, 0x7FFFFFFFLL);
+    if (total <= 0 || (!listed && (int)blockIdx.x >= total)) return;
+    stage_words(table_w, a.order_table, a.n_order);
+
+    int g_static = (int)blockIdx.x;
+    for (;;) {
+        __syncthreads();  // everyone is done with the previous item
+        if (threadIdx.x == 0) {
+            const int g = listed ? atomicAdd(a.work_counter, 1) : g_static;
+            *next_item = g < total ? g : -1;
+        }
+        g_static += (int)gridDim.x;
+        __syncthreads();
+        const int g = *next_item;
+        if (g < 0) break;
+        const int idx = g / a.mm_row_blocks;
+        const int blk = g - idx * a.mm_row_blocks;
+        Item it;
+        if (listed) {
+            it = a.items[idx];
+        } else {
+            it.expert = 0;
+            it.slot0 = idx * kMmTokens;
+            it.ntok = a.batch - idx * kMmTokens;
+        }
+        const int expert = it.expert, slot0 = it.slot0;
+        const int ntok = min(it.ntok, kMmTokens);
+        if (expert < 0 || expert >= a.n_experts || ntok < 1) continue;
+        if (threadIdx.x < kMmTokens) {
+            const int t = threadIdx.x;
+            const int tok = t < ntok ? (a.perm ? a.perm[slot0 + t] : slot0 + t) : 0;
+            tok_ids[t] = tok;
+            gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
+        }
+        const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
+        const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, xt_addr = (uint32_t)(uintptr_t)(lw_u8)xt;
+        if (ntok <= 32)
+            mm_item<1, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+                            (lp_f32)gate_s);
+        else
+            mm_item<2, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
+                            (lp_f32)gate_s);
+    }
+}
+
+// ---------------------------------------------------------------- decompression of whole matrices
+//
+// The codec without the product: dense ternary (int8) or scaled bf16 copies of compressed
+// matrices, for consumers that want a plain matrix (a library GEMM, a check).  Same ring
+// decoder as the matrix-core product: a workgroup of 512 lanes owns up to 512 rows, one lane
+// per row; after each 64-column step a wavefront writes out the 64 x 64 tile its own lanes
+// decoded, 8 rows per store instruction with 8 lanes covering a row's 64 columns, so that
+// the stores are whole 64- or 128-byte runs.  Wavefronts never wait for each other.
+
+
+// OUT 0: int8 in {-1, 0, +1}; 1: bf16(scale of the row) with the weight's sign, or 0;
+// 2: the row's bf16 grid point w_max or w_min, or 0 (asymmetric grid)
+template <int OUT>
+__global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
+    uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
+    stage_words(table_w, a.order_table, a.n_order);
+    __syncthreads();
+    lp_u32 table = (lp_u32)table_w;
+    const uint32_t wt = (uint32_t)(uintptr_t)(lw_u8)(smem + table_bytes);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
+    const int seg = lane & 7, sub_row = lane >> 3;  // write-out role: columns 8*seg.., rows sub_row + 8*i
+    const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+    const long long total = (long long)a.n_mats * a.row_blocks;
+
+    for (long long g = blockIdx.x; g < total; g += gridDim.x) {
+        const int m = (int)(g / a.row_blocks);
+        const int blk = (int)(g - (long long)m * a.row_blocks);
+        unsigned char *out = static_cast<unsigned char *>(a.out[m]);
+        if (!out) continue;
+        const qmoe_matrix M = a.mats[m];
+        const int r0 = blk * a.rows_per_block;
+        const int row = r0 + tid;
+        const bool row_live = tid < a.rows_per_block && row < a.rows;
+        QMOE_RING_ROW_SETUP(M, row, row_live);
+#pragma unroll
+        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+
+        // bf16 scale of the eight rows this lane writes out, in both halves of a register
+        uint32_t s2[8];
+        if constexpr (OUT == 2) {
+            // the (w_min, w_max) pair as stored: w_min in the low half
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                s2[i] = 0u;
+                if (rl < a.rows_per_block && r0 + rl < a.rows && M.minmax_bf16) s2[i] = ((gp_u32)M.minmax_bf16)[r0 + rl];
+            }
+        }
+        if constexpr (OUT == 1) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                uint32_t b = 0;
+                if (rl < a.rows_per_block && r0 + rl < a.rows)
+                    b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[r0 + rl]));
+                s2[i] = b | (b << 16);
+            }
+        }
+
+        for (int c = 0; c < nsteps; c++) {
+            QMOE_RING_DECODE_STEP(c, {}, OUT == 2 ? 0 : 5);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int k = kc + 8 * seg;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int rl = 64 * wave + sub_row + 8 * i;
+                const int r = r0 + rl;
+                if (rl < a.rows_per_block && r < a.rows && k + 8 <= a.cols) {
+                    const unsigned long long d =
+                        *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes + (c & 1) * kMmKc + 8 * seg));
+                    const uint32_t w0 = (uint32_t)d, w1 = (uint32_t)(d >> 32);
+                    const size_t at = (size_t)r * a.cols + k;
+                    if constexpr (OUT == 0) {
+                        // ring byte 0x40 -> 0x01, 0xC0 -> 0xFF, 0 -> 0
+                        const uint32_t o0 = ((w0 >> 6) & 0x01010101u) | (((w0 >> 7) & 0x01010101u) * 0xFEu);
+                        const uint32_t o1 = ((w1 >> 6) & 0x01010101u) | (((w1 >> 7) & 0x01010101u) * 0xFEu);
+                        *reinterpret_cast<unsigned long long *>(out + at) = (unsigned long long)o0 | ((unsigned long long)o1 << 32);
+                    } else if constexpr (OUT == 2) {
+                        const bf16x8 v = mm_expand_minmax(w0, w1, s2[i] << 16, s2[i] & 0xFFFF0000u);
+                        u32x4 o;
+                        __builtin_memcpy(&o, &v, 16);
+                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
+                    } else {
+                        u32x4 o;
+#pragma unroll
+                        for (int h = 0; h < 4; h++) {
+                            // two ring bytes -> the high bytes of two 16-bit halves: 0x4000 / 0xC000 / 0
+                            const uint32_t e = __builtin_amdgcn_perm(0u, h < 2 ? w0 : w1, (h & 1) ? 0x030c020cu : 0x010c000cu);
+                            const uint32_t present = ((e >> 14) & 0x00010001u) * 0xFFFFu;
+                            o[h] = ((e & 0x80008000u) | s2[i]) & present;
+                        }
+                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
+                    }
+                }
+            }
+            // the next step clears this half of the ring: after these reads
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+}  // namespace
+
+size_t mm_lds_bytes(int n_order)
+{
+    return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes +
+           2 * (size_t)kMmTokens * kMmXRowBytes + 2 * sizeof(int) * kMmTokens + 16;
+}
+
+size_t decompress_lds_bytes(int n_order)
+{
+    return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes;
+}
+
+void mm_rows(int rows, int *row_blocks, int *rows_per_block)
+{
+    const int nb = (rows + kMmThreads - 1) / kMmThreads;
+    const int per = (rows + nb - 1) / nb;
+    *row_blocks = nb;
+    *rows_per_block = std::min(kMmThreads, (per + 63) / 64 * 64);
+}
+
+// rows_per_block: 0 = as few workgroups per matrix as possible (a layer call has many
+// matrices); otherwise a multiple of 64 up to 512.
+qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s, int rows_per_block)
+{
+    if (rows_per_block > 0) {
+        a.mm_rows_per_block = rows_per_block;
+        a.mm_row_blocks = (a.rows + rows_per_block - 1) / rows_per_block;
+    } else {
+        mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
+    }
+    auto launch = [&](auto kernel) -> qmoe_status {
+        const qmoe_status st = allow_lds(kernel, mp.smem);
+        if (st != QMOE_OK) return st;
+        hipLaunchKernelGGL(kernel, dim3(mp.grid), dim3(kMmThreads), mp.smem, s, a);
+        return QMOE_OK;
+    };
+    qmoe_status st;
+    if (a.minmax)
+        st = a.epilogue ? launch(k_product_mm<1, 1>) : launch(k_product_mm<0, 1>);
+    else
+        st = a.epilogue ? launch(k_product_mm<1, 0>) : launch(k_product_mm<0, 0>);
+    if (st != QMOE_OK) return st;
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
+}
+
+
+qmoe_status launch_decompress(const DecompressArgs &a, int out_kind, bool minmax, int grid, size_t smem, hipStream_t s)
+{
+    qmoe_status st;
+    if (out_kind == 0) {
+        if ((st = allow_lds(k_decompress<0>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<0>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    } else if (minmax) {
+        if ((st = allow_lds(k_decompress<2>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<2>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    } else {
+        if ((st = allow_lds(k_decompress<1>, smem)) != QMOE_OK) return st;
+        hipLaunchKernelGGL(k_decompress<1>, dim3(grid), dim3(kMmThreads), smem, s, a);
+    }
+    QMOE_HIP_TRY(hipGetLastError());
+    return QMOE_OK;
+}
+
+}  // namespace qmoe

@@ -25,7 +25,8 @@ def lib_dict():
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "qmoe.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                     if h.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)  # declarations only
     declared = set(re.findall(r"\b(qmoe_[a-z0-9_]+)\s*\(", header))
     declared -= {"qmoe_status"}
