@@ -59,6 +59,8 @@ def _load():
         lib.orc_matvec_asym.restype = None
         lib.orc_ffn_token_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, dbl, vp, vp, vp]
         lib.orc_ffn_token_asym.restype = None
+        lib.orc_slot_parallel_matvec.argtypes = [vp, i32, vp, vp, vp, vp, i64, i64, vp]
+        lib.orc_slot_parallel_matvec.restype = i32
         lib.orc_dispatch.argtypes = [vp, i64, i64, vp, vp]
         lib.orc_dispatch.restype = None
         lib.orc_bf16_to_double.argtypes = [c.c_uint16]
@@ -192,6 +194,27 @@ def matvec(tern: np.ndarray, scale_f16: np.ndarray, x_bf16: np.ndarray, with_bou
         lib.orc_matvec_asym(_p(tern), _p(mm), _p(x), rows, cols, x.shape[0], _p(y),
                             _p(bound) if with_bound else None)
     return (y, bound) if with_bound else y
+
+
+def slot_parallel_matvec(words: np.ndarray, codes: np.ndarray, row_off: np.ndarray, rows: int, cols: int,
+                         w_min: np.ndarray, w_max: np.ndarray, x_bf16: np.ndarray) -> np.ndarray:
+    """The product in its second formulation (Section 4.3.3 "Execution", Listing 1): 28 slot
+    workers straight from (entry words, codewords, row offsets), no decoded matrix.
+    w_min / w_max: float64 [rows]; x_bf16: uint16 [cols].  Returns y float64 [rows]."""
+    lib = _load()
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    row_off = np.ascontiguousarray(row_off, dtype=np.uint32)
+    mm = np.ascontiguousarray(np.stack([w_min, w_max], axis=1), dtype=np.float64)
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    assert x.shape == (cols,) and mm.shape == (rows, 2) and row_off.shape == (rows + 1,)
+    y = np.zeros(rows, dtype=np.float64)
+    rc = lib.orc_slot_parallel_matvec(_p(words), words.shape[0], _p(codes), _p(row_off), _p(mm), _p(x), rows, cols,
+                                      _p(y))
+    if rc:
+        raise ValueError({1: "a row's phrases run past its end", 2: "codeword out of range",
+                          3: "symbol value 3"}.get(rc, f"error {rc}"))
+    return y
 
 
 def ffn_token(wi, wi_scale, wo, wo_scale, x_bf16, gate: float = 1.0, wi_minmax=None, wo_minmax=None):

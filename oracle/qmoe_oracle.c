@@ -413,6 +413,59 @@ void orc_ffn_token(const int8_t *wi, const uint16_t *wi_scale, const int8_t *wo,
 }
 
 /* ------------------------------------------------------------------ */
+/* Second formulation of the product: the slot-parallel decoder          */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The product as the paper's kernel computes it (Section 4.3.3, "Execution" and
+ * Listing 1), straight from the packed entry words and the codeword stream, without
+ * ever materialising the matrix: 28 workers, one per slot of a dictionary entry.  For
+ * every codeword of a row, worker j reads symbol j of the entry (slot j of the first
+ * word for j < 14, slot j - 14 of the second otherwise), dequantises it through the
+ * row's three-value table {0, w_min, w_max} and adds value * x[start + j] to its own
+ * partial sum; `start` then advances by twice the entry's pair count.  Nothing tests j
+ * against the entry's length: slots past it hold symbol 0, and x is read up to 27
+ * places past the row's end, where it is zero-padded.  The 28 partial sums are added at
+ * the end of the row.  fp64 throughout; result overwrites y (the printed kernel adds
+ * into a bfloat16 y).
+ * minmax: [rows][2] doubles (w_min, w_max) of each row.  Returns 0, or 2 for a codeword
+ * outside the table, 1 for a row whose phrases run past cols + 28.
+ */
+int orc_slot_parallel_matvec(const uint32_t *words, int n_entries, const uint16_t *codes, const uint32_t *row_off,
+                             const double *minmax, const uint16_t *x_bf16, int64_t rows, int64_t cols, double *y)
+{
+    enum { SLOTS = 28 };
+    double *xpad = (double *)calloc((size_t)cols + SLOTS, sizeof(double));
+    if (!xpad) return -1;
+    for (int64_t c = 0; c < cols; c++) xpad[c] = bf16_to_double(x_bf16[c]);
+    int rc = 0;
+    for (int64_t r = 0; r < rows && !rc; r++) {
+        const double deq[3] = {0.0, minmax[2 * r], minmax[2 * r + 1]};
+        double part[SLOTS];
+        for (int j = 0; j < SLOTS; j++) part[j] = 0.0;
+        int64_t start = 0;
+        for (uint32_t k = row_off[r]; k < row_off[r + 1]; k++) {
+            const uint32_t enc = codes[k];
+            if ((int)enc >= n_entries) { rc = 2; break; }
+            if (start > cols) { rc = 1; break; }
+            const uint32_t *w = words + 2 * (size_t)enc;
+            for (int j = 0; j < SLOTS; j++) {
+                const uint32_t half = w[j / 14];
+                const unsigned sym = (half >> (4 + 2 * (j % 14))) & 3u;
+                if (sym == 3u) { rc = 3; break; }
+                part[j] += deq[sym] * xpad[start + j];
+            }
+            start += 2 * (int64_t)(w[0] & 15u);
+        }
+        double sum = 0.0;
+        for (int j = 0; j < SLOTS; j++) sum += part[j];
+        y[r] = sum;
+    }
+    free(xpad);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
 /* Token dispatch: group tokens by expert, keeping their order          */
 /* ------------------------------------------------------------------ */
 

@@ -44,6 +44,11 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int &total)
 // the codewords.  Same stream as qmoe_encode_host, codeword for codeword.
 
 
+__global__ void k_encode_clear(int *status)
+{
+    if (threadIdx.x < 2) status[threadIdx.x] = 0;
+}
+
 template <bool WRITE>
 __global__ __launch_bounds__(256) void k_encode(const EncodeArgs a)
 {
@@ -240,6 +245,8 @@ __global__ __launch_bounds__(256) void k_renumber(uint16_t *codes, size_t n, con
 qmoe_status launch_encode(const EncodeArgs &a, hipStream_t s)
 {
     const int grid = (a.rows + 255) / 256;
+    // the status words are cleared by a kernel, not a memset node, so the call can be captured into a HIP graph
+    hipLaunchKernelGGL(k_encode_clear, dim3(1), dim3(64), 0, s, a.status);
     hipLaunchKernelGGL(k_encode<false>, dim3(grid), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_encode_offsets, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(k_encode<true>, dim3(grid), dim3(256), 0, s, a);

@@ -239,3 +239,69 @@ def test_asymmetric_ffn_token_and_layer():
     # the gate scales output and bound
     yg, _, bg = oracle.ffn_token(w.wi_ternary(e), None, w.wo_ternary(e), None, x[t0], 0.25, w.wi_minmax(e), w.wo_minmax(e))
     assert np.array_equal(yg, 0.25 * y) and np.array_equal(bg, 0.25 * bound)
+
+
+def _slot_parallel_case(od, tern, w_min, w_max, x_bits):
+    """decode-then-dot (orc_decode + a numpy product) against the slot-parallel formulation."""
+    rows, cols = tern.shape
+    codes, row_off = oracle.encode(od, tern)
+    y2 = oracle.slot_parallel_matvec(od.words, codes, row_off, rows, cols, w_min, w_max, x_bits)
+    dense = oracle.decode(od.words, codes, row_off, rows, cols)
+    x = (x_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    vals = np.where(dense > 0, w_max[:, None], np.where(dense < 0, w_min[:, None], 0.0))
+    y1 = vals @ x
+    scale = (np.abs(vals) @ np.abs(x)) + 1e-300
+    assert np.all(np.abs(y1 - y2) <= 1e-13 * scale)
+    return y2
+
+
+def test_slot_parallel_formulation_equals_decode_then_dot(oracle_dict):
+    """Section 4.3.3, Listing 1: 28 slot workers, no length test, zero-padded input.  It only
+    agrees with the sequential decoder if unused slots hold symbol 0, both count nibbles are read
+    alike, symbol 1 / 2 map to w_min / w_max and the column index advances by twice the pair count."""
+    rng = np.random.default_rng(11)
+    for rows, cols, p0 in [(40, 770, 0.9), (7, 2, 0.5), (5, 28, 0.0), (9, 58, 1.0), (12, 6144, 0.97), (33, 30, 0.3)]:
+        tern = synth.ternary(900 + cols, rows, cols, p0)
+        x = synth.normal_bf16(901 + cols, (cols,))
+        w_max = rng.uniform(0.01, 0.1, rows)
+        w_min = -rng.uniform(0.01, 0.1, rows)
+        _slot_parallel_case(oracle_dict, tern, w_min, w_max, x)
+    # symmetric grid through the other oracle routine: y = s * sum T x
+    tern = synth.ternary(950, 24, 280, 0.85)
+    s16 = synth.uniform_f16(951, (24,), 0.01, 0.1)
+    s = s16.view(np.float16).astype(np.float64)
+    x = synth.normal_bf16(952, (280,))
+    y2 = _slot_parallel_case(oracle_dict, tern, -s, s, x)
+    y1, bound = oracle.matvec(tern, s16, x[None, :], with_bound=True)
+    assert np.all(np.abs(y1[0] - y2) <= 1e-13 * bound[0] + 1e-300)
+    # edge rows: all +1, all -1, alternating, a single non-zero at every position of a 56-wide row
+    cols = 56
+    edge = [np.ones(cols), -np.ones(cols), np.resize([1, -1], cols), np.resize([0, 1, 0, -1], cols)]
+    for c in range(cols):
+        row = np.zeros(cols)
+        row[c] = 1 if c % 2 else -1
+        edge.append(row)
+    tern = np.array(edge, dtype=np.int8)
+    xi = _bf16_bits(np.arange(1, cols + 1, dtype=np.float64))  # exact integers: position c carries c + 1
+    y = _slot_parallel_case(oracle_dict, tern, np.full(len(edge), -2.0), np.full(len(edge), 3.0), xi)
+    for c in range(cols):  # row 4 + c holds one non-zero at c: w_max * (c + 1) or w_min * (c + 1)
+        assert y[4 + c] == (3.0 if c % 2 else -2.0) * (c + 1)
+    assert y[0] == 3.0 * cols * (cols + 1) / 2 and y[1] == -2.0 * cols * (cols + 1) / 2
+
+
+def test_slot_parallel_formulation_needs_zero_padding_slots(oracle_dict):
+    """A table whose unused slots are not 0 decodes the same sequentially (the decoder stops at the
+    pair count) but not slot-parallel: the reading "unused slots are 0" is what the listing relies on."""
+    tern = synth.ternary(960, 6, 120, 0.9)
+    x = synth.normal_bf16(961, (120,))
+    codes, row_off = oracle.encode(oracle_dict, tern)
+    s = np.full(6, 0.5)
+    good = oracle.slot_parallel_matvec(oracle_dict.words, codes, row_off, 6, 120, -s, s, x)
+    words = oracle_dict.words.copy()
+    k = int(codes[0])
+    n = int(words[k, 0] & 15)
+    assert n < 14  # the first phrase of a 90 % sparse row is never a full 14 pairs... checked, not assumed
+    slot = 2 * n   # first unused slot
+    words[k, slot // 14] |= np.uint32(2 << (4 + 2 * (slot % 14)))
+    bad = oracle.slot_parallel_matvec(words, codes, row_off, 6, 120, -s, s, x)
+    assert not np.allclose(good, bad, rtol=0, atol=1e-9)
