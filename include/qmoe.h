@@ -21,10 +21,16 @@
  *    errors are found before anything is enqueued.  The contents of device
  *    buffers are trusted: a corrupt codeword stream is not detected on the
  *    device (run qmoe_validate_host on the host copy first); the kernels clamp
- *    every index they derive from it, so such a stream gives wrong numbers,
- *    never an out-of-bounds access.
+ *    the row offsets to n_codes and every table index and column they derive from a
+ *    codeword, so such a stream gives wrong numbers, not an access outside the
+ *    buffers described here.
  *  - Nothing crosses the boundary but plain pointers, sizes and the opaque
- *    qmoe_dict handle.  The only global state is the last HIP error code.
+ *    qmoe_dict handle.
+ *  - Process-wide state: the last HIP error code; the launch tuning
+ *    (qmoe_set_tuning); per device, created on first use and kept until the process
+ *    ends: the device's compute-unit count and LDS size, two events and -- only if a
+ *    layer call brings no second stream of its own -- one stream (qmoe_moe_layer_forward),
+ *    and the address of the 8 MiB scratch array of qmoe_moe_layer_forward_static.
  */
 #ifndef QMOE_H
 #define QMOE_H
@@ -161,8 +167,7 @@ qmoe_status qmoe_validate_host(const qmoe_dict *d, const uint16_t *codes /*host*
  * stream qmoe_encode_host produces.  Nothing is read back: status (device int32[2]) holds
  * 0 or the first error (BAD_SYMBOL, UNENCODABLE, BUFFER_TOO_SMALL) and a row it happened
  * in once the work on `stream` is done; with an error the contents of codes are
- * undefined.  Enqueues a 8-byte memset of status and three kernels; do not capture it
- * into a HIP graph (memset node).
+ * undefined.  Enqueues four kernels (the first clears status), no memset.
  * Errors at the call: INVALID_ARG, NO_DEVICE_DICT, LIMIT (the table's trie has more than
  * 131072 nodes), HIP.
  */
@@ -305,10 +310,12 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * tokens and (device-order streams, widths divisible by 8, x 16-byte aligned) the
  * matrix-core kernel for crowded ones: an expert's matrix is decoded once per tile of up
  * to 64 tokens there, instead of once per 4.  When both kinds of experts are present the
- * two scalar kernels run on a library-owned side stream (one per device, created on first
- * use, default priority) that forks from `stream` after the dispatch and joins it again
- * before the call's work ends, so that later work on `stream` sees y complete as usual;
- * calls on one device must not be issued concurrently from several host threads.
+ * two scalar kernels run on a second stream that forks from `stream` after the dispatch and
+ * joins it again before the call's work ends (two library-owned events per device), so that
+ * later work on `stream` sees y complete as usual.  side_stream: that second stream, owned
+ * by the caller like `stream` (default priority; it must not be `stream` itself); NULL = a
+ * stream the library creates once per device and keeps.  Calls on one device must not be
+ * issued concurrently from several host threads.
  * Errors: INVALID_ARG, NO_DEVICE_DICT, WORKSPACE, LIMIT (n_experts > 16384,
  * n_tokens > 2^20, d_model or d_ff > 32768, or too wide for the LDS: a token's activations
  * take 8 bytes per column, about 20400 columns with 160 KB (with the device numbering the
@@ -320,7 +327,29 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi /*d
                                    int d_model, int d_ff, const uint16_t *x_bf16 /*device*/,
                                    const int32_t *expert_idx /*device*/, const float *gate /*device*/,
                                    int n_tokens, float *y /*device*/, void *workspace /*device*/,
-                                   size_t workspace_bytes, void *stream);
+                                   size_t workspace_bytes, void *stream, void *side_stream);
+
+/*
+ * The same layer for callers that cannot allocate device memory or must not create
+ * streams and events while they call: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No workspace argument: the dispatch results, work
+ * lists and the hidden vector live in a file-scope device array of
+ * qmoe_static_workspace_bytes() = 8 MiB inside the library (each GPU the library runs on
+ * holds its copy until the process ends).  All kernels are enqueued on `stream`, one after
+ * the other (no second stream, no events); the call allocates nothing and creates nothing.
+ * Limit: qmoe_moe_layer_workspace(n_experts, d_model, d_ff, n_tokens) must not exceed
+ * qmoe_static_workspace_bytes(), else QMOE_E_LIMIT (e.g. 512 tokens at d_ff = 4096 fit,
+ * 2048 tokens at d_ff = 6144 do not).  Every call on a GPU shares that GPU's array and
+ * finds the previous call's contents there (the dispatch kernel rewrites all it reads);
+ * calls that overlap on one GPU -- two streams, two host threads -- race.
+ * Other arguments, results and errors as qmoe_moe_layer_forward.
+ */
+size_t qmoe_static_workspace_bytes(void);
+qmoe_status qmoe_moe_layer_forward_static(const qmoe_dict *d, const qmoe_matrix *wi /*device*/,
+                                          const qmoe_matrix *wo /*device*/, int code_order, int n_experts,
+                                          int d_model, int d_ff, const uint16_t *x_bf16 /*device*/,
+                                          const int32_t *expert_idx /*device*/, const float *gate /*device*/,
+                                          int n_tokens, float *y /*device*/, void *stream);
 
 /*
  * Only the dispatch step of the layer (fills tok_off, perm, counters, work items), planned

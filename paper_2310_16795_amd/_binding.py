@@ -47,7 +47,7 @@ EXPORTS = [
     "qmoe_encode_host", "qmoe_validate_host", "qmoe_decode_matvec", "qmoe_decode_dense",
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
     "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
-    "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device", "qmoe_hook_set",
+    "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device", "qmoe_hook_set", "qmoe_static_workspace_bytes", "qmoe_moe_layer_forward_static",
 ]
 
 
@@ -78,7 +78,9 @@ def lib():
         L.qmoe_decode_dense.argtypes = [vp, POINTER(qmoe_matrix), vp, i, vp]
         L.qmoe_moe_layer_ws_layout.argtypes = [i, i, i, i, POINTER(qmoe_ws_layout)]
         L.qmoe_moe_layer_workspace.argtypes, L.qmoe_moe_layer_workspace.restype = [i, i, i, i], sz
-        L.qmoe_moe_layer_forward.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
+        L.qmoe_moe_layer_forward.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, sz, vp, vp]
+        L.qmoe_moe_layer_forward_static.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp]
+        L.qmoe_static_workspace_bytes.argtypes, L.qmoe_static_workspace_bytes.restype = [], sz
         L.qmoe_dict_device_order.argtypes = [vp, POINTER(vp), POINTER(vp), POINTER(i), POINTER(i)]
         L.qmoe_codes_to_device_order.argtypes = [vp, vp, sz, vp]
         L.qmoe_moe_dispatch.argtypes = [vp, i, vp, i, i, i, i, vp, sz, vp]
@@ -233,9 +235,33 @@ def qmoe_moe_layer_workspace(n_experts: int, d_model: int, d_ff: int, n_tokens: 
     return lib().qmoe_moe_layer_workspace(n_experts, d_model, d_ff, n_tokens)
 
 
+def _layer_shapes(wi_dev, wo_dev, n_experts, d_model, x_bf16, expert_idx, y) -> int:
+    n_tokens = x_bf16.shape[0]
+    if x_bf16.shape[1] != d_model or tuple(y.shape) != (n_tokens, d_model) or expert_idx.numel() != n_tokens:
+        raise ValueError("shape mismatch")
+    need = ctypes.sizeof(qmoe_matrix) * n_experts
+    if wi_dev.numel() * wi_dev.element_size() < need or wo_dev.numel() * wo_dev.element_size() < need:
+        raise ValueError("expert descriptor arrays too small")
+    return n_tokens
+
+
+def qmoe_static_workspace_bytes() -> int:
+    return lib().qmoe_static_workspace_bytes()
+
+
+def qmoe_moe_layer_forward_static(d: int, wi_dev, wo_dev, code_order: int, n_experts: int, d_model: int, d_ff: int,
+                                  x_bf16, expert_idx, gate, y, stream=None) -> None:
+    """The layer call that brings no workspace (the library's bounded scratch array is used)."""
+    n_tokens = _layer_shapes(wi_dev, wo_dev, n_experts, d_model, x_bf16, expert_idx, y)
+    _check(lib().qmoe_moe_layer_forward_static(d, _dev_ptr(wi_dev), _dev_ptr(wo_dev), code_order, n_experts, d_model,
+                                               d_ff, _dev_ptr(x_bf16), _dev_ptr(expert_idx), _dev_ptr(gate), n_tokens,
+                                               _dev_ptr(y), _stream_ptr(stream)), "qmoe_moe_layer_forward_static")
+
+
 def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, code_order: int, n_experts: int, d_model: int, d_ff: int,
-                           x_bf16, expert_idx, gate, y, workspace, stream=None) -> None:
-    """wi_dev / wo_dev: device byte tensors holding n_experts qmoe_matrix structs."""
+                           x_bf16, expert_idx, gate, y, workspace, stream=None, side_stream=None) -> None:
+    """wi_dev / wo_dev: device byte tensors holding n_experts qmoe_matrix structs.
+    side_stream: a second stream of the caller's for the scalar kernels (None: the library's own)."""
     n_tokens = x_bf16.shape[0]
     if x_bf16.shape[1] != d_model or tuple(y.shape) != (n_tokens, d_model) or expert_idx.numel() != n_tokens:
         raise ValueError("shape mismatch")
@@ -245,7 +271,8 @@ def qmoe_moe_layer_forward(d: int, wi_dev, wo_dev, code_order: int, n_experts: i
     _check(lib().qmoe_moe_layer_forward(d, _dev_ptr(wi_dev), _dev_ptr(wo_dev), code_order, n_experts, d_model, d_ff,
                                         _dev_ptr(x_bf16), _dev_ptr(expert_idx), _dev_ptr(gate), n_tokens,
                                         _dev_ptr(y), _dev_ptr(workspace),
-                                        workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+                                        workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+                                        0 if side_stream is None else _stream_ptr(side_stream)),
            "qmoe_moe_layer_forward")
 
 

@@ -26,9 +26,11 @@ namespace {
 qmoe_status device_info(DeviceInfo *out)
 {
     static DeviceInfo cached[64];
+    static std::mutex mu;
     int dev = 0;
     QMOE_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64) return QMOE_E_LIMIT;
+    std::lock_guard<std::mutex> lock(mu);
     if (!cached[dev].ok) {
         int cus = 0, lds = 0;
         QMOE_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
@@ -41,15 +43,17 @@ qmoe_status device_info(DeviceInfo *out)
     return QMOE_OK;
 }
 
-// A side stream and two events per device, made on first use and kept until the process
-// ends: the scalar kernels of a layer run there, next to the matrix-core kernels.
+// The scalar kernels of a layer run on a second stream, next to the matrix-core kernels.
+// The caller may bring that stream; otherwise the library makes one per device on first use
+// (default priority) and keeps it until the process ends.  The two events that fork and join
+// it are the library's in both cases (one pair per device, made on first use).
 struct SideStream {
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;   // library-owned, made only when a call brings none
     hipEvent_t fork = nullptr, join = nullptr;
-    bool ok = false;
+    bool events = false;
 };
 
-qmoe_status side_stream(SideStream *out)
+qmoe_status side_stream(hipStream_t callers, SideStream *out)
 {
     static SideStream cached[64];
     static std::mutex mu;
@@ -58,13 +62,39 @@ qmoe_status side_stream(SideStream *out)
     if (dev < 0 || dev >= 64) return QMOE_E_LIMIT;
     std::lock_guard<std::mutex> lock(mu);
     SideStream &c = cached[dev];
-    if (!c.ok) {
-        QMOE_HIP_TRY(hipStreamCreateWithFlags(&c.stream, hipStreamNonBlocking));
+    if (!c.events) {
         QMOE_HIP_TRY(hipEventCreateWithFlags(&c.fork, hipEventDisableTiming));
         QMOE_HIP_TRY(hipEventCreateWithFlags(&c.join, hipEventDisableTiming));
-        c.ok = true;
+        c.events = true;
     }
+    if (!callers && !c.stream) QMOE_HIP_TRY(hipStreamCreateWithFlags(&c.stream, hipStreamNonBlocking));
     *out = c;
+    if (callers) out->stream = callers;
+    return QMOE_OK;
+}
+
+// Scratch memory of qmoe_moe_layer_forward_static: a bounded workspace that lives in the
+// library's own device image, so that the call allocates nothing.  Each GPU holds its own
+// copy at its own address; host code uses the address hipGetSymbolAddress returns for the
+// current device, never the array's name.
+constexpr size_t kStaticWsBytes = (size_t)8 << 20;
+__device__ __align__(256) unsigned char g_static_ws[kStaticWsBytes];
+
+qmoe_status static_workspace(void **out)
+{
+    static void *cached[64];
+    static std::mutex mu;
+    int dev = 0;
+    QMOE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return QMOE_E_LIMIT;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cached[dev]) {
+        void *p = nullptr;
+        QMOE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_ws)));
+        if (!p) return QMOE_E_HIP;
+        cached[dev] = p;
+    }
+    *out = cached[dev];
     return QMOE_OK;
 }
 
@@ -578,10 +608,14 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
                            pwo.tb_max, mp.min_tokens, nullptr, static_cast<hipStream_t>(stream));
 }
 
-qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
-                                   int code_order, int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
-                                   const int32_t *expert_idx, const float *gate, int n_tokens, float *y,
-                                   void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+
+// side: 0 = every kernel on `stream`; 1 = the scalar kernels on `side_stream`, or on the
+// library's own second stream when that is NULL
+qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
+                          int code_order, int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
+                          const int32_t *expert_idx, const float *gate, int n_tokens, float *y,
+                          void *workspace, size_t workspace_bytes, void *stream, int side, void *side_stream_arg)
 {
     qmoe_ws_layout l;
     qmoe_status st = qmoe_moe_layer_ws_layout(n_experts, d_model, d_ff, n_tokens, &l);
@@ -622,14 +656,14 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     // With both kinds present the scalar chain goes to a side stream that forks from
     // `stream` after the dispatch and joins it again at the end, so the kernels fill each
     // other's idle compute units; the caller sees the usual stream order.
-    const bool overlap = mm && tuning().overlap >= 0 && (phases & 6) && (phases & 24);
+    const bool overlap = side && mm && tuning().overlap >= 0 && (phases & 6) && (phases & 24);
     hipStream_t s_scalar = s;
-    SideStream side;
+    SideStream ss;
     if (overlap) {
-        if ((st = side_stream(&side)) != QMOE_OK) return st;
-        s_scalar = side.stream;
-        QMOE_HIP_TRY(hipEventRecord(side.fork, s));
-        QMOE_HIP_TRY(hipStreamWaitEvent(s_scalar, side.fork, 0));
+        if ((st = side_stream(static_cast<hipStream_t>(side_stream_arg), &ss)) != QMOE_OK) return st;
+        s_scalar = ss.stream;
+        QMOE_HIP_TRY(hipEventRecord(ss.fork, s));
+        QMOE_HIP_TRY(hipStreamWaitEvent(s_scalar, ss.fork, 0));
     }
     ProductArgs a{};
     fill_tables(d, &a, code_order);
@@ -698,10 +732,42 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
     if (phases & 4)
         if ((st = launch_product(a2, pwo, run, s_scalar)) != QMOE_OK) return st;
     if (overlap) {
-        QMOE_HIP_TRY(hipEventRecord(side.join, s_scalar));
-        QMOE_HIP_TRY(hipStreamWaitEvent(s, side.join, 0));
+        QMOE_HIP_TRY(hipEventRecord(ss.join, s_scalar));
+        QMOE_HIP_TRY(hipStreamWaitEvent(s, ss.join, 0));
     }
     return QMOE_OK;
+}
+
+}  // namespace
+
+qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
+                                   int code_order, int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
+                                   const int32_t *expert_idx, const float *gate, int n_tokens, float *y,
+                                   void *workspace, size_t workspace_bytes, void *stream, void *side_stream)
+{
+    return layer_forward(d, wi, wo, code_order, n_experts, d_model, d_ff, x_bf16, expert_idx, gate, n_tokens, y,
+                         workspace, workspace_bytes, stream, 1, side_stream);
+}
+
+size_t qmoe_static_workspace_bytes(void) { return kStaticWsBytes; }
+
+qmoe_status qmoe_moe_layer_forward_static(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
+                                          int code_order, int n_experts, int d_model, int d_ff,
+                                          const uint16_t *x_bf16, const int32_t *expert_idx, const float *gate,
+                                          int n_tokens, float *y, void *stream)
+{
+    qmoe_ws_layout l;
+    const qmoe_status st = qmoe_moe_layer_ws_layout(n_experts, d_model, d_ff, n_tokens, &l);
+    if (st != QMOE_OK) return st;
+    if (!d || !wi || !wo || !x_bf16 || !expert_idx || !y) return QMOE_E_INVALID_ARG;
+    if (!d->dev) return QMOE_E_NO_DEVICE_DICT;
+    if (l.total > kStaticWsBytes) return QMOE_E_LIMIT;
+    void *ws = nullptr;
+    const qmoe_status wst = static_workspace(&ws);
+    if (wst != QMOE_OK) return wst;
+    // one stream, no events: nothing here creates a stream, an event or memory
+    return layer_forward(d, wi, wo, code_order, n_experts, d_model, d_ff, x_bf16, expert_idx, gate, n_tokens, y, ws,
+                         kStaticWsBytes, stream, 0, nullptr);
 }
 
 qmoe_status qmoe_bf16_layer_forward(const uint16_t *const *wi_dense, const uint16_t *const *wo_dense,

@@ -128,9 +128,15 @@ class DeviceLayer:
         return torch.empty(n, dtype=torch.uint8, device=self.device)
 
     def forward(self, dd: DeviceDict, x_bf16: torch.Tensor, expert_idx: torch.Tensor, y: torch.Tensor,
-                workspace: torch.Tensor, gate: torch.Tensor | None = None, stream=None):
+                workspace: torch.Tensor, gate: torch.Tensor | None = None, stream=None, side_stream=None):
         B.qmoe_moe_layer_forward(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.format, self.n_experts,
-                                 self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, workspace, stream)
+                                 self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, workspace, stream, side_stream)
+
+    def forward_static(self, dd: DeviceDict, x_bf16: torch.Tensor, expert_idx: torch.Tensor, y: torch.Tensor,
+                       gate: torch.Tensor | None = None, stream=None):
+        """The same layer on the library's own bounded scratch array (no workspace, nothing allocated)."""
+        B.qmoe_moe_layer_forward_static(dd.handle, self.desc_dev["wi"], self.desc_dev["wo"], self.format,
+                                        self.n_experts, self.d_model, self.d_ff, x_bf16, expert_idx, gate, y, stream)
 
 
 def read_workspace(workspace: torch.Tensor, n_experts: int, d_model: int, d_ff: int, n_tokens: int):

@@ -204,7 +204,9 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(lib_dict):
     assert L.qmoe_decode_matvec(lib_dict, ctypes.byref(W), 256, 1, 256, None) == -9     # pairs alone are enough
     assert L.qmoe_moe_dispatch(lib_dict, 4, 256, 4, 4, 8, 16, 256, 1 << 30, None) == -1  # unknown format bit
     assert L.qmoe_decompress(lib_dict, 256, 5, 2, 8, 16, 0, 256, None) == -1
-    assert L.qmoe_moe_layer_forward(lib_dict, 256, 256, 0, 4, 8, 16, 256, 256, None, 4, 256, None, 0, None) == -9
+    assert L.qmoe_moe_layer_forward(lib_dict, 256, 256, 0, 4, 8, 16, 256, 256, None, 4, 256, None, 0, None, None) == -9
+    assert L.qmoe_moe_layer_forward_static(lib_dict, 256, 256, 0, 4, 8, 16, 256, 256, None, 4, 256, None) == -9
+    assert L.qmoe_static_workspace_bytes() == 8 << 20
     assert L.qmoe_codes_to_device_order(lib_dict, 256, 10, None) == -9
     assert L.qmoe_codes_to_device_order(lib_dict, None, 10, None) == -1
     assert L.qmoe_dict_upload(lib_dict, None, 0, None) == -1
