@@ -27,8 +27,16 @@ MAX_PAIRS_DEFAULT = 14  # Section 4.3.2: at most 14 pairs per sequence
 N_ENTRIES_DEFAULT = 1 << 16
 
 
+# ORACLE_SANITIZE=1: the same source built with AddressSanitizer and UndefinedBehaviorSanitizer
+# (the process must then preload gcc's libasan; tests/test_sanitizers.py does that in a child)
+_SANITIZE = os.environ.get("ORACLE_SANITIZE") == "1"
+if _SANITIZE:
+    _SO = os.path.join(_HERE, "libqmoe_oracle_san.so")
+
+
 def build() -> str:
-    subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", _SO, _SRC, "-lm"])
+    flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if _SANITIZE else ["-O2"]
+    subprocess.check_call(["gcc", *flags, "-fPIC", "-shared", "-o", _SO, _SRC, "-lm"])
     return _SO
 
 

@@ -57,11 +57,15 @@ def lib():
     __graft_entry__.build(), after editing them): figures from a stale binary describe old code."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
-            _build.build_library()
-        elif _build.stale():
-            raise RuntimeError(f"{_build.LIB} is older than its sources: rebuild it (python paper_2310_16795_amd/build.py)")
-        L = ctypes.CDLL(_build.LIB)
+        path = os.environ.get("QMOE_LIBRARY")  # another build of the same sources, e.g. one with host sanitizers
+        if not path:
+            path = _build.LIB
+            if not os.path.exists(path):
+                _build.build_library()
+            elif _build.stale():
+                raise RuntimeError(f"{path} was built from other sources than the ones present: rebuild it "
+                                   "(python paper_2310_16795_amd/build.py)")
+        L = ctypes.CDLL(path)
         vp, sz, i = c_void_p, c_size_t, c_int
         L.qmoe_strerror.argtypes, L.qmoe_strerror.restype = [i], c_char_p
         L.qmoe_last_hip_error.argtypes, L.qmoe_last_hip_error.restype = [], i
