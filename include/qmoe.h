@@ -198,7 +198,49 @@ typedef struct qmoe_matrix {
                                   numbering (after qmoe_codes_to_device_order)          */
     const uint16_t *minmax_bf16; /* NULL, or [rows][2] bfloat16 (w_min, w_max) of each
                                   output row, 4-byte aligned                            */
+    const uint32_t *wave_off;  /* lane-interleaved layout (below): [lanes/64 + 1] first
+                                  16-byte piece of each group of 64 lanes; else NULL     */
+    uint32_t lanes;            /* lane-interleaved layout: the lane count it was built
+                                  for; 0 = rows back to back (the interchange layout)   */
+    uint32_t reserved;         /* 0 */
 } qmoe_matrix;
+
+/*
+ * Lane-interleaved device layout of a stream (a load-time re-packing, like the device
+ * numbering; the paper's kernel reads 32 consecutive codewords of one row with one coalesced
+ * transaction, Section 4.3.3 "Execution" -- this is the same for a kernel that gives every
+ * lane a row range of its own).  The rows of a matrix are dealt evenly over `lanes` lanes
+ * (lane g owns rows g*b + min(g, x) .. with b = rows / lanes, x = rows % lanes: the first x
+ * lanes own b + 1 rows), a lane's codewords are cut into pieces of 8 (16 bytes, the last one
+ * zero-padded), and the pieces of each group of 64 consecutive lanes are interleaved: piece p
+ * of lane g is piece number wave_off[g / 64] + 64 p + g % 64 of the buffer, so that the 64
+ * loads of a wavefront are 1 KiB of consecutive memory.  A group is as long as its longest
+ * lane (shorter lanes are padded).  Same codewords, same order inside a lane; row_off keeps
+ * its meaning (codeword counts), codes points to the pieces, n_codes is 8 * n_pieces.  The
+ * padding is part of the compressed size: report 16 * n_pieces bytes, not 2 * row_off[rows].
+ * Only the layer calls and qmoe_decompress read this layout, and only when their launch uses
+ * exactly `lanes` lanes per matrix: pass the lane counts in the format argument
+ * (QMOE_FORMAT_LANES) -- qmoe_plan_lanes gives the count the planner would pick.
+ *   qmoe_lane_layout_size    number of 16-byte pieces the layout takes
+ *   qmoe_lane_layout_build   codes (host, interchange or device numbering) -> out (host, 8 *
+ *                            out_pieces codewords), wave_off (host [lanes/64 + 1])
+ *   qmoe_lane_layout_unpack  the inverse (the layout round-trips)
+ * lanes: a multiple of 64, 64 .. 16320.  Errors: INVALID_ARG, BUFFER_TOO_SMALL,
+ * CORRUPT_STREAM (offsets that decrease), LIMIT (more than 2^32 - 1 pieces).
+ */
+qmoe_status qmoe_lane_layout_size(const uint32_t *row_off /*host [rows+1]*/, int rows, int lanes, size_t *n_pieces);
+qmoe_status qmoe_lane_layout_build(const uint16_t *codes /*host*/, const uint32_t *row_off /*host [rows+1]*/, int rows,
+                                   int lanes, uint16_t *out /*host*/, size_t out_pieces,
+                                   uint32_t *wave_off /*host [lanes/64 + 1]*/);
+qmoe_status qmoe_lane_layout_unpack(const uint16_t *pieces /*host*/, const uint32_t *wave_off /*host*/,
+                                    const uint32_t *row_off /*host [rows+1]*/, int rows, int lanes,
+                                    uint16_t *codes /*host*/, size_t codes_cap);
+/*
+ * Lanes per matrix that a layer call over n_experts experts and about n_tokens tokens would
+ * use for a rows x cols projection of dictionary d (needs the GPU: the answer depends on its
+ * LDS size); 0 on error.  Build the lane-interleaved layout of that projection for this count.
+ */
+int qmoe_plan_lanes(const qmoe_dict *d, int rows, int cols, int n_experts, int n_tokens);
 
 /*
  * Format bits for the calls whose matrix descriptors live in device memory (the host
@@ -208,6 +250,10 @@ typedef struct qmoe_matrix {
 #define QMOE_FORMAT_DEVICE_ORDER 1 /* every stream uses the device numbering              */
 #define QMOE_FORMAT_GRID_MINMAX 2  /* every matrix is on the asymmetric grid: the kernels
                                       read minmax_bf16 (a NULL there decodes to zeros)    */
+/* every matrix is in the lane-interleaved layout, built for lanes_wi lanes (first product's
+   matrices; the only ones of qmoe_decompress) and lanes_wo lanes (second product's); needs
+   QMOE_FORMAT_DEVICE_ORDER */
+#define QMOE_FORMAT_LANES(lanes_wi, lanes_wo) ((((lanes_wi) / 64) << 8) | (((lanes_wo) / 64) << 16))
 
 /*
  * Rewrite a codeword stream in device memory, in place, from the interchange numbering

@@ -10,5 +10,6 @@ from ._binding import (  # noqa: F401
     qmoe_codes_to_device_order, qmoe_decompress, qmoe_encode_device, qmoe_dict_device_bytes, qmoe_dict_device_order, qmoe_dict_from_words, qmoe_dict_max_nonzeros, qmoe_dict_upload, qmoe_dict_words,
     qmoe_encode_host, qmoe_moe_dispatch, qmoe_moe_layer_forward, qmoe_moe_layer_workspace,
     qmoe_moe_layer_ws_layout, qmoe_set_tuning, qmoe_stream_copy, qmoe_validate_host, qmoe_hook_set,
-    qmoe_moe_layer_forward_static, qmoe_static_workspace_bytes,
+    qmoe_moe_layer_forward_static, qmoe_static_workspace_bytes, qmoe_lane_layout_build, qmoe_lane_layout_unpack,
+    qmoe_plan_lanes, format_lanes,
 )

@@ -30,7 +30,7 @@ class QmoeError(RuntimeError):
 class qmoe_matrix(Structure):
     _fields_ = [("codes", c_void_p), ("row_off", c_void_p), ("scale_f16", c_void_p),
                 ("rows", c_int32), ("cols", c_int32), ("n_codes", c_uint32), ("code_order", c_uint32),
-                ("minmax_bf16", c_void_p)]
+                ("minmax_bf16", c_void_p), ("wave_off", c_void_p), ("lanes", c_uint32), ("reserved", c_uint32)]
 
 
 FORMAT_DEVICE_ORDER = 1
@@ -48,6 +48,7 @@ EXPORTS = [
     "qmoe_moe_layer_ws_layout", "qmoe_moe_layer_workspace", "qmoe_moe_layer_forward", "qmoe_moe_dispatch",
     "qmoe_bf16_layer_forward", "qmoe_set_tuning", "qmoe_stream_copy", "qmoe_dict_device_order",
     "qmoe_codes_to_device_order", "qmoe_decompress", "qmoe_encode_device", "qmoe_hook_set", "qmoe_static_workspace_bytes", "qmoe_moe_layer_forward_static",
+    "qmoe_lane_layout_size", "qmoe_lane_layout_build", "qmoe_lane_layout_unpack", "qmoe_plan_lanes",
 ]
 
 
@@ -92,6 +93,10 @@ def lib():
         L.qmoe_encode_device.argtypes = [vp, vp, i, i, vp, sz, vp, vp, vp]
         L.qmoe_bf16_layer_forward.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, sz, vp]
         L.qmoe_set_tuning.argtypes = [c_char_p, i]
+        L.qmoe_lane_layout_size.argtypes = [vp, i, i, POINTER(sz)]
+        L.qmoe_lane_layout_build.argtypes = [vp, vp, i, i, vp, sz, vp]
+        L.qmoe_lane_layout_unpack.argtypes = [vp, vp, vp, i, i, vp, sz]
+        L.qmoe_plan_lanes.argtypes = [vp, i, i, i, i]
         L.qmoe_hook_set.argtypes = [c_char_p, i]
         L.qmoe_stream_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
@@ -318,6 +323,41 @@ def qmoe_bf16_layer_forward(wi_ptrs, wo_ptrs, n_experts: int, d_model: int, d_ff
 
 def qmoe_set_tuning(key: str, value: int) -> None:
     _check(lib().qmoe_set_tuning(key.encode(), int(value)), "qmoe_set_tuning")
+
+
+def format_lanes(lanes_wi: int, lanes_wo: int) -> int:
+    """QMOE_FORMAT_LANES: the lane counts the lane-interleaved layouts of the two projections were built for."""
+    return ((lanes_wi // 64) << 8) | ((lanes_wo // 64) << 16)
+
+
+def qmoe_plan_lanes(d: int, rows: int, cols: int, n_experts: int, n_tokens: int) -> int:
+    n = lib().qmoe_plan_lanes(d, rows, cols, n_experts, n_tokens)
+    if n <= 0:
+        raise QmoeError(-1, "qmoe_plan_lanes")
+    return n
+
+
+def qmoe_lane_layout_build(codes: np.ndarray, row_off: np.ndarray, rows: int, lanes: int):
+    """-> (pieces uint16 [8 * n_pieces], wave_off uint32 [lanes / 64 + 1])"""
+    c = np.ascontiguousarray(codes, dtype=np.uint16)
+    r = np.ascontiguousarray(row_off, dtype=np.uint32)
+    n = c_size_t(0)
+    _check(lib().qmoe_lane_layout_size(_host_ptr(r), rows, lanes, byref(n)), "qmoe_lane_layout_size")
+    out = np.empty(8 * max(n.value, 1), dtype=np.uint16)
+    wave_off = np.zeros(lanes // 64 + 1, dtype=np.uint32)
+    _check(lib().qmoe_lane_layout_build(_host_ptr(c), _host_ptr(r), rows, lanes, _host_ptr(out), n.value,
+                                        _host_ptr(wave_off)), "qmoe_lane_layout_build")
+    return out[: 8 * n.value], wave_off
+
+
+def qmoe_lane_layout_unpack(pieces: np.ndarray, wave_off: np.ndarray, row_off: np.ndarray, rows: int, lanes: int):
+    p = np.ascontiguousarray(pieces, dtype=np.uint16)
+    w = np.ascontiguousarray(wave_off, dtype=np.uint32)
+    r = np.ascontiguousarray(row_off, dtype=np.uint32)
+    codes = np.empty(max(int(r[rows]), 1), dtype=np.uint16)
+    _check(lib().qmoe_lane_layout_unpack(_host_ptr(p), _host_ptr(w), _host_ptr(r), rows, lanes, _host_ptr(codes),
+                                         codes.size), "qmoe_lane_layout_unpack")
+    return codes[: int(r[rows])]
 
 
 def qmoe_hook_set(key: str, value: int) -> None:

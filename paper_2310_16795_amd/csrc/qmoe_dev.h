@@ -317,14 +317,22 @@ __device__ __forceinline__ void stage_x_tile(uint16_t *xs_w, const uint16_t *xba
 // bits of every code flip the sign bits of fields 1 and 2; the single entries are stored
 // with those flips already applied once, so that the second application restores them
 // and no case distinction is needed.
+// What the two low bits of a device-order code flip in its entry: bit 0 -> bit 18, bit 1 -> bit 26
+// (the sign bits of fields 1 and 2).  Written as one shift-or instruction: left to itself the
+// compiler turns the two shifts into a 32-bit multiply, which runs at a quarter of the rate.
+__device__ __forceinline__ uint32_t order_flips(uint32_t code)
+{
+    const uint32_t two = code & 3u;
+    uint32_t f;
+    asm("v_lshl_or_b32 %0, %1, 25, %2" : "=v"(f) : "v"(two), "v"(two << 18));
+    return f & ((1u << 18) | (1u << 26));
+}
+
 template <typename TablePtr>
 __device__ __forceinline__ uint32_t order_entry(TablePtr table, uint32_t code, uint32_t n_groups, uint32_t n_order)
 {
     const uint32_t u = max(code >> 2, __builtin_elementwise_sub_sat(code, 3u * n_groups));
-    // bit 0 -> bit 18, bit 1 -> bit 26 (two shifts and a mask: a 32-bit multiply runs at a quarter of the rate)
-    const uint32_t two = code & 3u;
-    const uint32_t flips = ((two << 18) | (two << 25)) & ((1u << 18) | (1u << 26));
-    return table[min(u, n_order - 1u)] ^ flips;
+    return table[min(u, n_order - 1u)] ^ order_flips(code);
 }
 
 // The same look-up for the two codewords held in one 32-bit word of the stream.  The
@@ -428,7 +436,8 @@ __device__ __forceinline__ int entry_len(const Entry &e)
 
 // activations of one column for the tokens of the tile: bf16 in LDS -> fp32.
 // `rec8` is 8 * column.  One token: 8-byte records, +x in the second 16-bit slot;
-// 2 / 4 / 8 tokens: packed, 4 / 8 / 16 bytes per column.
+// 2 / 4 / 8 tokens: packed, 8 / 8 / 16 bytes per column (a tile of two is staged as a
+// tile of four whose last two tokens are not read).
 template <int TBI>
 __device__ __forceinline__ void lds_load_x(uint32_t xs_addr, uint32_t rec8, float (&v)[TBI])
 {
@@ -436,7 +445,7 @@ __device__ __forceinline__ void lds_load_x(uint32_t xs_addr, uint32_t rec8, floa
     if constexpr (TBI == 1) {
         v[0] = __uint_as_float((uint32_t)(*(lp_u16)(uintptr_t)(xs_addr + rec8 + 2u)) << 16);
     } else if constexpr (TBI == 2) {
-        const uint32_t u = *(p32)(uintptr_t)(xs_addr + (rec8 >> 1));
+        const uint32_t u = *(p32)(uintptr_t)(xs_addr + rec8);
         v[0] = __uint_as_float(u << 16); v[1] = __uint_as_float(u & 0xFFFF0000u);
     } else if constexpr (TBI == 4) {
         p32 p = (p32)(uintptr_t)(xs_addr + rec8);
@@ -499,6 +508,57 @@ __device__ __forceinline__ void accumulate(const Entry &e, uint32_t xs_addr, uin
                     for (int t = 0; t < TBI; t++) acc[TBI + t] = fmaf(wa, xv[t], acc[TBI + t]);
                 }
             }
+        }
+    }
+}
+
+// The same for a run entry and a tile of 2, 4 or 8 tokens, without widening a value: the
+// gathered words hold two tokens' bf16 activations of one column each; a byte permute pairs the
+// values that fields 1 and 2 select for one token, and one packed dot product multiplies
+// them with the two weights, which are made from the entry's weight bits as bf16 +-2.0 or 0
+// (bit 14 = non-zero, bit 15 = negative: 0x4000 / 0xC000): the sums come out doubled, exactly,
+// and the caller halves the row scale.  Field 0 takes a dot product with (weight, 0) and
+// (0, weight).  Per codeword: three gathers, TBI / 2 * 2 permutes and 2 * TBI dot products.
+template <int TBI, int ASYM = 0>
+__device__ __forceinline__ void accumulate_tile(uint32_t e0, uint32_t xs_addr, uint32_t pos8,
+                                                float (&acc)[TBI * (1 + ASYM)])
+{
+    static_assert(TBI == 2 || TBI == 4 || TBI == 8, "tile sizes");
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef const __attribute__((address_space(3))) uint32_t *p32;
+    constexpr int NW = TBI / 2;             // words per column that are read
+    const uint32_t ec = e0 & 0xF8F8F800u;   // byte 1 + z: 8 * position of field z
+    const uint32_t t5 = e0 << 5;
+    uint32_t w[3];                          // weight pairs: (field 1, field 2), (field 0, 0), (0, field 0)
+    w[0] = (t5 & 0xC0000000u) | ((e0 >> 3) & 0x0000C000u);
+    w[1] = t5 & 0x0000C000u;
+    w[2] = w[1] << 16;
+    uint32_t g[3][NW];
+#pragma unroll
+    for (int z = 0; z < 3; z++) {
+        const uint32_t at = pos8 + ((ec >> (8 + 8 * z)) & 0xFFu);
+        p32 p = (p32)(uintptr_t)(xs_addr + (TBI == 8 ? 2u * at : at));
+#pragma unroll
+        for (int k = 0; k < NW; k++) g[z][k] = p[k];
+    }
+    auto dot = [](uint32_t x2, uint32_t w2, float c) -> float {
+        bf16x2 a, b;
+        __builtin_memcpy(&a, &x2, 4);
+        __builtin_memcpy(&b, &w2, 4);
+        return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false);
+    };
+#pragma unroll
+    for (int k = 0; k < NW; k++) {
+        // {g2, g1} as eight bytes: g1 = bytes 0..3, g2 = bytes 4..7
+        const uint32_t even = __builtin_amdgcn_perm(g[2][k], g[1][k], 0x05040100u);  // token 2k: (field 1, field 2)
+        const uint32_t odd = __builtin_amdgcn_perm(g[2][k], g[1][k], 0x07060302u);   // token 2k + 1
+        acc[2 * k] = dot(g[0][k], w[1], dot(even, w[0], acc[2 * k]));
+        acc[2 * k + 1] = dot(g[0][k], w[2], dot(odd, w[0], acc[2 * k + 1]));
+        if constexpr (ASYM) {
+            // the same inputs under |weight|
+            const uint32_t m = 0x40004000u;
+            acc[TBI + 2 * k] = dot(g[0][k], w[1] & m, dot(even, w[0] & m, acc[TBI + 2 * k]));
+            acc[TBI + 2 * k + 1] = dot(g[0][k], w[2] & m, dot(odd, w[0] & m, acc[TBI + 2 * k + 1]));
         }
     }
 }

@@ -418,6 +418,80 @@ qmoe_status qmoe_validate_host(const qmoe_dict *d, const uint16_t *codes, const 
     return QMOE_OK;
 }
 
+// ---- lane-interleaved device layout of a codeword stream (see include/qmoe.h) ----
+namespace {
+
+// rows [*ra, *rb) of lane g when `rows` rows are dealt evenly over `lanes` lanes
+inline void lane_rows(int rows, int lanes, int g, int *ra, int *rb)
+{
+    const int base = rows / lanes, extra = rows - base * lanes;
+    *ra = g * base + std::min(g, extra);
+    *rb = *ra + base + (g < extra ? 1 : 0);
+}
+
+qmoe_status lane_layout_walk(const uint32_t *row_off, int rows, int lanes, uint32_t *wave_off, size_t *n_pieces)
+{
+    if (!row_off || rows < 1 || lanes < 64 || (lanes % 64) || lanes > 16320) return QMOE_E_INVALID_ARG;
+    unsigned long long total = 0;
+    for (int w = 0; w < lanes / 64; w++) {
+        if (wave_off) wave_off[w] = (uint32_t)total;
+        uint32_t most = 0;
+        for (int g = 64 * w; g < 64 * w + 64; g++) {
+            int ra, rb;
+            lane_rows(rows, lanes, g, &ra, &rb);
+            if (row_off[rb] < row_off[ra]) return QMOE_E_CORRUPT_STREAM;
+            most = std::max(most, (row_off[rb] - row_off[ra] + 7u) / 8u);
+        }
+        total += 64ull * most;
+        if (total > 0xFFFFFFFFull) return QMOE_E_LIMIT;
+    }
+    if (wave_off) wave_off[lanes / 64] = (uint32_t)total;
+    *n_pieces = (size_t)total;
+    return QMOE_OK;
+}
+
+}  // namespace
+
+qmoe_status qmoe_lane_layout_size(const uint32_t *row_off, int rows, int lanes, size_t *n_pieces)
+{
+    if (!n_pieces) return QMOE_E_INVALID_ARG;
+    return lane_layout_walk(row_off, rows, lanes, nullptr, n_pieces);
+}
+
+qmoe_status qmoe_lane_layout_build(const uint16_t *codes, const uint32_t *row_off, int rows, int lanes, uint16_t *out,
+                                   size_t out_pieces, uint32_t *wave_off)
+{
+    if (!codes || !out || !wave_off) return QMOE_E_INVALID_ARG;
+    size_t need = 0;
+    const qmoe_status st = lane_layout_walk(row_off, rows, lanes, wave_off, &need);
+    if (st != QMOE_OK) return st;
+    if (out_pieces < need) return QMOE_E_BUFFER_TOO_SMALL;
+    std::memset(out, 0, 16 * need);
+    for (int g = 0; g < lanes; g++) {
+        int ra, rb;
+        lane_rows(rows, lanes, g, &ra, &rb);
+        const uint32_t k0 = row_off[ra], n = row_off[rb] - k0;
+        const size_t first = (size_t)wave_off[g / 64] + (size_t)(g % 64);  // piece p of the lane sits at first + 64 p
+        for (uint32_t i = 0; i < n; i++) out[8 * (first + 64 * (size_t)(i / 8)) + (i % 8)] = codes[k0 + i];
+    }
+    return QMOE_OK;
+}
+
+qmoe_status qmoe_lane_layout_unpack(const uint16_t *pieces, const uint32_t *wave_off, const uint32_t *row_off, int rows,
+                                    int lanes, uint16_t *codes, size_t codes_cap)
+{
+    if (!pieces || !wave_off || !row_off || !codes || rows < 1 || lanes < 64 || (lanes % 64)) return QMOE_E_INVALID_ARG;
+    if (codes_cap < row_off[rows]) return QMOE_E_BUFFER_TOO_SMALL;
+    for (int g = 0; g < lanes; g++) {
+        int ra, rb;
+        lane_rows(rows, lanes, g, &ra, &rb);
+        const uint32_t k0 = row_off[ra], n = row_off[rb] - k0;
+        const size_t first = (size_t)wave_off[g / 64] + (size_t)(g % 64);
+        for (uint32_t i = 0; i < n; i++) codes[k0 + i] = pieces[8 * (first + 64 * (size_t)(i / 8)) + (i % 8)];
+    }
+    return QMOE_OK;
+}
+
 qmoe_status qmoe_set_tuning(const char *key, int value)
 {
     if (!key) return QMOE_E_INVALID_ARG;

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
             auto row_of = [&](int t) { return slot0 + t; };
             switch (tbi) {
             case 1: stage_x_one(xs_w, a.x + (size_t)slot0 * a.ldx, a.cols, true, false); break;  // lds_load_x<1> reads the +x slot
-            case 2: stage_x_tile<2>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            case 2: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;  // eight bytes per column as well
             case 4: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             default: stage_x_tile<8>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             }

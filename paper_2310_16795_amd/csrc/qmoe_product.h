@@ -39,6 +39,7 @@ struct RowSink {
     const __attribute__((address_space(3))) int *tok_ids;   // output token of each tile slot
     const __attribute__((address_space(3))) float *gate_s;  // gate of each tile slot
     int ntok, slot0;
+    float acc_unit;   // what one unit of a running sum stands for: 1, or 0.5 where the weights were applied as +-2
     uint32_t out_s;   // LDS byte address of the block's staged results [tile][out_rows] (bf16 or fp32), 0 = none
     int out_rows;     // rows of the block
     float gate0;      // gate of tile slot 0
@@ -65,6 +66,8 @@ __device__ __forceinline__ void write_row(const ProductArgs &a, const LaneState<
     } else {
         scale = half_bits_to_float(rs.scale_s[st.row - rs.r0]);
     }
+    scale *= rs.acc_unit;  // exact: a power of two
+    mid *= rs.acc_unit;
 #pragma unroll
     for (int t = 0; t < TBI; t++) {
         if (t < rs.ntok) {
@@ -177,7 +180,10 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
             const uint32_t rec = pos[j];  // the activations begin at LDS address 0 (the caller checks)
 #pragma unroll
             for (int z = 0; z < 3; z++) {
-                const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
+                uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
+#ifdef QMOE_PROBE_NOCONFLICT
+                addr = (addr & ~0xFCu) | ((threadIdx.x & 63u) << 2);  // timing probe only: every lane on a bank of its own (wrong numbers)
+#endif
                 x[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)addr);
                 // the -x slot is 4 bytes after the +x slot; an unused field stays on the zero slot
                 if constexpr (ASYM) xa[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)(addr & ~4u));
@@ -206,10 +212,19 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
                 part[j][NA - 1] = st.acc[NA - 1];
             }
         }
+#ifdef QMOE_SCHED_INTERLEAVE
+        // experiment: one LDS read, then QMOE_SCHED_INTERLEAVE vector instructions, over and over
+#pragma unroll
+        for (int i_ = 0; i_ < 32; i_++) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, QMOE_SCHED_INTERLEAVE, 0);
+        }
+#endif
     } else {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            accumulate<TBI, DICT, ASYM>(e[j], xs_addr, pos[j], st.acc);
+            if constexpr (DICT != kDictWords) accumulate_tile<TBI, ASYM>(e[j].e0, xs_addr, pos[j], st.acc);
+            else accumulate<TBI, DICT, ASYM>(e[j], xs_addr, pos[j], st.acc);
 #pragma unroll
             for (int t = 0; t < NA; t++) part[j][t] = st.acc[t];
         }
@@ -274,8 +289,12 @@ __device__ __forceinline__ void lookup8(const ProductArgs &a, const u32x4 &v, lp
 // entries are fetched eight codewords ahead of their use.
 template <int TBI, int DICT, int EPI, int ASYM>
 __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_matrix &M, int blk,
-                                              uint32_t xs_addr, const RowSink &rs, lp_u32 lds_run)
+                                              uint32_t xs_addr, const RowSink &rs_in, lp_u32 lds_run)
 {
+    const bool fast = DICT != kDictWords && a.cols > 224 && (TBI != 1 || xs_addr == 0u);
+    RowSink rs = rs_in;
+    // token tiles on the fast form apply the weights as +-2 (see accumulate_tile)
+    rs.acc_unit = (fast && TBI != 1) ? 0.5f : 1.0f;
     const int nlanes = (int)blockDim.x * a.blocks_per_pass;
     const int gl = blk * (int)blockDim.x + (int)threadIdx.x;
     const int base_rows = a.rows / nlanes, extra = a.rows - base_rows * nlanes;
@@ -314,7 +333,6 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     // Piece p + 2 is being loaded and the entries of piece p + 1 looked up while piece p
     // is applied.
     const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(my_pieces - 1, 0);
-    const bool fast = DICT != kDictWords && a.cols > 224 && (TBI != 1 || xs_addr == 0u);
     auto load_piece = [&](int p) -> u32x4 {
         // lanes past their own end re-read their last piece (its slots are masked out below)
         const uintptr_t at = chunk + 16u * (uintptr_t)p;
@@ -493,7 +511,7 @@ __global__ __launch_bounds__(kProductMaxThreads) void k_product(const ProductArg
             auto row_of = [&](int t) { return x_rows[t]; };
             switch (tbi) {
             case 1: stage_x_one(xs_w, a.x + (size_t)x_rows[0] * a.ldx, a.cols, ntok > 0, true); break;
-            case 2: stage_x_tile<2>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
+            case 2: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;  // eight bytes per column as well
             case 4: stage_x_tile<4>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             default: stage_x_tile<8>(xs_w, a.x, row_of, ntok, a.ldx, a.cols); break;
             }
@@ -527,6 +545,7 @@ __global__ __launch_bounds__(kProductMaxThreads) void k_product(const ProductArg
         rs.out_s = staged ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)out_w : 0u;
         rs.out_rows = (r1 - r0 + 7) & ~7;
         rs.gate0 = gate_s[0];
+        rs.acc_unit = 1.0f;
         switch (tbi) {
         case 1: product_block<1, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;
         case 2: product_block<2, DICT, EPI, ASYM>(a, M, blk, xs_addr, rs, lds_run); break;

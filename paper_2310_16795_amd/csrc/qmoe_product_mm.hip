@@ -9,7 +9,7 @@ namespace {
 // ---------------------------------------------------------------- matrix-core product for crowded experts
 //
 // An expert with many tokens is a dense contraction once its ternary weights are
-// in hand: y[token][row] = sum_k x[token][k] * W[row][k].  The scalar kernel above
+// in hand: y[token][row] = sum_k x[token][k] * W[row][k].  The scalar kernel
 // would decode the matrix again for every few tokens; this one decodes it once per
 // tile of up to 64 tokens.  A workgroup owns up to 512 rows (one lane per row) and
 // walks the columns 64 at a time.  Every lane keeps a ring of 128 one-byte columns
@@ -17,18 +17,17 @@ namespace {
 // the ring allows (so the lanes of a wavefront, whose codewords end at different
 // columns, seldom wait for each other); then each wavefront multiplies the 64
 // columns that are complete, for the 64 rows its own lanes decoded, with the
-// tokens' activations (staged in LDS, shared by all wavefronts) on the matrix
-// cores: D[token][row] += X[token][k] * W^T[k][row], fp32 accumulators in
-// registers.  The ring holds the weights as the high byte of bf16 +-2.0 (0x40 /
-// 0xC0, low byte zero), expanded to bf16 by a byte permute when a fragment is
-// read; the factor 2 is taken out again, exactly, when a row is written.
+// tokens' activations on the matrix cores, fp32 accumulators in registers.  The
+// ring holds the weights as the high byte of bf16 +-2.0 (0x40 / 0xC0, low byte
+// zero), expanded to bf16 by a byte permute when a fragment is read; the factor 2
+// is taken out again, exactly, when a row is written.
 // Only device-order streams (whole table in LDS) take this path.
 
 constexpr int kMmKc = 64;                      // columns per step
 constexpr int kMmRing = 2 * kMmKc;             // columns a lane's ring holds
-constexpr int kMmAhead = kMmRing - 28;         // a codeword may start this far past the step's first column
-constexpr int kMmWRowBytes = kMmRing + 8;      // 34 banks per row: 16 consecutive rows read 8 bytes each without conflict
-constexpr int kMmXRowBytes = 2 * kMmKc + 16;   // 36 banks per row: 8 consecutive rows read 16 bytes each without conflict
+constexpr int kMmAhead = kMmRing - 28 - 1;     // a codeword may start this far past the step's first column (its run then ends
+                                               // below column kc + 128, the first one that shares a ring byte with the step)
+constexpr int kMmWRowBytes = kMmRing + 16;     // 36 banks per row: 16 consecutive rows read 16 bytes each (two lanes, 8 bytes apiece) without conflict
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -177,135 +176,245 @@ __device__ __forceinline__ void lds_barrier()
         }                                                                                               \
     } while (__any(left != 0u && pos < kend))
 
-// MB: 32-token blocks in the tile (1 or 2).  wt / xt: LDS byte addresses of the weight
-// rings and the two activation buffers.
+// ---- the matrix-core product ----
+//
+// Every wavefront works on its own: its 64 lanes decode 64 consecutive rows into their rings,
+// and when all of them have passed the next 64 columns the wavefront multiplies those 64 x 64
+// weights with the tile's activations, which every lane fetches straight from global memory
+// in the layout the matrix cores want (a token's 8 consecutive columns = one 16-byte load;
+// the eight wavefronts of a workgroup read the same lines, which the caches serve).  No
+// workgroup barrier inside an item.
+//
+// The decoder: a lane's codewords pass through a window of two 16-byte pieces in LDS (the
+// next piece is in flight in a register); the codeword three places ahead is read from the
+// window, the table entry two places ahead is looked up, while the current entry is applied.
+// All of it sits under the lane's own "go" predicate -- a lane goes when it has codewords left,
+// its next run fits the ring (it starts at most kMmAhead columns past the step's first column)
+// and the window holds the codeword three places ahead -- so lanes that sit out issue nothing.
+// Applying an entry is three one-byte stores: field z goes to ring column (column + position)
+// mod 128 with the value bits of the field shifted to the top of the byte (0x40: +2.0, 0xC0:
+// -2.0 as the high byte of bf16, 0 for an unused field, which comes first and so writes its
+// zero at the run's first column before any real weight of the same run).
+//
+// MB: blocks of 16 tokens in the tile (1, 2 or 4).  D[token][row] += X[token][k] * W^T[k][row]
+// with v_mfma_f32_16x16x32_bf16: operand lane l holds 8 consecutive k (group l / 16) of token
+// or row l % 16; accumulator v of lane l is token 4 * (l / 16) + v, row l % 16 of the block.
+constexpr int kMmWinBytes = 40;   // a lane's window: two 16-byte pieces, padded so that the 64 slots spread over the banks
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <int MB, int EPI, int ASYM>
 __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
-                                        lp_u32 table, uint32_t wt, uint32_t xt, lp_i32 tok_ids, lp_f32 gate_s)
+                                        lp_u32 table, uint32_t wt, uint32_t win, lp_i32 tok_ids, lp_f32 gate_s)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int l16 = lane & 15, lg = lane >> 4;
 
-    // this thread's part of the activation tile: token tx, columns 8*seg .. 8*seg+7 of each step
-    const int tx = tid >> 3, seg = tid & 7;
-    const bool x_live = tx < ntok;
-    size_t xrow = 0;
-    if (x_live) {
-        const int tok = a.perm ? a.perm[slot0 + tx] : slot0 + tx;
-        xrow = a.x_by_slot ? (size_t)(slot0 + tx) : (size_t)tok;
-    }
-    // Loads are unconditional (a lane without a token, or past the last column, reads a
-    // valid address and drops the value when it stages it): a load under a branch would
-    // be waited for at the end of the branch instead of staying in flight.
-    const bool x_ok = x_live && 8 * seg + 8 <= a.cols;
-    const uintptr_t xsrc =
-        reinterpret_cast<uintptr_t>(a.x) + (x_ok ? 2 * (xrow * (size_t)a.ldx + 8 * (size_t)seg) : (size_t)0);
-    const int x_last = x_ok ? a.cols - 8 * seg - 8 : 0;  // last column offset this thread may read at
-    auto load_x = [&](int kc) -> u32x4 { return *(gp_u32x4)(xsrc + 2 * (uintptr_t)min(kc, x_last)); };
-    auto keep_x = [&](const u32x4 &v, int kc) -> u32x4 {
-        return (x_ok && kc <= x_last) ? v : u32x4{0u, 0u, 0u, 0u};
-    };
-    const uint32_t x_slot = xt + (uint32_t)(tx * kMmXRowBytes + 16 * seg);  // in buffer 0
-
-    // this lane's row and its codewords
+    // ---- this lane's row and its codewords
     const int r0 = blk * a.mm_rows_per_block;
     const int row = r0 + tid;
     const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
-    QMOE_RING_ROW_SETUP(M, row, row_live);
+    uint32_t left = 0;                                               // codewords to go
+    uintptr_t pp = reinterpret_cast<uintptr_t>(M.codes), last = pp;  // first piece of the window, the lane's last piece
+    uint32_t ci = 0;                                                 // index of the next codeword, counted from piece 0
+    if (row_live) {
+        gp_u32 row_off = (gp_u32)M.row_off;
+        const uint32_t cap = min(M.n_codes, kMaxCodes);
+        const uint32_t K1 = min(row_off[row + 1], cap);
+        const uint32_t K0 = min(row_off[row], K1);
+        left = K1 - K0;
+        // a row without codewords reads the matrix's first piece, never past the stream's end
+        const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + (left ? 2 * (uintptr_t)K0 : (uintptr_t)0);
+        const uint32_t lead = (uint32_t)(first_byte & 15u);
+        pp = first_byte - lead;
+        ci = lead >> 1;
+        last = pp + 16u * (uintptr_t)(left ? ((lead + 2u * left + 15u) >> 4) - 1u : 0u);
+    }
     const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
+    const uint32_t slot = win + (uint32_t)(tid * kMmWinBytes);
+    auto piece_at = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
+    auto store_piece = [&](uint32_t half_bytes, const u32x4 &v) {
+        lw_u64 d = (lw_u64)(uintptr_t)(slot + half_bytes);
+        d[0] = (unsigned long long)v.x | ((unsigned long long)v.y << 32);
+        d[1] = (unsigned long long)v.z | ((unsigned long long)v.w << 32);
+    };
+    auto code_at = [&](uint32_t i) -> uint32_t { return (uint32_t)(*(lp_u16)(uintptr_t)(slot + 2u * (i & 15u))); };
+    {
+        const u32x4 p0 = piece_at(pp), p1 = piece_at(pp + 16u);
+        store_piece(0u, p0);
+        store_piece(16u, p1);
+    }
+    u32x4 fut = piece_at(pp + 32u);
+    uint32_t wbase = 0;   // index of the first codeword of the window's first piece (a multiple of 8)
+#pragma unroll
+    for (int i = 0; i < kMmRing / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
 
-    f32x16 acc[MB][2];
+    // ---- this lane's part of the activations: token 16 * mb + l16, columns 8 * lg .. 8 * lg + 7 of every 32
+    uintptr_t xsrc[MB];
+    bool x_ok[MB];
+    const bool x_col = 8 * lg + 8 <= a.cols;
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++) {
+        const int t = 16 * mb + l16;
+        x_ok[mb] = t < ntok;
+        size_t xrow = 0;
+        if (x_ok[mb]) {
+            const int tok = a.perm ? a.perm[slot0 + t] : slot0 + t;
+            xrow = a.x_by_slot ? (size_t)(slot0 + t) : (size_t)tok;
+        }
+        // (a lane whose columns do not exist -- fewer than 8 * lg + 8 columns -- reads column 0 and drops it)
+        x_ok[mb] = x_ok[mb] && x_col;
+        xsrc[mb] = reinterpret_cast<uintptr_t>(a.x) + 2 * (xrow * (size_t)a.ldx + (x_col ? 8 * (size_t)lg : (size_t)0));
+    }
+    // Loads are unconditional (a lane without a token, or past the last column, reads a valid
+    // address -- column 8 * lg of some row -- and drops the value): a load under a branch would
+    // be waited for at the end of the branch instead of staying in flight.
+    const int x_last = x_col ? a.cols - 8 * lg - 8 : 0;  // last column offset this lane may read at
+    auto load_x = [&](int mb, int k) -> u32x4 { return *(gp_u32x4)(xsrc[mb] + 2 * (uintptr_t)min(k, x_last)); };
+    auto keep_x = [&](int mb, const u32x4 &v, int k) -> u32x4 {
+        return (x_ok[mb] && k <= x_last) ? v : u32x4{0u, 0u, 0u, 0u};
+    };
+
+    f32x4 acc[MB][4];
 #pragma unroll
     for (int mb = 0; mb < MB; mb++)
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) acc[mb][nb][v] = 0.0f;
+        for (int nb = 0; nb < 4; nb++) acc[mb][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Activations: step c is read from LDS buffer c & 1; step c + 1 is in flight to a
-    // register during step c and staged at its end.
-    *(lw_u32x4)(uintptr_t)x_slot = keep_x(load_x(0), 0);
-    u32x4 xr = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
-
-    // asymmetric grid: the grid points of the two rows whose weights this lane feeds to the matrix cores
-    uint32_t g_hi[2] = {0u, 0u}, g_lo[2] = {0u, 0u};
+    // asymmetric grid: the grid points of the four rows whose weights this lane feeds to the matrix cores
+    uint32_t g_hi[4] = {0u, 0u, 0u, 0u}, g_lo[4] = {0u, 0u, 0u, 0u};
     if constexpr (ASYM) {
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
-            const int rl = 64 * wave + 32 * nb + l32;
+        for (int nb = 0; nb < 4; nb++) {
+            const int rl = 64 * wave + 16 * nb + l16;
             uint32_t pair = 0u;  // a row past the end, or a matrix without a pair array, multiplies as zeros
             if (rl < a.mm_rows_per_block && r0 + rl < a.rows && M.minmax_bf16) pair = ((gp_u32)M.minmax_bf16)[r0 + rl];
             g_hi[nb] = pair << 16;
             g_lo[nb] = pair & 0xFFFF0000u;
         }
     }
-    const uint32_t wfrag = wt + (uint32_t)((64 * wave + l32) * kMmWRowBytes + 8 * lhi);
-    const uint32_t xfrag0 = xt + (uint32_t)(l32 * kMmXRowBytes + 16 * lhi);
+    const uint32_t wfrag = wt + (uint32_t)((64 * wave + l16) * kMmWRowBytes + 8 * lg);
     const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
+    const uint32_t n_groups = (uint32_t)a.n_groups, n_order = (uint32_t)a.n_order;
 
-    __syncthreads();  // token ids, gates and the first activation step are in place
+    __syncthreads();  // token ids and gates are in place (the epilogue reads them)
+
+    // The decoder's pipeline: entries of codewords ci and ci + 1, codes of ci + 1 and ci + 2.
+    // Nothing that was just read is used in the round that reads it (a select or a sign flip on
+    // a fresh value would make the wavefront wait for it on the spot): a round's two reads are
+    // issued first, unconditional, from addresses chosen so that a lane that sat out reads again
+    // what it already holds, and are used a round later; the entry of ci + 1 is kept as read,
+    // next to the sign flips of its code's two low bits.
+    auto entry_index = [&](uint32_t code) -> uint32_t {
+        return min(max(code >> 2, __builtin_elementwise_sub_sat(code, 3u * n_groups)), n_order - 1u);
+    };
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    uint32_t c1 = code_at(ci + 1u), c2 = code_at(ci + 2u);
+    uint32_t ent = order_entry(table, code_at(ci), n_groups, n_order);
+    uint32_t ent_n = table[entry_index(c1)], flips_n = order_flips(c1);
+    uint32_t pos8 = 0;  // 8 * (column where the next run starts)
+
+    u32x4 xa[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) xa[mb][ks] = keep_x(mb, load_x(mb, 32 * ks), 32 * ks);
+
     for (int c = 0; c < nsteps; c++) {
-        // ---- decode step c; the next step's activations, staged after this step's product,
-        // are fetched right after the window's wait, so that a whole step hides the latency
-        // of both loads (the empty asm keeps the compiler from moving the load up, in front
-        // of that wait)
-        // The arbiter serves the older wavefront of a SIMD first, so the older four finish a
-        // step's decoding early and wait at the step's barrier (a quarter of their time) for
-        // the younger four; the younger ones decode at a raised priority (2-3 %, measured;
-        // raising it for all eight helps the second product only, alternating it hurts).
-        if (wave >= kMmThreads / 128) __builtin_amdgcn_s_setprio(1);
-        QMOE_RING_DECODE_STEP(c, {
-            int k_next = kend;
-            asm volatile("" : "+s"(k_next));
-            xr = load_x(k_next);
-        }, ASYM ? 0 : 5);
-        __builtin_amdgcn_s_setprio(0);
+        const int kc = c * kMmKc;
+        const uint32_t lim8 = 8u * (uint32_t)(kc + kMmAhead), end8 = 8u * (uint32_t)(kc + kMmKc);
+        // ---- decode until every lane has passed column kc + 64
+        u32x4 xn[MB][2];
+        bool first = true;
+        do {
+            // Slide the window by one piece where its first piece is used up (once per step as a
+            // rule).  The other lanes fetch the piece they already wait for again, so that the
+            // load is unconditional and stays in flight until the next slide.
+            {
+                const bool s8 = ci - wbase >= 8u;
+                if (s8) store_piece(2u * (wbase & 8u), fut);
+                wbase += s8 ? 8u : 0u;
+                pp += s8 ? 16u : 0u;
+                fut = piece_at(pp + 32u);
+            }
+            if (first) {
+                // the next step's activations: fetched right after the window's wait, a whole step ahead
+                first = false;
+                int k_next = kc + kMmKc;
+                asm volatile("" : "+s"(k_next));
+#pragma unroll
+                for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+                    for (int ks = 0; ks < 2; ks++) xn[mb][ks] = load_x(mb, k_next + 32 * ks);
+            }
+            while (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u)) {
+                const bool go = left != 0u && pos8 <= lim8 && ci - wbase <= 12u;
+                // The entry this round applies; a lane that sits out applies an empty one, which stores
+                // three zeros at the column where its next run starts: nothing was written there yet, and
+                // it is never a column of the step being completed (kMmAhead keeps a lane's position below
+                // kc + 128), so the loop body has no branch and the stores need not be waited for.
+                const uint32_t e0 = go ? ent : 0u;
+                // move on to codeword ci + go: its entry is the one read a round ago (go) or still e0,
+                // the code after it c2 (go) or still c1; this round's reads go out before anything else
+                const uint32_t csel = go ? c2 : c1;
+                ent = go ? (ent_n ^ flips_n) : ent;
+                ci += go ? 1u : 0u;
+                ent_n = table[entry_index(csel)];
+                flips_n = order_flips(csel);
+                c1 = csel;
+                c2 = code_at(ci + 2u);
+#pragma unroll
+                for (int z = 0; z < kRunMaxNonzeros; z++) {
+                    const uint32_t t = pos8 + ((e0 >> (8 + 8 * z)) & 0xFFu);  // 8 * column + the field's low three bits
+                    const uint32_t col = (t >> 3) & (uint32_t)(kMmRing - 1);
+                    // value bits of the field (2: +1, 6: -1): as they are (asymmetric grid: byte selectors), or
+                    // at the top of the byte (0x40 / 0xC0; the store keeps the low eight bits)
+                    *(lw_u8)(uintptr_t)(wrow + col) = (unsigned char)(ASYM ? (t & 6u) : (t << 5));
+                }
+                pos8 += e0 & 0xFFu;
+                left -= go ? 1u : 0u;
+            }
+        } while (__any(left != 0u && pos8 < end8));
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
         // ---- multiply step c
-        const uint32_t xf = xfrag0 + (uint32_t)((c & 1) * kMmTokens * kMmXRowBytes);
         const uint32_t wf = wfrag + (uint32_t)((c & 1) * kMmKc);
 #pragma unroll
-        for (int ks = 0; ks < kMmKc / 16; ks++) {
-            bf16x8 bw[2], ax[MB];
+        for (int ks = 0; ks < 2; ks++) {
+            bf16x8 bw[4], ax[MB];
 #pragma unroll
-            for (int nb = 0; nb < 2; nb++) {
-                const unsigned long long d = *(lp_u64)(uintptr_t)(wf + (uint32_t)(nb * 32 * kMmWRowBytes + 16 * ks));
+            for (int nb = 0; nb < 4; nb++) {
+                const unsigned long long d = *(lp_u64)(uintptr_t)(wf + (uint32_t)(nb * 16 * kMmWRowBytes + 32 * ks));
                 if constexpr (ASYM)
                     bw[nb] = mm_expand_minmax((uint32_t)d, (uint32_t)(d >> 32), g_hi[nb], g_lo[nb]);
                 else
                     bw[nb] = mm_expand((uint32_t)d, (uint32_t)(d >> 32));
             }
 #pragma unroll
-            for (int mb = 0; mb < MB; mb++) {
-                const u32x4 t = *(lp_u32x4)(uintptr_t)(xf + (uint32_t)(mb * 32 * kMmXRowBytes + 32 * ks));
-                __builtin_memcpy(&ax[mb], &t, 16);
-            }
+            for (int mb = 0; mb < MB; mb++) __builtin_memcpy(&ax[mb], &xa[mb][ks], 16);
 #pragma unroll
             for (int mb = 0; mb < MB; mb++)
 #pragma unroll
-                for (int nb = 0; nb < 2; nb++)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[mb], bw[nb], acc[mb][nb], 0, 0, 0);
+                for (int nb = 0; nb < 4; nb++)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ax[mb], bw[nb], acc[mb][nb], 0, 0, 0);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-
-        // ---- stage this thread's part of step c + 1 of the activations: the buffer held
-        // step c - 1, which every wavefront has finished by now, and nobody reads step c + 1
-        // before the barrier below
-        *(lw_u32x4)(uintptr_t)(x_slot + (uint32_t)(((c + 1) & 1) * kMmTokens * kMmXRowBytes)) =
-            keep_x(xr, kend);
-        lds_barrier();
+        // this half of the ring becomes columns kc + 128 .. kc + 191: cleared after the reads above
+#pragma unroll
+        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + (uint32_t)((c & 1) * kMmKc)))[i] = 0ull;
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++) xa[mb][ks] = keep_x(mb, xn[mb][ks], kc + kMmKc + 32 * ks);
     }
 
-    // accumulator v of lane l: token 32*mb + 8*(v/4) + 4*(l/32) + v%4, row 32*nb + l%32 of the wavefront's 64
+    // accumulator v of lane l: token 16 * mb + 4 * (l / 16) + v, row 16 * nb + l % 16 of the wavefront's 64
 #pragma unroll
-    for (int nb = 0; nb < 2; nb++) {
-        const int rl = 64 * wave + 32 * nb + l32;
+    for (int nb = 0; nb < 4; nb++) {
+        const int rl = 64 * wave + 16 * nb + l16;
         const int r = r0 + rl;
         if (rl < a.mm_rows_per_block && r < a.rows) {
             // symmetric grid: the weights were +-2; asymmetric: they were the grid points themselves
@@ -313,8 +422,8 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 #pragma unroll
             for (int mb = 0; mb < MB; mb++) {
 #pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int t = 32 * mb + 8 * (v / 4) + 4 * lhi + (v % 4);
+                for (int v = 0; v < 4; v++) {
+                    const int t = 16 * mb + 4 * lg + v;
                     if (t < ntok) {
                         const float val = acc[mb][nb][v] * scale;
                         if constexpr (EPI == 0) {
@@ -337,9 +446,9 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     extern __shared__ __align__(16) unsigned char smem[];
     const size_t table_bytes = ((size_t)a.n_order * 4 + 15) & ~(size_t)15;
     uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
-    unsigned char *wt = smem + table_bytes;                           // [512][kMmWRowBytes]
-    unsigned char *xt = wt + (size_t)kMmThreads * kMmWRowBytes;       // 2 x [64][kMmXRowBytes]
-    int *tok_ids = reinterpret_cast<int *>(xt + 2 * (size_t)kMmTokens * kMmXRowBytes);  // [64]
+    unsigned char *wt = smem + table_bytes;                           // [512][kMmWRowBytes] rings
+    unsigned char *win = wt + (size_t)kMmThreads * kMmWRowBytes;      // [512][kMmWinBytes] codeword windows
+    int *tok_ids = reinterpret_cast<int *>(win + (size_t)kMmThreads * kMmWinBytes);  // [64]
     float *gate_s = reinterpret_cast<float *>(tok_ids + kMmTokens);   // [64]
     int *next_item = reinterpret_cast<int *>(gate_s + kMmTokens);     // [1]
 
@@ -383,13 +492,16 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
             gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
         }
         const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
-        const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, xt_addr = (uint32_t)(uintptr_t)(lw_u8)xt;
-        if (ntok <= 32)
-            mm_item<1, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
-                            (lp_f32)gate_s);
+        const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, win_addr = (uint32_t)(uintptr_t)(lw_u8)win;
+        if (ntok <= 16)
+            mm_item<1, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
+                                  (lp_f32)gate_s);
+        else if (ntok <= 32)
+            mm_item<2, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
+                                  (lp_f32)gate_s);
         else
-            mm_item<2, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, xt_addr, (lp_i32)tok_ids,
-                            (lp_f32)gate_s);
+            mm_item<4, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
+                                  (lp_f32)gate_s);
     }
 }
 
@@ -505,7 +617,7 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
 size_t mm_lds_bytes(int n_order)
 {
     return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes +
-           2 * (size_t)kMmTokens * kMmXRowBytes + 2 * sizeof(int) * kMmTokens + 16;
+           (size_t)kMmThreads * kMmWinBytes + 2 * sizeof(int) * kMmTokens + 16;
 }
 
 size_t decompress_lds_bytes(int n_order)
