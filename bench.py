@@ -33,13 +33,15 @@ def log(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def build_layer(w, dd, gpu, workers, interchange_order=False, minmax=False):
-    """Generate and encode every expert (host threads), upload once.  minmax: rows on the
-    asymmetric grid (a bf16 (w_min, w_max) pair per row in place of the binary16 scale)."""
+def build_layer(w, dd, gpu, workers, interchange_order=False, minmax=False, lanes_for_tokens=0, copies=1):
+    """Generate and encode every expert (host threads), upload `copies` separate copies of the layer (a
+    list; more than one for a cold-cache measurement of a layer that would otherwise stay in the
+    last-level cache).  minmax: rows on the asymmetric grid (a bf16 (w_min, w_max) pair per row in place
+    of the binary16 scale)."""
     import paper_2310_16795_amd as q
     from paper_2310_16795_amd import device as dev
 
-    layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax)
+    layers = [dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax) for _ in range(copies)]
     q.qmoe_set_tuning("host_threads", 1)  # parallelism is across experts here
 
     def one(e):
@@ -55,13 +57,15 @@ def build_layer(w, dd, gpu, workers, interchange_order=False, minmax=False):
     with ThreadPoolExecutor(max_workers=workers) as pool:
         for e, parts in pool.map(one, range(w.n_experts)):
             for which, codes, row_off, scale in parts:
-                layer.set_expert(e, which, codes, row_off, scale)
+                for layer in layers:
+                    layer.set_expert(e, which, codes, row_off, scale)
             done += 1
             if done % 256 == 0:
                 log(f"encoded {done}/{w.n_experts} experts ({time.time() - t0:.0f} s)")
     q.qmoe_set_tuning("host_threads", 0)
-    layer.finalize(device_order_of=None if interchange_order else dd)
-    return layer
+    for layer in layers:
+        layer.finalize(device_order_of=None if interchange_order else dd, lanes_for_tokens=lanes_for_tokens)
+    return layers
 
 
 def dense_bf16_experts(layer, dd, active, gpu, stats=None):
@@ -121,13 +125,11 @@ def single_matvec(w, layer, dd, gpu, expert):
     return out
 
 
-def row_meta_bytes(layer):
-    """Per output row: a 4-byte stream offset and the 2-byte scale (4-byte pair on the asymmetric grid)."""
-    return 8 if layer.minmax else 6
-
-
 def layer_bytes_of(layer, experts):
-    return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + row_meta_bytes(layer) * (layer.d_ff + layer.d_model)
+    """Bytes of the experts' matrices as the device holds them: codewords (in the lane-interleaved layout the
+    padding counts), per row a 4-byte offset and the 2-byte scale (4-byte pair on the asymmetric grid), and in
+    the lane-interleaved layout a 4-byte offset per group of 64 lanes."""
+    return int(sum(2 * (layer.n_codes["wi"][e] + layer.n_codes["wo"][e]) + layer.matrix_meta["wi"] + layer.matrix_meta["wo"]
                    for e in experts))
 
 
@@ -179,34 +181,70 @@ def time_phases(fn, steps):
             for i, (name, _) in enumerate(PHASES)}
 
 
-def cpu_baseline(w, idx, x_bits, active, budget_s=12.0, minmax=False):
-    """The oracle (one thread, as it stands) on a bounded sample of the workload:
-    decode both matrices of an expert and push its tokens through, expert after expert."""
+def cpu_baseline(w, idx, x_bits, active, budget_s=7.0, minmax=False):
+    """The oracle, as it stands, on a bounded sample of the workload (expert after expert: decode both
+    matrices, push the expert's tokens through in fp64), timed three ways: one thread; every host core
+    this job may use, one expert per thread at a time (the C routines release the interpreter lock);
+    and, on one thread, the products alone on matrices that are already decoded (the decode-free dense
+    int8 leg).  Rates are bytes of the sample's compressed matrices (2 per codeword + row metadata) per
+    second, so that they compare with the GPU line."""
     import oracle
 
     od = oracle.Dictionary()
-    t_used, n_bytes, n_experts, n_tokens = 0.0, 0, 0, 0
-    for e in active:
+    cores = max(1, min(16, os.cpu_count() or 1))  # a job's share of the box's cores
+
+    def prepare(e):
         wi, wo = w.wi_ternary(e), w.wo_ternary(e)
-        wis, wos = (None, None) if minmax else (w.wi_scale(e), w.wo_scale(e))
-        wim, wom = (w.wi_minmax(e), w.wo_minmax(e)) if minmax else (None, None)
         ci, ri = oracle.encode(od, wi)
         co, ro = oracle.encode(od, wo)
-        toks = np.nonzero(idx == e)[0]
+        meta = (8 if minmax else 6) * (wi.shape[0] + wo.shape[0])
+        return {"e": e, "wi": (ci, ri, wi.shape), "wo": (co, ro, wo.shape), "bytes": 2 * (ci.size + co.size) + meta,
+                "scales": (None, None) if minmax else (w.wi_scale(e), w.wo_scale(e)),
+                "pairs": (w.wi_minmax(e), w.wo_minmax(e)) if minmax else (None, None),
+                "toks": np.nonzero(idx == e)[0]}
+
+    def decode(p):
+        return (oracle.decode(od.words, p["wi"][0], p["wi"][1], *p["wi"][2]),
+                oracle.decode(od.words, p["wo"][0], p["wo"][1], *p["wo"][2]))
+
+    def products(p, di, do):
+        for t in p["toks"]:
+            oracle.ffn_token(di, p["scales"][0], do, p["scales"][1], x_bits[t], 1.0, p["pairs"][0], p["pairs"][1])
+
+    # one thread, and the decode-free leg on the same experts
+    t_one = t_dense = 0.0
+    sample = []
+    for e in active:
+        p = prepare(e)
         t0 = time.perf_counter()
-        di = oracle.decode(od.words, ci, ri, *wi.shape)
-        do = oracle.decode(od.words, co, ro, *wo.shape)
-        for t in toks:
-            oracle.ffn_token(di, wis, do, wos, x_bits[t], 1.0, wim, wom)
-        t_used += time.perf_counter() - t0
-        n_bytes += 2 * (ci.size + co.size) + (8 if minmax else 6) * (wi.shape[0] + wo.shape[0])
-        n_experts += 1
-        n_tokens += toks.size
-        if t_used > budget_s:
+        di, do = decode(p)
+        t1 = time.perf_counter()
+        products(p, di, do)
+        t2 = time.perf_counter()
+        t_one += t2 - t0
+        t_dense += t2 - t1
+        sample.append(p)
+        if t_one > budget_s:
             break
-    return {"value": n_bytes / t_used / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {n_experts} active experts of the workload with their {n_tokens} tokens "
-                      f"(decode both matrices + fp64 products), {t_used:.1f} s"}
+    b_one = sum(p["bytes"] for p in sample)
+    n_tok = int(sum(p["toks"].size for p in sample))
+    # every core: about the same wall time, `cores` times the experts
+    more = [e for e in active if e not in {p["e"] for p in sample}][: len(sample) * (cores - 1)]
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        batch = sample + list(pool.map(prepare, more))
+        t0 = time.perf_counter()
+        list(pool.map(lambda p: products(p, *decode(p)), batch))
+        t_all = time.perf_counter() - t0
+    b_all = sum(p["bytes"] for p in batch)
+    return {"value": b_all / t_all / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(batch)} active experts of the workload with their {int(sum(p['toks'].size for p in batch))} "
+                      f"tokens (decode both matrices + fp64 products), one expert per thread, {t_all:.1f} s",
+            "one_thread": {"value": b_one / t_one / 1e9, "unit": "GB/s", "cores": 1,
+                           "sample": f"first {len(sample)} active experts, {n_tok} tokens, {t_one:.1f} s"},
+            "decode_free_dense_int8_one_thread": {
+                "value": b_one / max(t_dense, 1e-9) / 1e9, "unit": "GB/s (bytes of the compressed form; the matrices are "
+                "already decoded int8, only the fp64 products are timed)", "cores": 1,
+                "sample": f"the same {len(sample)} experts, {t_dense:.1f} s"}}
 
 
 def main():
@@ -223,6 +261,13 @@ def main():
     ap.add_argument("--dict-max-pairs", type=int, default=14, help="longest dictionary entry in pairs (the paper's is 14)")
     ap.add_argument("--interchange-order", action="store_true",
                     help="leave the codeword streams as encoded instead of renumbering them at load time")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="resident copies of the layer that the timed steps rotate through, so that every step reads its "
+                         "weights from HBM; 0 = as many as make the rotation at least four times the last-level cache "
+                         "plus L2 (one for the c2048 workloads, whose single step already is)")
+    ap.add_argument("--layout", choices=("lanes", "rows"), default="lanes",
+                    help="codeword streams re-packed at load time into the lane-interleaved layout (a wavefront's 64 loads "
+                         "are consecutive; its padding counts as compressed bytes), or rows back to back as encoded")
     ap.add_argument("--grid", choices=("scale", "minmax"), default="scale",
                     help="per-row grid: {-s,0,+s} with one binary16 scale (the headline format) or the paper's "
                          "{w_min,0,w_max} with a bf16 pair")
@@ -258,19 +303,32 @@ def main():
     workers = min(16, os.cpu_count() or 1)
     t0 = time.time()
     minmax = args.grid == "minmax"
-    layer = build_layer(w, dd, gpu, workers, args.interchange_order, minmax)
-    log(f"layer resident: {layer.compressed_bytes / 1e9:.3f} GB compressed, built in {time.time() - t0:.0f} s")
+    lanes_layout = args.layout == "lanes" and not args.interchange_order
+    # cold protocol: a step must not find its weights in the 256 MB last-level cache or the 8 x 4 MB of L2
+    est_touched = 2 * 2 * w.d_model * w.d_ff * len(active) * 0.09  # ~0.71 bits per weight
+    copies = args.copies if args.copies > 0 else int(min(32, max(1, np.ceil(4 * 288e6 / est_touched))))
+    layers = build_layer(w, dd, gpu, workers, args.interchange_order, minmax, lanes_for_tokens=T if lanes_layout else 0,
+                         copies=copies)
+    layer = layers[0]
+    log(f"layer resident: {layer.compressed_bytes / 1e9:.3f} GB compressed x {copies} copies, built in {time.time() - t0:.0f} s")
 
     x = torch.from_numpy(x_bits.view(np.int16).copy()).to(gpu)
     d_idx = torch.from_numpy(idx).to(gpu)
     y = torch.empty((T, w.d_model), dtype=torch.float32, device=gpu)
     ws = layer.workspace(T)
 
+    turn = [0]
+
     def step():
+        layers[turn[0] % copies].forward(dd, x, d_idx, y, ws)
+        turn[0] += 1
+
+    def step_warm():
         layer.forward(dd, x, d_idx, y, ws)
 
     spread = {}
     ms, wall_ms = time_steps(step, args.steps, args.warmup, spread)
+    warm_ms = ms if copies == 1 else time_steps(step_warm, args.steps, args.warmup)[0]
     kernel_ms = time_phases(step, min(args.steps, 30))
 
     # which experts went to the matrix-core kernels (tiles of up to 64 tokens), which to the scalar ones
@@ -283,7 +341,7 @@ def main():
     # expert's compressed matrix (codewords + 6 bytes of row metadata) once, activations in, results out
     n_params = 2 * w.d_model * w.d_ff
     def mat_bytes(which, rows, experts):
-        return int(sum(2 * layer.n_codes[which][e] + row_meta_bytes(layer) * rows for e in experts))
+        return int(sum(2 * layer.n_codes[which][e] + layer.matrix_meta[which] for e in experts))
     weight_bytes = mat_bytes("wi", w.d_ff, active) + mat_bytes("wo", w.d_model, active)
     n_codewords = int(sum(layer.n_codes["wi"][e] + layer.n_codes["wo"][e] for e in active))
     def kernel_bytes(which, experts):
@@ -326,6 +384,8 @@ def main():
                    "tokens": T, "experts_with_tokens": len(active), "routing": w.routing,
                    "zero_fraction": "0.80-0.97 per row" if w.p0_spread else w.p0,
                    "code_order": "interchange" if args.interchange_order else "device",
+                   "stream_layout": (f"lane-interleaved ({layer.lanes['wi']} / {layer.lanes['wo']} lanes per matrix)"
+                                     if lanes_layout else "rows back to back"),
                    "grid": "{w_min,0,w_max}, bf16 pair per row" if minmax else "{-s,0,+s}, binary16 scale per row",
                    "dict_entries": args.dict_entries, "dict_max_pairs": args.dict_max_pairs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -336,8 +396,11 @@ def main():
         "frac_of_stream_copy_rate": weight_bytes / (ms * 1e-3) / 1e9 / copy_gbps,
         # decode rate of the whole step: codewords per clock per compute unit at 2.4 GHz, 256 units
         "codewords_per_clk_per_cu": n_codewords / (ms * 1e-3) / (256 * 2.4e9),
-        "cache_state": "cold by construction: a step touches %.2f GB of codewords, more than four times "
-                       "the 256 MB last-level cache plus L2" % (weight_bytes / 1e9),
+        "cache_state": ("cold by construction: a step touches %.2f GB of codewords, more than four times the 256 MB "
+                        "last-level cache plus L2" % (weight_bytes / 1e9)) if copies == 1 else
+                       ("cold by rotation: the timed steps go round %d resident copies of the layer (%.2f GB together, at "
+                        "least four times the 256 MB last-level cache plus L2)" % (copies, copies * weight_bytes / 1e9)),
+        "ms_per_step_warm": warm_ms,
         "kernel_ms": kernel_ms,
         "kernels": {k: {"name": v[0], "algorithmic_bytes": v[1],
                         "GBps": (v[1] / (kernel_ms[k] * 1e-3) / 1e9) if kernel_ms[k] > 0 else None}

@@ -37,6 +37,11 @@ FORMAT_DEVICE_ORDER = 1
 FORMAT_GRID_MINMAX = 2
 
 
+def format_lanes(lanes_wi: int, lanes_wo: int) -> int:
+    """QMOE_FORMAT_LANES: the lane counts the lane-interleaved layouts of the two projections were built for."""
+    return ((lanes_wi // 64) << 8) | ((lanes_wo // 64) << 16)
+
+
 class qmoe_ws_layout(Structure):
     _fields_ = [(n, c_size_t) for n in ("tok_off", "perm", "counters", "items_wi", "items_wo", "items_mm", "hidden", "total")]
 
@@ -323,11 +328,6 @@ def qmoe_bf16_layer_forward(wi_ptrs, wo_ptrs, n_experts: int, d_model: int, d_ff
 
 def qmoe_set_tuning(key: str, value: int) -> None:
     _check(lib().qmoe_set_tuning(key.encode(), int(value)), "qmoe_set_tuning")
-
-
-def format_lanes(lanes_wi: int, lanes_wo: int) -> int:
-    """QMOE_FORMAT_LANES: the lane counts the lane-interleaved layouts of the two projections were built for."""
-    return ((lanes_wi // 64) << 8) | ((lanes_wo // 64) << 16)
 
 
 def qmoe_plan_lanes(d: int, rows: int, cols: int, n_experts: int, n_tokens: int) -> int:

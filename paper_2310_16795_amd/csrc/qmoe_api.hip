@@ -104,7 +104,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Pick the token tile, workgroup size, blocks per matrix and grid for a product over rows x cols
 // matrices with the lane-per-row kernel (compressed path).
 qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passes_hint, ProductPlan *p,
-                         int n_order = 0, int force_blocks = 0, int stage_out_row_bytes = 0, bool minmax = false)
+                         int n_order = 0, int force_blocks = 0, int stage_out_row_bytes = 0, bool minmax = false,
+                         int force_lanes = 0)
 {
     DeviceInfo di;
     const qmoe_status st = device_info(&di);
@@ -187,6 +188,15 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
         best_t = std::max(64, std::min(kProductMaxThreads, tu.threads / 64 * 64));
         const int rpl = tu.rows_per_item > 0 ? tu.rows_per_item : want_rpl;
         best_b = std::max(1, (int)((rows + (long long)best_t * rpl - 1) / ((long long)best_t * rpl)));
+    }
+    if (force_lanes > 0) {
+        // streams in the lane-interleaved layout: workgroups x lanes must be the count the layout was
+        // built for; as few workgroups per matrix as the workgroup size allows
+        best_b = 0;
+        for (int b = 1; b <= force_lanes / 64 && !best_b; b++)
+            if (force_lanes % b == 0 && (force_lanes / b) % 64 == 0 && force_lanes / b <= max_threads) best_b = b;
+        if (!best_b) return QMOE_E_INVALID_ARG;
+        best_t = force_lanes / best_b;
     }
     p->threads = best_t;
     p->blocks_per_pass = best_b;
@@ -289,6 +299,7 @@ qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, i
 qmoe_status check_matrix_args(const qmoe_dict *d, const qmoe_matrix *W)
 {
     if (!d || !W) return QMOE_E_INVALID_ARG;
+    if (W->lanes || W->wave_off) return QMOE_E_INVALID_ARG;  // the single-matrix calls read rows back to back
     if (!W->codes || !W->row_off || (!W->scale_f16 && !W->minmax_bf16) || W->rows < 1 || W->cols < 2 || (W->cols & 1))
         return QMOE_E_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(W->minmax_bf16) % 4) return QMOE_E_INVALID_ARG;  // pairs are read as one word
@@ -308,12 +319,17 @@ void fill_tables(const qmoe_dict *d, ProductArgs *a, int code_order)
     a->code_order = code_order;
 }
 
-// Splits a format argument (QMOE_FORMAT_* bits) into the numbering and the grid.
-qmoe_status split_format(int format, int *code_order, bool *minmax)
+// Splits a format argument (QMOE_FORMAT_* bits) into the numbering, the grid and the lane counts
+// of the lane-interleaved layout (0, 0 = rows back to back).
+qmoe_status split_format(int format, int *code_order, bool *minmax, int *lanes_wi = nullptr, int *lanes_wo = nullptr)
 {
-    if (format < 0 || (format & ~(QMOE_FORMAT_DEVICE_ORDER | QMOE_FORMAT_GRID_MINMAX))) return QMOE_E_INVALID_ARG;
+    if (format < 0 || (format & ~(QMOE_FORMAT_DEVICE_ORDER | QMOE_FORMAT_GRID_MINMAX | 0xFFFF00))) return QMOE_E_INVALID_ARG;
     *code_order = (format & QMOE_FORMAT_DEVICE_ORDER) ? 1 : 0;
     *minmax = (format & QMOE_FORMAT_GRID_MINMAX) != 0;
+    const int lwi = 64 * ((format >> 8) & 0xFF), lwo = 64 * ((format >> 16) & 0xFF);
+    if ((lwi || lwo) && (!*code_order || !lwi || !lwo)) return QMOE_E_INVALID_ARG;  // both or neither; device numbering only
+    if (lanes_wi) *lanes_wi = lwi;
+    if (lanes_wo) *lanes_wo = lwo;
     return QMOE_OK;
 }
 
@@ -588,7 +604,8 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
     bool minmax = false;
-    if ((st = split_format(code_order, &code_order, &minmax)) != QMOE_OK) return st;
+    int lanes_wi = 0, lanes_wo = 0;
+    if ((st = split_format(code_order, &code_order, &minmax, &lanes_wi, &lanes_wo)) != QMOE_OK) return st;
     if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
@@ -597,11 +614,11 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
                            tuning().blocks_first > 0 ? tuning().blocks_first : spread,
-                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax)) != QMOE_OK)
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax, lanes_wi)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread,
-                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax)) != QMOE_OK)
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax, lanes_wo)) != QMOE_OK)
         return st;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, true, &mp)) != QMOE_OK) return st;
     return launch_dispatch(expert_idx, n_tokens, n_experts, d_model, layer_ptrs(workspace, l), pwi.tb_max,
@@ -625,7 +642,8 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < l.total)
         return QMOE_E_WORKSPACE;
     bool minmax = false;
-    if ((st = split_format(code_order, &code_order, &minmax)) != QMOE_OK) return st;
+    int lanes_wi = 0, lanes_wo = 0;
+    if ((st = split_format(code_order, &code_order, &minmax, &lanes_wi, &lanes_wo)) != QMOE_OK) return st;
     if ((st = check_code_order(d, code_order)) != QMOE_OK) return st;
     const bool run = d->max_nonzeros <= kRunMaxNonzeros;
     const int n_order = code_order ? (int)d->order_table.size() : 0;
@@ -633,11 +651,11 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
     const int spread = layer_blocks_hint(n_experts, n_tokens);
     if ((st = plan_product(d_ff, d_model, run, n_tokens, &pwi, n_order,
                            tuning().blocks_first > 0 ? tuning().blocks_first : spread,
-                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax)) != QMOE_OK)
+                           (d_ff % 8 == 0 && tuning().stage_out >= 0) ? 2 : 0, minmax, lanes_wi)) != QMOE_OK)
         return st;
     if ((st = plan_product(d_model, d_ff, run, n_tokens, &pwo, n_order,
                            tuning().blocks_second > 0 ? tuning().blocks_second : spread,
-                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax)) != QMOE_OK)
+                           (d_model % 8 == 0 && tuning().stage_out >= 0) ? 4 : 0, minmax, lanes_wo)) != QMOE_OK)
         return st;
     MmPlan mp;
     if ((st = plan_mm(d, code_order, d_model, d_ff, n_tokens, reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0, &mp)) != QMOE_OK)
@@ -701,12 +719,16 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
         am.items = lp.items_mm;
         am.n_items_dev = lp.counters + 7;
         am.work_counter = lp.counters + 8;
+        // the hidden vectors of the crowded experts are kept in blocks of 16 tokens (see ProductArgs); only the two
+        // matrix-core kernels touch those slots (needs whole 8-column groups on the hidden side: d_ff % 8 == 0)
+        am.out_tiled = 1;
         if (phases & 8)
             if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
         am = a2;
         am.items = lp.items_mm;
         am.n_items_dev = lp.counters + 7;
         am.work_counter = lp.counters + 9;
+        am.x_tiled = 1;
         if (phases & 16)
             if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
     }
@@ -747,6 +769,17 @@ qmoe_status qmoe_moe_layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, co
 {
     return layer_forward(d, wi, wo, code_order, n_experts, d_model, d_ff, x_bf16, expert_idx, gate, n_tokens, y,
                          workspace, workspace_bytes, stream, 1, side_stream);
+}
+
+int qmoe_plan_lanes(const qmoe_dict *d, int rows, int cols, int n_experts, int n_tokens)
+{
+    if (!d || rows < 1 || cols < 2 || (cols & 1) || n_experts < 1 || n_tokens < 1 || d->order_table.empty()) return 0;
+    ProductPlan p;
+    const bool run = d->max_nonzeros <= kRunMaxNonzeros;
+    if (plan_product(rows, cols, run, n_tokens, &p, (int)d->order_table.size(), layer_blocks_hint(n_experts, n_tokens)) !=
+        QMOE_OK)
+        return 0;
+    return p.threads * p.blocks_per_pass;
 }
 
 size_t qmoe_static_workspace_bytes(void) { return kStaticWsBytes; }

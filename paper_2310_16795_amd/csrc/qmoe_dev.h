@@ -78,6 +78,11 @@ struct ProductArgs {
     int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
     int mm_row_blocks, mm_rows_per_block;  // matrix-core kernel: workgroups per matrix, rows each takes (<= 512)
     int minmax;               // rows on the grid {w_min, 0, w_max} (host side: which kernel to launch)
+    // matrix-core kernel, layer calls: the hidden vectors of a tile are kept in blocks of 16 tokens,
+    // [8-column group][token of the block][8 columns] (a partial last block: its own token count),
+    // in the same bytes the plain [slot][column] rows would take, so that the 16-byte operand
+    // loads of the second product are consecutive over the 64 lanes of a wavefront
+    int x_tiled, out_tiled;
 };
 
 
@@ -317,6 +322,58 @@ __device__ __forceinline__ void stage_x_tile(uint16_t *xs_w, const uint16_t *xba
 // bits of every code flip the sign bits of fields 1 and 2; the single entries are stored
 // with those flips already applied once, so that the second application restores them
 // and no case distinction is needed.
+// Where one row's codewords sit, for the kernels that give a lane one row: `pp` is the address
+// of the 16-byte piece that holds the row's first codeword, `sub` that codeword's index in the
+// piece (0..7), `left` the number of codewords, `last` the address of the piece that holds the
+// last one, `pstride` the distance from a piece to the next of the same stream (16 with rows
+// back to back; 1024 in the lane-interleaved layout, where the row is a part of the stream of
+// the lane that owns it under the even split of rows over M.lanes lanes).  A row that is not
+// live, or has no codewords, points at the matrix's first piece with left = 0.
+struct RowStream {
+    uintptr_t pp, last, pstride;
+    uint32_t left, sub;
+};
+
+__device__ __forceinline__ RowStream row_stream(const qmoe_matrix &M, int row, bool live)
+{
+    RowStream r;
+    r.pp = reinterpret_cast<uintptr_t>(M.codes);
+    r.last = r.pp;
+    r.pstride = M.lanes ? 1024u : 16u;
+    r.left = 0u;
+    r.sub = 0u;
+    if (!live) return r;
+    gp_u32 row_off = (gp_u32)M.row_off;
+    const uint32_t cap = min(M.n_codes, kMaxCodes);
+    const uint32_t K1 = min(row_off[row + 1], cap);
+    const uint32_t K0 = min(row_off[row], K1);
+    r.left = K1 - K0;
+    if (r.left == 0u) return r;
+    uint32_t lead;  // bytes from the start of the first piece to the row's first codeword
+    if (M.lanes) {
+        const int lanes = (int)M.lanes, base = M.rows / lanes, extra = M.rows - base * lanes;
+        const int split = extra * (base + 1);  // rows below it belong to lanes that own base + 1 rows
+        int g, ra;
+        if (row < split) {
+            g = row / (base + 1);
+            ra = g * (base + 1);
+        } else {
+            g = extra + (row - split) / max(base, 1);
+            ra = split + (g - extra) * base;
+        }
+        const uint32_t before = K0 - min(row_off[ra], K0);  // the lane's codewords ahead of this row
+        r.pp += 16u * ((uintptr_t)((gp_u32)M.wave_off)[g >> 6] + (uintptr_t)(g & 63) + 64u * (uintptr_t)(before >> 3));
+        lead = 2u * (before & 7u);
+    } else {
+        const uintptr_t first_byte = r.pp + 2 * (uintptr_t)K0;
+        lead = (uint32_t)(first_byte & 15u);
+        r.pp = first_byte - lead;
+    }
+    r.sub = lead >> 1;
+    r.last = r.pp + r.pstride * (uintptr_t)(((lead + 2u * r.left + 15u) >> 4) - 1u);
+    return r;
+}
+
 // What the two low bits of a device-order code flip in its entry: bit 0 -> bit 18, bit 1 -> bit 26
 // (the sign bits of fields 1 and 2).  Written as one shift-or instruction: left to itself the
 // compiler turns the two shifts into a 32-bit multiply, which runs at a quarter of the rate.

@@ -311,9 +311,19 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
     // The stream is read in aligned 16-byte pieces (eight codewords); `rel` is the stream
     // index (relative to K0) of the first slot of the lane's first piece.
     // (a lane without codewords reads the matrix's first piece, never past the stream's end)
-    const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + (n ? 2 * (uintptr_t)K0 : (uintptr_t)0);
+    // Rows back to back: a lane's pieces follow each other.  Lane-interleaved layout (built for
+    // exactly this launch's lanes per matrix): the lane's stream starts on a piece of its own
+    // and piece p sits 64 p pieces further on, next to the same piece of the wavefront's other
+    // lanes, so that the wavefront's 64 loads are one run of 1 KiB.
+    const bool interleaved = M.lanes != 0u;
+    if (interleaved && M.lanes != (uint32_t)nlanes) return;  // not the launch the layout was built for
+    uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + (n ? 2 * (uintptr_t)K0 : (uintptr_t)0);
+    if (interleaved && n)
+        first_byte = reinterpret_cast<uintptr_t>(M.codes) +
+                     16u * ((uintptr_t)((gp_u32)M.wave_off)[gl >> 6] + (uintptr_t)(gl & 63));
     const uint32_t lead = (uint32_t)(first_byte & 15u);
     const uintptr_t chunk = first_byte - lead;
+    const uintptr_t pstride = interleaved ? 1024u : 16u;  // from a piece of the lane to its next
     const int rel = -(int)(lead >> 1);
     const int my_pieces = n ? (int)((lead + 2u * n + 15u) >> 4) : 0;
     int npieces = my_pieces;
@@ -332,10 +342,10 @@ __device__ __forceinline__ void product_block(const ProductArgs &a, const qmoe_m
 
     // Piece p + 2 is being loaded and the entries of piece p + 1 looked up while piece p
     // is applied.
-    const uintptr_t last_piece = chunk + 16u * (uintptr_t)max(my_pieces - 1, 0);
+    const uintptr_t last_piece = chunk + pstride * (uintptr_t)max(my_pieces - 1, 0);
     auto load_piece = [&](int p) -> u32x4 {
         // lanes past their own end re-read their last piece (its slots are masked out below)
-        const uintptr_t at = chunk + 16u * (uintptr_t)p;
+        const uintptr_t at = chunk + pstride * (uintptr_t)p;
         return *(gp_u32x4)(at < last_piece ? at : last_piece);
     };
     auto apply = [&](Entry (&e)[8], int r) {

@@ -88,30 +88,18 @@ __device__ __forceinline__ void lds_barrier()
 // lane's last one re-read the last (never used: `left` runs out first) -- and `pos`, the
 // column where the next codeword starts.
 #define QMOE_RING_ROW_SETUP(M, row, row_live)                                                           \
-    uint32_t left = 0;                                                                                  \
-    uintptr_t pp = reinterpret_cast<uintptr_t>((M).codes), last = pp;                                   \
-    uint32_t sub = 0;                                                                                   \
-    if (row_live) {                                                                                     \
-        gp_u32 row_off_ = (gp_u32)(M).row_off;                                                          \
-        const uint32_t cap_ = min((M).n_codes, kMaxCodes);                                              \
-        const uint32_t K1_ = min(row_off_[(row) + 1], cap_);                                            \
-        const uint32_t K0_ = min(row_off_[(row)], K1_);                                                 \
-        left = K1_ - K0_;                                                                               \
-        /* a row without codewords reads the matrix's first piece, never past the stream's end */      \
-        const uintptr_t first_byte_ =                                                                   \
-            reinterpret_cast<uintptr_t>((M).codes) + (left ? 2 * (uintptr_t)K0_ : (uintptr_t)0);        \
-        const uint32_t lead_ = (uint32_t)(first_byte_ & 15u);                                           \
-        pp = first_byte_ - lead_;                                                                       \
-        sub = lead_ >> 1;                                                                               \
-        last = pp + 16u * (uintptr_t)(left ? ((lead_ + 2u * left + 15u) >> 4) - 1u : 0u);               \
-    }                                                                                                   \
+    const RowStream rst_ = row_stream((M), (row), (row_live));                                          \
+    uint32_t left = rst_.left;                                                                          \
+    uintptr_t pp = rst_.pp;                                                                             \
+    const uintptr_t last = rst_.last, pstr = rst_.pstride;                                              \
+    uint32_t sub = rst_.sub;                                                                            \
     uint32_t c0, c1, c2, c3, n0, n1, n2, n3;                                                            \
     {                                                                                                   \
-        const u32x4 a0_ = *(gp_u32x4)pp, a1_ = *(gp_u32x4)(pp + 16u < last ? pp + 16u : last);          \
+        const u32x4 a0_ = *(gp_u32x4)pp, a1_ = *(gp_u32x4)(pp + pstr < last ? pp + pstr : last);        \
         c0 = a0_.x; c1 = a0_.y; c2 = a0_.z; c3 = a0_.w;                                                 \
         n0 = a1_.x; n1 = a1_.y; n2 = a1_.z; n3 = a1_.w;                                                 \
     }                                                                                                   \
-    u32x4 fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                         \
+    u32x4 fut = *(gp_u32x4)(pp + 2u * pstr < last ? pp + 2u * pstr : last);                             \
     int pos = 0
 
 // Table entry of the codeword at index `at` (0..15) of the window (anything when at > 15:
@@ -144,11 +132,11 @@ __device__ __forceinline__ void lds_barrier()
         {                                                                                               \
             const bool s8_ = sub >= 8u;                                                                 \
             sub -= s8_ ? 8u : 0u;                                                                       \
-            pp += s8_ ? 16u : 0u;                                                                       \
+            pp += s8_ ? pstr : (uintptr_t)0;                                                            \
             const uint32_t f0_ = fut.x, f1_ = fut.y, f2_ = fut.z, f3_ = fut.w;                          \
             c0 = s8_ ? n0 : c0; c1 = s8_ ? n1 : c1; c2 = s8_ ? n2 : c2; c3 = s8_ ? n3 : c3;             \
             n0 = s8_ ? f0_ : n0; n1 = s8_ ? f1_ : n1; n2 = s8_ ? f2_ : n2; n3 = s8_ ? f3_ : n3;         \
-            fut = *(gp_u32x4)(pp + 32u < last ? pp + 32u : last);                                       \
+            fut = *(gp_u32x4)(pp + 2u * pstr < last ? pp + 2u * pstr : last);                           \
         }                                                                                               \
         AFTER_WAIT                                                                                      \
         /* No branches inside the inner loop: a lane that sits out decodes an empty entry into */      \
@@ -214,22 +202,11 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     const int r0 = blk * a.mm_rows_per_block;
     const int row = r0 + tid;
     const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
-    uint32_t left = 0;                                               // codewords to go
-    uintptr_t pp = reinterpret_cast<uintptr_t>(M.codes), last = pp;  // first piece of the window, the lane's last piece
-    uint32_t ci = 0;                                                 // index of the next codeword, counted from piece 0
-    if (row_live) {
-        gp_u32 row_off = (gp_u32)M.row_off;
-        const uint32_t cap = min(M.n_codes, kMaxCodes);
-        const uint32_t K1 = min(row_off[row + 1], cap);
-        const uint32_t K0 = min(row_off[row], K1);
-        left = K1 - K0;
-        // a row without codewords reads the matrix's first piece, never past the stream's end
-        const uintptr_t first_byte = reinterpret_cast<uintptr_t>(M.codes) + (left ? 2 * (uintptr_t)K0 : (uintptr_t)0);
-        const uint32_t lead = (uint32_t)(first_byte & 15u);
-        pp = first_byte - lead;
-        ci = lead >> 1;
-        last = pp + 16u * (uintptr_t)(left ? ((lead + 2u * left + 15u) >> 4) - 1u : 0u);
-    }
+    const RowStream rst = row_stream(M, row, row_live);
+    uint32_t left = rst.left;                  // codewords to go
+    uintptr_t pp = rst.pp;                     // first piece of the window
+    const uintptr_t last = rst.last, pstr = rst.pstride;
+    uint32_t ci = rst.sub;                     // index of the next codeword, counted from piece 0
     const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
     const uint32_t slot = win + (uint32_t)(tid * kMmWinBytes);
     auto piece_at = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
@@ -240,37 +217,51 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     };
     auto code_at = [&](uint32_t i) -> uint32_t { return (uint32_t)(*(lp_u16)(uintptr_t)(slot + 2u * (i & 15u))); };
     {
-        const u32x4 p0 = piece_at(pp), p1 = piece_at(pp + 16u);
+        const u32x4 p0 = piece_at(pp), p1 = piece_at(pp + pstr);
         store_piece(0u, p0);
         store_piece(16u, p1);
     }
-    u32x4 fut = piece_at(pp + 32u);
+    u32x4 fut = piece_at(pp + 2u * pstr);
     uint32_t wbase = 0;   // index of the first codeword of the window's first piece (a multiple of 8)
 #pragma unroll
     for (int i = 0; i < kMmRing / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
 
     // ---- this lane's part of the activations: token 16 * mb + l16, columns 8 * lg .. 8 * lg + 7 of every 32
     uintptr_t xsrc[MB];
+    uint32_t xmul[MB];  // bytes from one column's value to the next column's, in units of 2: 1, or (tiled) the block's tokens
     bool x_ok[MB];
     const bool x_col = 8 * lg + 8 <= a.cols;
 #pragma unroll
     for (int mb = 0; mb < MB; mb++) {
         const int t = 16 * mb + l16;
         x_ok[mb] = t < ntok;
-        size_t xrow = 0;
-        if (x_ok[mb]) {
-            const int tok = a.perm ? a.perm[slot0 + t] : slot0 + t;
-            xrow = a.x_by_slot ? (size_t)(slot0 + t) : (size_t)tok;
+        xmul[mb] = 1u;
+        // (a lane whose columns do not exist -- fewer than 8 * lg + 8 columns -- reads column 0 and drops it;
+        // a lane without a token reads the block's first token, or row 0)
+        const size_t col0 = x_col ? 8 * (size_t)lg : (size_t)0;
+        if (a.x_tiled) {
+            const int tb = min(16, ntok - 16 * mb);  // tokens in this block (<= 0: no such block)
+            const size_t block0 = tb > 0 ? (size_t)(slot0 + 16 * mb) : (size_t)slot0;
+            const size_t j = x_ok[mb] ? (size_t)l16 : (size_t)0;
+            xmul[mb] = (uint32_t)max(tb, 1);
+            xsrc[mb] = reinterpret_cast<uintptr_t>(a.x) + 2 * (block0 * (size_t)a.ldx + col0 * (size_t)xmul[mb] + 8 * j);
+        } else {
+            size_t xrow = 0;
+            if (x_ok[mb]) {
+                const int tok = a.perm ? a.perm[slot0 + t] : slot0 + t;
+                xrow = a.x_by_slot ? (size_t)(slot0 + t) : (size_t)tok;
+            }
+            xsrc[mb] = reinterpret_cast<uintptr_t>(a.x) + 2 * (xrow * (size_t)a.ldx + col0);
         }
-        // (a lane whose columns do not exist -- fewer than 8 * lg + 8 columns -- reads column 0 and drops it)
         x_ok[mb] = x_ok[mb] && x_col;
-        xsrc[mb] = reinterpret_cast<uintptr_t>(a.x) + 2 * (xrow * (size_t)a.ldx + (x_col ? 8 * (size_t)lg : (size_t)0));
     }
     // Loads are unconditional (a lane without a token, or past the last column, reads a valid
     // address -- column 8 * lg of some row -- and drops the value): a load under a branch would
     // be waited for at the end of the branch instead of staying in flight.
     const int x_last = x_col ? a.cols - 8 * lg - 8 : 0;  // last column offset this lane may read at
-    auto load_x = [&](int mb, int k) -> u32x4 { return *(gp_u32x4)(xsrc[mb] + 2 * (uintptr_t)min(k, x_last)); };
+    auto load_x = [&](int mb, int k) -> u32x4 {
+        return *(gp_u32x4)(xsrc[mb] + 2 * (uintptr_t)xmul[mb] * (uintptr_t)min(k, x_last));
+    };
     auto keep_x = [&](int mb, const u32x4 &v, int k) -> u32x4 {
         return (x_ok[mb] && k <= x_last) ? v : u32x4{0u, 0u, 0u, 0u};
     };
@@ -334,8 +325,8 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                 const bool s8 = ci - wbase >= 8u;
                 if (s8) store_piece(2u * (wbase & 8u), fut);
                 wbase += s8 ? 8u : 0u;
-                pp += s8 ? 16u : 0u;
-                fut = piece_at(pp + 32u);
+                pp += s8 ? pstr : (uintptr_t)0;
+                fut = piece_at(pp + 2u * pstr);
             }
             if (first) {
                 // the next step's activations: fetched right after the window's wait, a whole step ahead
@@ -430,8 +421,12 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                             reinterpret_cast<float *>(a.out)[(size_t)tok_ids[t] * a.ld_out + r] = gate_s[t] * val;
                         } else {
                             const float h = val > 0.0f ? val : 0.0f;
-                            reinterpret_cast<uint16_t *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] =
-                                float_to_bf16_bits(h);
+                            size_t at = (size_t)(slot0 + t) * a.ld_out + r;
+                            if (a.out_tiled) {
+                                const int tb = min(16, ntok - 16 * mb);
+                                at = (size_t)(slot0 + 16 * mb) * a.ld_out + ((size_t)(r >> 3) * tb + (4 * lg + v)) * 8 + (r & 7);
+                            }
+                            reinterpret_cast<uint16_t *>(a.out)[at] = float_to_bf16_bits(h);
                         }
                     }
                 }

@@ -77,16 +77,31 @@ class DeviceLayer:
         self._host[which][e] = (codes, row_off.astype(np.uint32), scale)
         self.n_codes[which][e] = codes.size
 
-    def finalize(self, device_order_of: "DeviceDict | None" = None):
-        """Upload everything; with device_order_of, renumber the streams for that dictionary."""
+    def finalize(self, device_order_of: "DeviceDict | None" = None, lanes_for_tokens: int = 0):
+        """Upload everything; with device_order_of, renumber the streams for that dictionary; with
+        lanes_for_tokens (a typical token count of the calls to come; needs device_order_of), re-pack
+        every stream into the lane-interleaved layout for the lane count the planner picks."""
         self.code_order = 0 if device_order_of is None else 1
         self.format = self.code_order | (B.FORMAT_GRID_MINMAX if self.minmax else 0)
         per_row = 2 if self.minmax else 1  # 16-bit values of scale data per row
         self.bufs, self.desc_dev, self.desc_host = {}, {}, {}
+        self.lanes = {"wi": 0, "wo": 0}
         for which in ("wi", "wo"):
             rows = self.d_ff if which == "wi" else self.d_model
             cols = self.d_model if which == "wi" else self.d_ff
             parts = self._host[which]
+            lanes = 0
+            wave_off = None
+            if lanes_for_tokens > 0:
+                assert device_order_of is not None
+                lanes = B.qmoe_plan_lanes(device_order_of.handle, rows, cols, self.n_experts, lanes_for_tokens)
+                self.lanes[which] = lanes
+                wave_off = np.zeros((self.n_experts, lanes // 64 + 1), dtype=np.uint32)
+                for e, p in enumerate(parts):
+                    if p is not None:
+                        pieces, wave_off[e] = B.qmoe_lane_layout_build(p[0], p[1], rows, lanes)
+                        parts[e] = (pieces, p[1], p[2])  # the stream as the device holds it (padding included)
+                        self.n_codes[which][e] = pieces.size
             code_off, total = [], 0
             for p in parts:
                 code_off.append(total)
@@ -106,6 +121,7 @@ class DeviceLayer:
                 B.qmoe_codes_to_device_order(device_order_of.handle, d_codes)
             d_row = torch.from_numpy(row_off.view(np.int32)).to(self.device)
             d_scale = torch.from_numpy(scale.view(np.int16)).to(self.device)
+            d_wave = None if wave_off is None else torch.from_numpy(wave_off.view(np.int32)).to(self.device)
             descs = (B.qmoe_matrix * self.n_experts)()
             for e, p in enumerate(parts):
                 if p is None:
@@ -114,12 +130,19 @@ class DeviceLayer:
                 descs[e] = B.qmoe_matrix(d_codes.data_ptr() + 2 * code_off[e],
                                          d_row.data_ptr() + 4 * e * (rows + 1),
                                          None if self.minmax else at, rows, cols, int(p[0].size), self.code_order,
-                                         at if self.minmax else None)
+                                         at if self.minmax else None,
+                                         None if d_wave is None else d_wave.data_ptr() + 4 * e * (lanes // 64 + 1), lanes, 0)
             raw = np.frombuffer(bytes(descs), dtype=np.uint8).copy()
-            self.bufs[which] = (d_codes, d_row, d_scale)
+            self.bufs[which] = (d_codes, d_row, d_scale, d_wave)
             self.desc_host[which] = descs
             self.desc_dev[which] = torch.from_numpy(raw).to(self.device)
-            self.compressed_bytes += sum(2 * p[0].size + (4 + 2 * per_row) * rows for p in parts if p is not None)
+            # bytes of a matrix as the device holds it: codewords (lane-interleaved: padding included),
+            # per row a 4-byte offset and the scale (pair), per group of 64 lanes a 4-byte piece offset
+            self.row_meta = 4 + 2 * per_row
+            self.matrix_meta = {**getattr(self, "matrix_meta", {}), which: self.row_meta * rows + (4 * (lanes // 64 + 1) if lanes else 0)}
+            self.compressed_bytes += sum(2 * p[0].size + self.matrix_meta[which] for p in parts if p is not None)
+        if self.lanes["wi"]:
+            self.format |= B.format_lanes(self.lanes["wi"], self.lanes["wo"])
         self._host = None
         return self
 
@@ -152,5 +175,20 @@ def read_workspace(workspace: torch.Tensor, n_experts: int, d_model: int, d_ff: 
         "items_wi": view(l.items_wi, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
         "items_wo": view(l.items_wo, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
         "items_mm": view(l.items_mm, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
-        "hidden": view(l.hidden, n_tokens * d_ff, np.uint16).reshape(n_tokens, d_ff),
+        "hidden": _untile_hidden(view(l.hidden, n_tokens * d_ff, np.uint16).reshape(n_tokens, d_ff),
+                                 view(l.items_mm, 4 * n_tokens, np.int32).reshape(n_tokens, 4),
+                                 int(view(l.counters, 16, np.int32)[7]), d_ff),
     }
+
+
+def _untile_hidden(hidden: np.ndarray, items_mm: np.ndarray, n_mm: int, d_ff: int) -> np.ndarray:
+    """The hidden vectors by slot.  The matrix-core kernels keep those of their tiles in blocks of up to
+    16 tokens, [8-column group][token of the block][8 columns], in the bytes of the same slots: put
+    them back into [slot][column] order (a permutation of the buffer, no arithmetic)."""
+    out = hidden.copy()
+    for _, slot0, ntok, _ in items_mm[:n_mm]:
+        for b0 in range(0, int(ntok), 16):
+            tb = min(16, int(ntok) - b0)
+            blk = hidden[slot0 + b0: slot0 + b0 + tb].reshape(-1)          # the block's bytes, as stored
+            out[slot0 + b0: slot0 + b0 + tb] = blk.reshape(d_ff // 8, tb, 8).transpose(1, 0, 2).reshape(tb, d_ff)
+    return out

@@ -197,7 +197,8 @@ def test_dispatch_bit_exact(gpu, E, T, seed, order):
     dd.close()
 
 
-def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None, minmax=False):
+def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=None, order_of=None, minmax=False,
+                 lanes_for_tokens=0):
     layer = dev.DeviceLayer(w.n_experts, w.d_model, w.d_ff, gpu, minmax=minmax)
     for e in (range(w.n_experts) if experts is None else experts):
         for which, tern, scale in (("wi", w.wi_ternary(e), w.wi_minmax(e) if minmax else w.wi_scale(e)),
@@ -207,7 +208,7 @@ def _build_layer(w, oracle_dict, gpu, encoder="oracle", lib_dict=None, experts=N
             else:
                 codes, row_off = q.qmoe_encode_host(lib_dict, tern)
             layer.set_expert(e, which, codes, row_off, scale)
-    return layer.finalize(device_order_of=order_of)
+    return layer.finalize(device_order_of=order_of, lanes_for_tokens=lanes_for_tokens)
 
 
 def _run_layer(layer, ddict, x_bits, idx, gpu, gate=None):
@@ -587,8 +588,9 @@ def test_bf16_comparator_close_to_the_compressed_layer(gpu, ddict, oracle_dict):
 # own dictionary and encoder, device-order streams, sampled tokens checked one
 # by one against the oracle (which regenerates and multiplies the expert densely).
 
-def _full_layer(w, gpu, minmax=False):
-    """minmax: the same streams on the asymmetric grid (bf16 pairs in place of the scales)."""
+def _full_layer(w, gpu, minmax=False, lanes_for_tokens=0):
+    """minmax: the same streams on the asymmetric grid (bf16 pairs in place of the scales);
+    lanes_for_tokens: the streams re-packed into the lane-interleaved layout."""
     import os
     from concurrent.futures import ThreadPoolExecutor
     dd = dev.DeviceDict(device=gpu)
@@ -608,7 +610,7 @@ def _full_layer(w, gpu, minmax=False):
             for which, codes, row_off, scale in parts:
                 layer.set_expert(e, which, codes, row_off, scale)
     q.qmoe_set_tuning("host_threads", 0)
-    return dd, layer.finalize(device_order_of=dd)
+    return dd, layer.finalize(device_order_of=dd, lanes_for_tokens=lanes_for_tokens)
 
 
 def _sample_tokens(idx, n_experts, per_class=4):
@@ -641,6 +643,71 @@ def test_c2048_layer_full_size_sampled(gpu, oracle_dict):
     _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts))
     y2, _ = _run_layer(layer, dd, x, idx, gpu)
     assert np.array_equal(y, y2)  # run-to-run bitwise identical
+    dd.close()
+
+
+# ---------------------------------------------------------------- the lane-interleaved layout
+#
+# Same codewords, re-packed when the layer is loaded so that the 64 loads of a wavefront of the
+# scalar kernel are one run of memory; every kernel of a layer call and the decompression read it.
+
+@pytest.mark.parametrize("d_model,d_ff,tokens", [(96, 200, 70), (260, 300, 70), (450, 228, 9), (136, 600, 40)])
+def test_small_layer_lane_interleaved_every_token(gpu, ddict, oracle_dict, d_model, d_ff, tokens):
+    """Rows on both sides of 224 columns, fewer rows than lanes, lanes with unequal row counts; tiles of one to
+    four tokens and (second call) the matrix-core kernel; the answers equal those of the plain layout bit for bit."""
+    w = synth.WORKLOADS["switch_base128"].scaled(n_experts=12, d_model=d_model, d_ff=d_ff, n_tokens=tokens)
+    idx, x = w.expert_idx(), w.tokens()
+    idx[5: 5 + tokens // 2] = 3  # one expert with many tokens
+    idx[idx == 7] = 8            # at least one expert without tokens
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict, lanes_for_tokens=tokens)
+    plain = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    assert layer.lanes["wi"] % 64 == 0 and layer.lanes["wo"] % 64 == 0 and layer.format >> 8
+    gate = np.random.default_rng(7).uniform(0.2, 1.0, idx.size)
+    y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
+    _check_layer(w, idx, x, y, wsout, list(range(idx.size)), gate)
+    y_plain, _ = _run_layer(plain, ddict, x, idx, gpu, gate)
+    assert np.array_equal(y, y_plain)
+    q.qmoe_set_tuning("mfma_min_tokens", 8)
+    try:
+        y2, ws2 = _run_layer(layer, ddict, x, idx, gpu, gate)
+        assert (ws2["counters"][7] >= 1) == (d_model % 8 == 0 and d_ff % 8 == 0 and tokens >= 16)
+        _check_layer(w, idx, x, y2, ws2, list(range(idx.size)), gate)
+        y2_plain, _ = _run_layer(plain, ddict, x, idx, gpu, gate)
+        assert np.array_equal(y2, y2_plain)
+    finally:
+        q.qmoe_set_tuning("mfma_min_tokens", 0)
+    # decompression reads the layout too
+    out = torch.zeros((w.n_experts, w.d_ff, w.d_model), dtype=torch.int8, device=gpu) if d_model % 8 == 0 else None
+    if out is not None:
+        ptrs = torch.tensor([out[e].data_ptr() for e in range(w.n_experts)], dtype=torch.int64, device=gpu)
+        q.qmoe_decompress(ddict.handle, layer.desc_dev["wi"], layer.format, w.n_experts, w.d_ff, w.d_model, 0, ptrs)
+        torch.cuda.synchronize()
+        for e in range(w.n_experts):
+            assert np.array_equal(out[e].cpu().numpy(), w.wi_ternary(e))
+    # a single-matrix call refuses the layout; a layer call refuses lane counts its launch cannot take
+    with pytest.raises(q.QmoeError):
+        q.qmoe_decode_matvec(ddict.handle, layer.desc_host["wi"][0], _to_dev16(x[:1], gpu),
+                             torch.empty((1, d_ff), dtype=torch.float32, device=gpu))
+    with pytest.raises(q.QmoeError):
+        q.qmoe_moe_layer_forward(ddict.handle, layer.desc_dev["wi"], layer.desc_dev["wo"], 1 | q.format_lanes(64, 0),
+                                 w.n_experts, d_model, d_ff, _to_dev16(x, gpu), torch.from_numpy(idx).to(gpu), None,
+                                 torch.empty((idx.size, d_model), dtype=torch.float32, device=gpu),
+                                 layer.workspace(idx.size))
+    torch.cuda.synchronize()
+
+
+def test_c2048_lane_interleaved_full_size_sampled(gpu, oracle_dict):
+    """The benchmark's layer in the lane-interleaved layout: sampled tokens against the oracle, and the
+    padding of the layout stays small."""
+    w = synth.WORKLOADS["c2048"]
+    idx, x = w.expert_idx(), w.tokens()
+    dd, layer = _full_layer(w, gpu, lanes_for_tokens=idx.size)
+    y, wsout = _run_layer(layer, dd, x, idx, gpu)
+    assert np.isfinite(y).all()
+    _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts))
+    e = int(idx[0])
+    oc, _ = oracle.encode(oracle_dict, w.wo_ternary(e))
+    assert oc.size <= layer.n_codes["wo"][e] <= 1.06 * oc.size  # padding of the layout: a few per cent
     dd.close()
 
 

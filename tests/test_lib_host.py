@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     L = q.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert ctypes.sizeof(q.qmoe_matrix) == 48 and q.qmoe_matrix.minmax_bf16.offset == 40
+    assert ctypes.sizeof(q.qmoe_matrix) == 64 and q.qmoe_matrix.minmax_bf16.offset == 40
     assert (q.FORMAT_DEVICE_ORDER, q.FORMAT_GRID_MINMAX) == (1, 2)
     assert L.qmoe_strerror(0) == b"ok" and L.qmoe_strerror(-4) == b"corrupt codeword stream"
     # run entries, interchange words, device-order table and map, then the encoder's trie (2^17 nodes)
@@ -286,3 +286,46 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0 and r.stdout.strip() == ""
     assert "one GPU" in r.stderr
+
+
+def test_lane_layout_round_trip_and_placement(lib_dict):
+    """The lane-interleaved layout is a re-packing of the same codewords: piece p of lane g sits at
+    wave_off[g // 64] + 64 p + g % 64, lanes own rows by the even split, padding is zero, and
+    unpacking gives the stream back."""
+    rng = np.random.default_rng(3)
+    for rows, cols, lanes in [(300, 280, 128), (64, 56, 64), (50, 120, 64), (777, 96, 192)]:
+        tern = synth.ternary(4000 + rows, rows, cols, 0.9)
+        codes, row_off = q.qmoe_encode_host(lib_dict, tern)
+        pieces, wave_off = q.qmoe_lane_layout_build(codes, row_off, rows, lanes)
+        assert pieces.size % 8 == 0 and wave_off[0] == 0 and 8 * int(wave_off[-1]) == pieces.size
+        base, extra = divmod(rows, lanes)
+        seen = np.zeros(pieces.size, dtype=bool)
+        for g in range(lanes):
+            ra = g * base + min(g, extra)
+            rb = ra + base + (1 if g < extra else 0)
+            mine = codes[row_off[ra]: row_off[rb]]
+            for p in range((mine.size + 7) // 8):
+                at = 8 * (int(wave_off[g // 64]) + 64 * p + g % 64)
+                want = np.zeros(8, dtype=np.uint16)
+                want[: min(8, mine.size - 8 * p)] = mine[8 * p: 8 * p + 8]
+                assert np.array_equal(pieces[at: at + 8], want)
+                seen[at: at + 8] = True
+            # a group of 64 lanes is as long as its longest lane
+            assert (mine.size + 7) // 8 <= (int(wave_off[g // 64 + 1]) - int(wave_off[g // 64])) // 64
+        assert not pieces[~seen].any()
+        assert np.array_equal(q.qmoe_lane_layout_unpack(pieces, wave_off, row_off, rows, lanes), codes)
+    L = q.lib()
+    n = ctypes.c_size_t()
+    ro = np.array([0, 3, 5], dtype=np.uint32)
+    assert L.qmoe_lane_layout_size(ro.ctypes.data, 2, 100, ctypes.byref(n)) == -1     # lanes not a multiple of 64
+    assert L.qmoe_lane_layout_size(ro.ctypes.data, 2, 64, None) == -1
+    assert L.qmoe_lane_layout_size(ro.ctypes.data, 2, 64, ctypes.byref(n)) == 0 and n.value == 64
+    bad = np.array([0, 5, 3], dtype=np.uint32)
+    assert L.qmoe_lane_layout_size(bad.ctypes.data, 2, 64, ctypes.byref(n)) == -4     # offsets that decrease
+    out = np.zeros(8 * 64, dtype=np.uint16)
+    wo = np.zeros(2, dtype=np.uint32)
+    c = np.arange(5, dtype=np.uint16)
+    assert L.qmoe_lane_layout_build(c.ctypes.data, ro.ctypes.data, 2, 64, out.ctypes.data, 63, wo.ctypes.data) == -2
+    assert L.qmoe_lane_layout_build(c.ctypes.data, ro.ctypes.data, 2, 64, out.ctypes.data, 64, wo.ctypes.data) == 0
+    assert out[:3].tolist() == [0, 1, 2] and out[8:10].tolist() == [3, 4]  # lane 0 owns row 0, lane 1 row 1
+    assert L.qmoe_plan_lanes(None, 8, 16, 4, 4) == 0
