@@ -99,25 +99,30 @@ def dense_bf16_experts(layer, dd, active, gpu, stats=None):
     return ptrs["wi"], ptrs["wo"], keep
 
 
-def single_matvec(w, layer, dd, gpu, expert):
-    """The paper's per-matrix benchmark: one compressed expert matrix times one token
-    (`qmoe_decode_matvec`) next to torch.matmul on the same matrix in bf16, back-to-back
-    launches, microseconds per call."""
+def single_matvec(w, dd, gpu, expert, minmax=False):
+    """The paper's per-matrix benchmark: one compressed expert matrix (rows back to back, device
+    numbering) times one token (`qmoe_decode_matvec`) next to torch.matmul on the same matrix in bf16,
+    back-to-back launches, microseconds per call."""
     import torch
     import paper_2310_16795_amd as q
+    from paper_2310_16795_amd import device as dev
 
     out = {}
     for which in ("wi", "wo"):
-        rows = layer.d_ff if which == "wi" else layer.d_model
-        cols = layer.d_model if which == "wi" else layer.d_ff
-        desc = layer.desc_host[which][expert]
+        tern = w.wi_ternary(expert) if which == "wi" else w.wo_ternary(expert)
+        rows, cols = tern.shape
+        codes, row_off = q.qmoe_encode_host(dd.handle, tern)
+        scale = None if minmax else (w.wi_scale(expert) if which == "wi" else w.wo_scale(expert))
+        pairs = (w.wi_minmax(expert) if which == "wi" else w.wo_minmax(expert)) if minmax else None
+        M = dev.DeviceMatrix(codes, row_off, scale, rows, cols, device=gpu, device_order_of=dd, minmax_bf16=pairs)
         x = torch.randn(1, cols, device=gpu).to(torch.bfloat16)
         y = torch.empty(1, rows, dtype=torch.float32, device=gpu)
         dense = torch.empty((rows, cols), dtype=torch.bfloat16, device=gpu)
-        one = ctypes.sizeof(q.qmoe_matrix)  # the descriptor of this expert alone
-        q.qmoe_decompress(dd.handle, layer.desc_dev[which][one * expert: one * (expert + 1)], layer.format, 1, rows, cols, 1,
+        desc_dev = torch.from_numpy(np.frombuffer(bytes(M.desc), dtype=np.uint8).copy()).to(gpu)
+        fmt = q.FORMAT_DEVICE_ORDER | (q.FORMAT_GRID_MINMAX if minmax else 0)
+        q.qmoe_decompress(dd.handle, desc_dev, fmt, 1, rows, cols, 1,
                           torch.tensor([dense.data_ptr()], dtype=torch.int64, device=gpu))
-        t_c, _ = time_steps(lambda: q.qmoe_decode_matvec(dd.handle, desc, x.view(torch.int16), y), 200, 20)
+        t_c, _ = time_steps(lambda: q.qmoe_decode_matvec(dd.handle, M.desc, x.view(torch.int16), y), 200, 20)
         t_b, _ = time_steps(lambda: torch.matmul(x, dense.T), 200, 20)
         ref = torch.matmul(x.float(), dense.float().T)
         out[which] = {"rows": rows, "cols": cols, "compressed_us": t_c * 1e3, "bf16_torch_matmul_us": t_b * 1e3,
@@ -368,13 +373,23 @@ def main():
     copy_gbps = 2 * src.numel() / (copy_ms * 1e-3) / 1e9
     del src, dst
 
-    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    # (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for k_stream_copy)
-    traffic = None
+    # HBM bytes per launch of the dominant kernel: not measured by this run (counters need the profiler) but
+    # read from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+    # counter reads for k_stream_copy) -- and only if that summary was taken from the kernel sources present
+    from paper_2310_16795_amd import build as lib_build
+    traffic, traffic_source = None, "none"
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tpath) and not minmax:  # the committed counters are the headline format's
+    if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(dom_key)
+            tj = json.load(f)
+        same = tj.get("kernel_sources") == lib_build.kernel_sources_hash()
+        fits = tj.get("layout") == args.layout and not minmax and not custom_dict and not args.interchange_order and not args.tune
+        if same and fits:
+            traffic = tj["bytes_per_launch"].get(dom_key)
+            traffic_source = f"profiles/traffic_{w.name}.json: {tj.get('command', 'rocprofv3 --pmc')}"
+        else:
+            traffic_source = (f"none: profiles/traffic_{w.name}.json was measured for " +
+                              ("other kernel sources" if not same else "another configuration"))
 
     result = {
         "metric": "compressed_weight_GBps", "value": weight_bytes / (ms * 1e-3) / 1e9, "unit": "GB/s",
@@ -389,7 +404,7 @@ def main():
                    "grid": "{w_min,0,w_max}, bf16 pair per row" if minmax else "{-s,0,+s}, binary16 scale per row",
                    "dict_entries": args.dict_entries, "dict_max_pairs": args.dict_max_pairs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": dom[0],
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source, "kernel": dom[0],
                      "kernel_ms": dom[1], "algorithmic_bytes": dom[2]},
         "hbm_frac_whole_step": weight_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "ms_per_step_spread": spread,
@@ -415,7 +430,7 @@ def main():
     }
 
     if not args.interchange_order:
-        result["single_matvec_batch1"] = single_matvec(w, layer, dd, gpu, active[0])
+        result["single_matvec_batch1"] = single_matvec(w, dd, gpu, active[0], minmax)
 
     if not args.no_bf16:
         t0 = time.time()

@@ -296,8 +296,9 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
                               int path, void *stream);
 
 /*
- * Decompress whole matrices (the codec of Section 4.3.3 without the product; the
- * "decompress, then a standard matrix product" alternative named in Section 5.3):
+ * Decompress whole matrices (the codec of Section 4.3.3 without the product; the first
+ * half of the alternative Section 5.3 names for experts with many tokens: decompress, then
+ * multiply with a library routine):
  * out[m] receives matrix mats[m], row-major rows x cols, as int8 in {-1, 0, +1}
  * (out_kind 0) or as bf16 with the row scale folded in, bf16(s_r) * w (out_kind 1; with
  * QMOE_FORMAT_GRID_MINMAX the row's own w_min / w_max, which are bf16 already).
@@ -407,8 +408,8 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
                               void *workspace /*device*/, size_t workspace_bytes, void *stream);
 
 /*
- * The same layer on uncompressed weights, for the "uncompressed bf16
- * execution" the paper compares against (Section 5.3): wi_dense[e] / wo_dense[e]
+ * The same layer on uncompressed bf16 weights, the execution the paper compares
+ * against (Section 5.3): wi_dense[e] / wo_dense[e]
  * are device pointers to row-major bf16 matrices that already include the row
  * scales (NULL allowed for experts without tokens).  Same dispatch, same
  * workspace, same outputs.

@@ -18,7 +18,8 @@
  *
  * Readings of the paper taken here:
  *  - a sequence holds 1..max_pairs pairs, max_pairs = 14 by default (the
- *    text's "at most 14 such pairs" and the 2 x 7 slots of the entry format;
+ *    pair limit stated in the text of Section 4.3.2 above Algorithm 1, and the 2 x 7 slots
+ *    of the entry format;
  *    Algorithm 1's strict "< 28" would leave the last slot unused);
  *  - the queue orders by probability, computed as a*ln(p0) + b*ln(q) from
  *    the integer counts a = #zeros, b = #non-zeros (q = (1-p0)/2), so that

@@ -55,6 +55,19 @@ def sources_hash() -> str:
     return h.hexdigest()
 
 
+KERNEL_SOURCES = ["qmoe_dev.h", "qmoe_product.h", "qmoe_product_sym.hip", "qmoe_product_asym.hip", "qmoe_product_mm.hip"]
+
+
+def kernel_sources_hash() -> str:
+    """Hash of the files that define the product kernels: measured figures kept under profiles/
+    (HBM traffic per launch) carry it, so that a figure taken from other kernels is recognised."""
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(CSRC, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def stale() -> bool:
     """True when the built library is missing or was built from other sources than the ones present
     (contents are compared, not time stamps, which a copy of the tree need not preserve)."""

@@ -192,9 +192,16 @@ qmoe_status plan_product(int rows, int cols, bool run_table, long long max_passe
     if (force_lanes > 0) {
         // streams in the lane-interleaved layout: workgroups x lanes must be the count the layout was
         // built for; as few workgroups per matrix as the workgroup size allows
+        // (the split the search above found if it has that many lanes, else the nearest one that does)
+        auto fits = [&](int b) {
+            return b >= 1 && force_lanes % b == 0 && (force_lanes / b) % 64 == 0 && force_lanes / b <= max_threads;
+        };
+        const int want_b = best_b;
         best_b = 0;
-        for (int b = 1; b <= force_lanes / 64 && !best_b; b++)
-            if (force_lanes % b == 0 && (force_lanes / b) % 64 == 0 && force_lanes / b <= max_threads) best_b = b;
+        for (int d = 0; d <= force_lanes / 64 && !best_b; d++) {
+            if (fits(want_b + d)) best_b = want_b + d;
+            else if (fits(want_b - d)) best_b = want_b - d;
+        }
         if (!best_b) return QMOE_E_INVALID_ARG;
         best_t = force_lanes / best_b;
     }

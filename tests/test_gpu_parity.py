@@ -705,6 +705,11 @@ def test_c2048_lane_interleaved_full_size_sampled(gpu, oracle_dict):
     y, wsout = _run_layer(layer, dd, x, idx, gpu)
     assert np.isfinite(y).all()
     _check_layer(w, idx, x, y, wsout, _sample_tokens(idx, w.n_experts))
+    # every token of the busiest expert (several tiles of the matrix-core kernel, the last one partial)
+    counts = np.bincount(idx, minlength=w.n_experts)
+    busiest = int(np.argmax(counts))
+    assert counts[busiest] > 128
+    _check_layer(w, idx, x, y, wsout, [int(t) for t in np.nonzero(idx == busiest)[0]])
     e = int(idx[0])
     oc, _ = oracle.encode(oracle_dict, w.wo_ternary(e))
     assert oc.size <= layer.n_codes["wo"][e] <= 1.06 * oc.size  # padding of the layout: a few per cent
