@@ -228,7 +228,10 @@ qmoe_status launch_dispatch_kernel(const DispatchArgs &da, hipStream_t s)
     const size_t smem = sizeof(int) * ((size_t)da.n_experts + 256 + 2 * 1024);
     const qmoe_status st = allow_lds(k_dispatch, smem);
     if (st != QMOE_OK) return st;
-    hipLaunchKernelGGL(k_dispatch, dim3(1), dim3(1024), smem, s, da);
+    // small layers: fewer wavefronts meet at the kernel's barriers and the scan has fewer partial sums
+    const int need = da.n_tokens > da.n_experts ? da.n_tokens : da.n_experts;
+    const int threads = need <= 256 ? 256 : (need <= 512 ? 512 : 1024);
+    hipLaunchKernelGGL(k_dispatch, dim3(1), dim3(threads), smem, s, da);
     QMOE_HIP_TRY(hipGetLastError());
     return QMOE_OK;
 }

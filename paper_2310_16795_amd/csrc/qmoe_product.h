@@ -180,10 +180,7 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
             const uint32_t rec = pos[j];  // the activations begin at LDS address 0 (the caller checks)
 #pragma unroll
             for (int z = 0; z < 3; z++) {
-                uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
-#ifdef QMOE_PROBE_NOCONFLICT
-                addr = (addr & ~0xFCu) | ((threadIdx.x & 63u) << 2);  // timing probe only: every lane on a bank of its own (wrong numbers)
-#endif
+                const uint32_t addr = rec + ((e[j].e0 >> (8 + 8 * z)) & 0xFFu);
                 x[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)addr);
                 // the -x slot is 4 bytes after the +x slot; an unused field stays on the zero slot
                 if constexpr (ASYM) xa[3 * j + z] = (uint32_t)(*(lp_u16)(uintptr_t)(addr & ~4u));
@@ -212,14 +209,6 @@ __device__ __forceinline__ void consume8(const ProductArgs &a, LaneState<TBI, AS
                 part[j][NA - 1] = st.acc[NA - 1];
             }
         }
-#ifdef QMOE_SCHED_INTERLEAVE
-        // experiment: one LDS read, then QMOE_SCHED_INTERLEAVE vector instructions, over and over
-#pragma unroll
-        for (int i_ = 0; i_ < 32; i_++) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, QMOE_SCHED_INTERLEAVE, 0);
-        }
-#endif
     } else {
 #pragma unroll
         for (int j = 0; j < 8; j++) {

@@ -304,6 +304,9 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     uint32_t ent = order_entry(table, code_at(ci), n_groups, n_order);
     uint32_t ent_n = table[entry_index(c1)], flips_n = order_flips(c1);
     uint32_t pos8 = 0;  // 8 * (column where the next run starts)
+    // Nothing is in flight when the loop starts, so that the wait at the top of a round is for the two
+    // reads of the round before and not for the three stores issued after them.
+    asm volatile("" : "+v"(ent_n), "+v"(c1), "+v"(c2), "+v"(ent));
 
     u32x4 xa[MB][2];
 #pragma unroll
@@ -338,7 +341,9 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 #pragma unroll
                     for (int ks = 0; ks < 2; ks++) xn[mb][ks] = load_x(mb, k_next + 32 * ks);
             }
-            while (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u)) {
+            // (a loop with its test at the end: with the test in front the compiler keeps two copies of the
+            // decoder's state and moves all of it from one to the other every round)
+            if (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u)) do {
                 const bool go = left != 0u && pos8 <= lim8 && ci - wbase <= 12u;
                 // The entry this round applies; a lane that sits out applies an empty one, which stores
                 // three zeros at the column where its next run starts: nothing was written there yet, and
@@ -354,6 +359,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                 flips_n = order_flips(csel);
                 c1 = csel;
                 c2 = code_at(ci + 2u);
+                __builtin_amdgcn_sched_barrier(0);  // the round's two reads go out before the rest of its work
 #pragma unroll
                 for (int z = 0; z < kRunMaxNonzeros; z++) {
                     const uint32_t t = pos8 + ((e0 >> (8 + 8 * z)) & 0xFFu);  // 8 * column + the field's low three bits
@@ -364,7 +370,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                 }
                 pos8 += e0 & 0xFFu;
                 left -= go ? 1u : 0u;
-            }
+            } while (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u));
         } while (__any(left != 0u && pos8 < end8));
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
