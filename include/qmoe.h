@@ -306,7 +306,8 @@ qmoe_status qmoe_decode_dense(const qmoe_dict *d, const qmoe_matrix *W /*host*/,
  * (code_order must have QMOE_FORMAT_DEVICE_ORDER set).  out: device array [n_mats] of device pointers, 16-byte
  * aligned, NULL = skip that matrix.  cols must be a multiple of 8.  One launch for all
  * matrices; nothing is allocated.
- * Errors: INVALID_ARG, NO_DEVICE_DICT, LIMIT (no device order; cols > 32768), HIP.
+ * Errors: INVALID_ARG, NO_DEVICE_DICT, LIMIT (no device order; cols > 32768; more matrices in
+ * one call than the kernel's LDS has a bit for: about 20000 with the paper's table), HIP.
  */
 qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats /*device*/, int code_order,
                             int n_mats, int rows, int cols, int out_kind,

@@ -570,10 +570,12 @@ qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats, int cod
     a.order_table = reinterpret_cast<const uint32_t *>(static_cast<const unsigned char *>(d->dev) + kDevOrderTableOffset);
     a.n_groups = d->n_groups;
     a.n_order = (int)d->order_table.size();
-    const size_t smem = decompress_lds_bytes(a.n_order);
-    if (smem > (size_t)di.max_lds) return QMOE_E_LIMIT;
+    const size_t smem = decompress_lds_bytes(a.n_order, n_mats);
+    if (smem > (size_t)di.max_lds) return QMOE_E_LIMIT;  // (the paper's table leaves room for about 5000 matrices a call)
+    // one workgroup per compute unit (its LDS is taken whole); the kernel deals the matrices that have a
+    // destination out over them
     const long long total = (long long)n_mats * a.row_blocks;
-    const int grid = (int)std::min<long long>(total, 2LL * di.cus);
+    const int grid = (int)std::min<long long>(total, (long long)di.cus);
     return launch_decompress(a, out_kind, minmax, grid, smem, static_cast<hipStream_t>(stream));
 }
 

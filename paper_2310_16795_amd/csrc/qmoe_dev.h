@@ -175,7 +175,7 @@ size_t mm_lds_bytes(int n_order);                                               
 qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s, int rows_per_block = 0);
 void mm_rows(int rows, int *row_blocks, int *rows_per_block);
 qmoe_status launch_decompress(const DecompressArgs &a, int out_kind, bool minmax, int grid, size_t smem, hipStream_t s);
-size_t decompress_lds_bytes(int n_order);
+size_t decompress_lds_bytes(int n_order, int n_mats);  // table, rings, windows, one bit per matrix
 qmoe_status launch_matvec_rows(const ProductArgs &a, bool run, bool minmax, int grid, int threads, size_t smem,
                                hipStream_t s);                                                      // qmoe_matvec.hip
 qmoe_status launch_decode_dense(const ProductArgs &a, bool run, int8_t *out, int grid, hipStream_t s);

@@ -108,29 +108,46 @@ __global__ __launch_bounds__(1024) void k_encode_offsets(const EncodeArgs a)
 // ---------------------------------------------------------------- uncompressed bf16 comparator
 
 
-// One wavefront per row; a lane takes four consecutive columns at a time (8 bytes of
-// weights, coalesced to 512 bytes per wavefront) and the matching activations from
-// token-major fp32 planes in LDS (16 bytes per lane, consecutive lanes: conflict-free).
+// One wavefront per row; a lane takes eight consecutive columns at a time (16 bytes of
+// weights, 1 KiB per wavefront and load; rows whose width is no multiple of 8: four columns,
+// 8 bytes) and the matching activations from token-major fp32 planes in LDS (consecutive
+// lanes read consecutive 16-byte pieces).  The weight pointer comes out of an array in memory,
+// so it is given its address space by hand: through a generic pointer every load would also
+// count as LDS traffic and be waited for together with the reads of the activations.
 template <int TBI>
 __device__ __forceinline__ void dense_rows(const DenseArgs &a, const uint16_t *W, int ntok, int slot0,
                                            int r0, int r1, const float *xs, int plane, const int *tok_ids)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int nq = a.cols / 4;
+    const uintptr_t wbase = reinterpret_cast<uintptr_t>(W);
+    auto fma4 = [&](uint32_t qx, uint32_t qy, int c4, float (&acc)[TBI]) {
+        const float w0 = __uint_as_float(qx << 16), w1 = __uint_as_float(qx & 0xFFFF0000u);
+        const float w2 = __uint_as_float(qy << 16), w3 = __uint_as_float(qy & 0xFFFF0000u);
+#pragma unroll
+        for (int t = 0; t < TBI; t++) {
+            const float4 x = reinterpret_cast<const float4 *>(xs + (size_t)t * plane)[c4];
+            acc[t] = fmaf(w3, x.w, fmaf(w2, x.z, fmaf(w1, x.y, fmaf(w0, x.x, acc[t]))));
+        }
+    };
     for (int r = r0 + wave; r < r1; r += nwaves) {
-        const uint2 *wrow = reinterpret_cast<const uint2 *>(W + (size_t)r * a.cols);
+        const uintptr_t wrow = wbase + 2 * (size_t)r * a.cols;
         float acc[TBI];
 #pragma unroll
         for (int t = 0; t < TBI; t++) acc[t] = 0.0f;
+        if ((a.cols & 7) == 0) {
+            const int n8 = a.cols / 8;
 #pragma unroll 4
-        for (int c4 = lane; c4 < nq; c4 += 64) {
-            const uint2 q = wrow[c4];
-            const float w0 = __uint_as_float(q.x << 16), w1 = __uint_as_float(q.x & 0xFFFF0000u);
-            const float w2 = __uint_as_float(q.y << 16), w3 = __uint_as_float(q.y & 0xFFFF0000u);
-#pragma unroll
-            for (int t = 0; t < TBI; t++) {
-                const float4 x = reinterpret_cast<const float4 *>(xs + (size_t)t * plane)[c4];
-                acc[t] = fmaf(w3, x.w, fmaf(w2, x.z, fmaf(w1, x.y, fmaf(w0, x.x, acc[t]))));
+            for (int c8 = lane; c8 < n8; c8 += 64) {
+                const u32x4 q = ((gp_u32x4)wrow)[c8];
+                fma4(q.x, q.y, 2 * c8, acc);
+                fma4(q.z, q.w, 2 * c8 + 1, acc);
+            }
+        } else {
+            const int nq = a.cols / 4;
+#pragma unroll 4
+            for (int c4 = lane; c4 < nq; c4 += 64) {
+                const unsigned long long q = ((gp_u64)wrow)[c4];
+                fma4((uint32_t)q, (uint32_t)(q >> 32), c4, acc);
             }
         }
 #pragma unroll

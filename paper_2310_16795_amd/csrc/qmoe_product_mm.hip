@@ -62,6 +62,8 @@ __device__ __forceinline__ bf16x8 mm_expand_minmax(uint32_t d0, uint32_t d1, uin
     return r;
 }
 
+using gw_u64 = __attribute__((address_space(1))) unsigned long long *;
+using gw_u32x4 = __attribute__((address_space(1))) u32x4 *;
 using lw_u8 = __attribute__((address_space(3))) unsigned char *;
 using lw_u64 = __attribute__((address_space(3))) unsigned long long *;
 using lw_u32x4 = __attribute__((address_space(3))) u32x4 *;
@@ -70,99 +72,166 @@ using lp_u32x4 = const __attribute__((address_space(3))) u32x4 *;
 using lp_i32 = const __attribute__((address_space(3))) int *;
 using lp_f32 = const __attribute__((address_space(3))) float *;
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global
-// memory, which makes every wavefront wait for all its loads in flight: the prefetches
-// of codewords and activations would then be exposed at every step.
-__device__ __forceinline__ void lds_barrier()
+// ---- the ring decoder shared by the matrix-core product and the decompression kernel ----
+//
+// One lane = one row.  A lane's codewords pass through a window of two 16-byte pieces (sixteen
+// codewords) in LDS, the next piece is in flight in a register; the codeword two places ahead
+// is read from the window and the table entry one place ahead is looked up while the current
+// entry is applied.  Applying an entry is three one-byte stores into the lane's ring of 128
+// columns: field z goes to ring column (column + position) mod 128 with the value bits of the
+// field shifted to the top of the byte (0x40: +2.0, 0xC0: -2.0 as the high byte of bf16) or, for
+// the asymmetric grid, as they are (byte selectors 2 / 6); an unused field (0) comes first and
+// writes its zero at the run's first column before any real weight of the same run.
+//
+// (A struct of plain scalars and free functions that are always inlined: the state stays in
+// registers.)
+constexpr int kMmWinBytes = 40;   // a lane's window: two 16-byte pieces, padded so that the 64 slots spread over the banks
+
+struct RingDecoder {
+    uint32_t left;              // codewords to go
+    uint32_t ci;                // index of the next codeword, counted from the lane's first piece
+    uint32_t wbase;             // index of the first codeword of the window's first piece (a multiple of 8)
+    uint32_t pos8;              // 8 * (column where the next run starts)
+    uint32_t ent, ent_n, flips_n, c1, c2;  // the pipeline: entry of codeword ci, entry of ci + 1 as read and the
+                                           // sign flips of its code, codes of ci + 1 and ci + 2
+    uintptr_t pp, last, pstr;   // first piece of the window, the lane's last piece, bytes from a piece to the next
+    u32x4 fut;                  // the piece after the window, in flight
+    uint32_t wrow, slot;        // LDS byte addresses of the lane's ring and window
+};
+
+__device__ __forceinline__ u32x4 ring_piece_at(const RingDecoder &d, uintptr_t at)
 {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // pieces past the lane's last one re-read the last (never used: `left` runs out first)
+    return *(gp_u32x4)(at < d.last ? at : d.last);
 }
 
-// ---- the ring decoder shared by the matrix-core product and the decompression kernel ----
-// (macros rather than a struct with member functions: the decoder's state has to stay in
-// plain scalar registers, and the compiler keeps it there only when it sees scalars.)
+__device__ __forceinline__ void ring_store_piece(const RingDecoder &d, uint32_t half_bytes, const u32x4 &v)
+{
+    lw_u64 w = (lw_u64)(uintptr_t)(d.slot + half_bytes);
+    w[0] = (unsigned long long)v.x | ((unsigned long long)v.y << 32);
+    w[1] = (unsigned long long)v.z | ((unsigned long long)v.w << 32);
+}
+
+__device__ __forceinline__ uint32_t ring_code_at(const RingDecoder &d, uint32_t i)
+{
+    return (uint32_t)(*(lp_u16)(uintptr_t)(d.slot + 2u * (i & 15u)));
+}
+
+__device__ __forceinline__ uint32_t ring_entry_index(uint32_t code, uint32_t n_groups, uint32_t n_order)
+{
+    return min(max(code >> 2, __builtin_elementwise_sub_sat(code, 3u * n_groups)), n_order - 1u);
+}
+
+// The lane's row (none: an empty stream), its window filled, its ring cleared.
+__device__ __forceinline__ void ring_setup(RingDecoder &d, const qmoe_matrix &M, int row, bool row_live, uint32_t wrow,
+                                           uint32_t slot)
+{
+    const RowStream rst = row_stream(M, row, row_live);
+    d.left = rst.left;
+    d.pp = rst.pp;
+    d.last = rst.last;
+    d.pstr = rst.pstride;
+    d.ci = rst.sub;
+    d.wrow = wrow;
+    d.slot = slot;
+    {
+        const u32x4 p0 = ring_piece_at(d, d.pp), p1 = ring_piece_at(d, d.pp + d.pstr);
+        ring_store_piece(d, 0u, p0);
+        ring_store_piece(d, 16u, p1);
+    }
+    d.fut = ring_piece_at(d, d.pp + 2u * d.pstr);
+    d.wbase = 0;
+    d.pos8 = 0;
+#pragma unroll
+    for (int i = 0; i < kMmRing / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+}
+
+// Fill the pipeline.  Nothing is in flight afterwards, so that the wait at the top of a round is
+// for the two reads of the round before and not for the three stores issued after them.
+__device__ __forceinline__ void ring_prime(RingDecoder &d, lp_u32 table, uint32_t n_groups, uint32_t n_order)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    d.c1 = ring_code_at(d, d.ci + 1u);
+    d.c2 = ring_code_at(d, d.ci + 2u);
+    d.ent = order_entry(table, ring_code_at(d, d.ci), n_groups, n_order);
+    d.ent_n = table[ring_entry_index(d.c1, n_groups, n_order)];
+    d.flips_n = order_flips(d.c1);
+    asm volatile("" : "+v"(d.ent_n), "+v"(d.c1), "+v"(d.c2), "+v"(d.ent));
+}
+
+// Decode until every lane of the wavefront has passed column kc + 64.  A lane that is there
+// already keeps going as long as its next run starts at most kMmAhead columns past kc (its run
+// then ends below column kc + 128, the first one that shares a ring byte with the step), so
+// the lanes of a wavefront, whose codewords end at different columns, seldom wait for each
+// other.  `after_wait` runs once, right after the step's wait for global memory: the place
+// to issue loads that should stay in flight for a whole step.
 //
-// QMOE_RING_ROW_SETUP declares the state for one lane = one row: `left` codewords to go,
-// the stream in 16-byte pieces (eight codewords) -- c0..c3 and n0..n3 are the window the
-// decoder picks codewords from (index sub = 0..15), `fut` is in flight; pieces past the
-// lane's last one re-read the last (never used: `left` runs out first) -- and `pos`, the
-// column where the next codeword starts.
-#define QMOE_RING_ROW_SETUP(M, row, row_live)                                                           \
-    const RowStream rst_ = row_stream((M), (row), (row_live));                                          \
-    uint32_t left = rst_.left;                                                                          \
-    uintptr_t pp = rst_.pp;                                                                             \
-    const uintptr_t last = rst_.last, pstr = rst_.pstride;                                              \
-    uint32_t sub = rst_.sub;                                                                            \
-    uint32_t c0, c1, c2, c3, n0, n1, n2, n3;                                                            \
-    {                                                                                                   \
-        const u32x4 a0_ = *(gp_u32x4)pp, a1_ = *(gp_u32x4)(pp + pstr < last ? pp + pstr : last);        \
-        c0 = a0_.x; c1 = a0_.y; c2 = a0_.z; c3 = a0_.w;                                                 \
-        n0 = a1_.x; n1 = a1_.y; n2 = a1_.z; n3 = a1_.w;                                                 \
-    }                                                                                                   \
-    u32x4 fut = *(gp_u32x4)(pp + 2u * pstr < last ? pp + 2u * pstr : last);                             \
-    int pos = 0
+// The pipeline: nothing that was just read is used in the round that reads it (a select or a
+// sign flip on a fresh value would make the wavefront wait for it on the spot): a round's two
+// reads are issued first, unconditional, from addresses chosen so that a lane that sat out
+// reads again what it already holds, and are used a round later; the entry of ci + 1 is kept
+// as read, next to the sign flips of its code's two low bits.
+template <int ASYM, class AfterWait>
+__device__ __forceinline__ void ring_decode_step(RingDecoder &d, lp_u32 table, uint32_t n_groups, uint32_t n_order, int kc,
+                                                 AfterWait &&after_wait)
+{
+    const uint32_t lim8 = 8u * (uint32_t)(kc + kMmAhead), end8 = 8u * (uint32_t)(kc + kMmKc);
+    bool first = true;
+    do {
+        // Slide the window by one piece where its first piece is used up (once per step as a
+        // rule).  The other lanes fetch the piece they already wait for again, so that the
+        // load is unconditional and stays in flight until the next slide.
+        {
+            const bool s8 = d.ci - d.wbase >= 8u;
+            if (s8) ring_store_piece(d, 2u * (d.wbase & 8u), d.fut);
+            d.wbase += s8 ? 8u : 0u;
+            d.pp += s8 ? d.pstr : (uintptr_t)0;
+            d.fut = ring_piece_at(d, d.pp + 2u * d.pstr);
+        }
+        if (first) {
+            first = false;
+            after_wait();
+        }
+        // (a loop with its test at the end: with the test in front the compiler keeps two copies of the
+        // decoder's state and moves all of it from one to the other every round)
+        if (__any(d.left != 0u && d.pos8 < end8 && d.ci - d.wbase <= 12u)) do {
+            const bool go = d.left != 0u && d.pos8 <= lim8 && d.ci - d.wbase <= 12u;
+            // The entry this round applies; a lane that sits out applies an empty one, which stores
+            // three zeros at the column where its next run starts: nothing was written there yet, and
+            // it is never a column of the step being completed (kMmAhead keeps a lane's position below
+            // kc + 128), so the loop body has no branch and the stores need not be waited for.
+            const uint32_t e0 = go ? d.ent : 0u;
+            // move on to codeword ci + go: its entry is the one read a round ago (go) or still e0,
+            // the code after it c2 (go) or still c1; this round's reads go out before anything else
+            const uint32_t csel = go ? d.c2 : d.c1;
+            d.ent = go ? (d.ent_n ^ d.flips_n) : d.ent;
+            d.ci += go ? 1u : 0u;
+            d.ent_n = table[ring_entry_index(csel, n_groups, n_order)];
+            d.flips_n = order_flips(csel);
+            d.c1 = csel;
+            d.c2 = ring_code_at(d, d.ci + 2u);
+            __builtin_amdgcn_sched_barrier(0);  // the round's two reads go out before the rest of its work
+#pragma unroll
+            for (int z = 0; z < kRunMaxNonzeros; z++) {
+                const uint32_t t = d.pos8 + ((e0 >> (8 + 8 * z)) & 0xFFu);  // 8 * column + the field's low three bits
+                const uint32_t col = (t >> 3) & (uint32_t)(kMmRing - 1);
+                // value bits of the field (2: +1, 6: -1): as they are (asymmetric grid: byte selectors), or
+                // at the top of the byte (0x40 / 0xC0; the store keeps the low eight bits)
+                *(lw_u8)(uintptr_t)(d.wrow + col) = (unsigned char)(ASYM ? (t & 6u) : (t << 5));
+            }
+            d.pos8 += e0 & 0xFFu;
+            d.left -= go ? 1u : 0u;
+        } while (__any(d.left != 0u && d.pos8 < end8 && d.ci - d.wbase <= 12u));
+    } while (__any(d.left != 0u && d.pos8 < end8));
+}
 
-// Table entry of the codeword at index `at` (0..15) of the window (anything when at > 15:
-// not used then).
-#define QMOE_MM_ENTRY_AT(dst, at)                                                                       \
-    do {                                                                                                \
-        const bool hi8_ = ((at) & 8u) != 0u, hi4_ = ((at) & 4u) != 0u;                                  \
-        const uint32_t lo_ = hi8_ ? (hi4_ ? n2 : n0) : (hi4_ ? c2 : c0);                                \
-        const uint32_t hi_ = hi8_ ? (hi4_ ? n3 : n1) : (hi4_ ? c3 : c1);                                \
-        /* bytes 2s, 2s+1 of {hi, lo}: selector 0x0c0c0100 + 0x0202 * s */                              \
-        const uint32_t code_ = __builtin_amdgcn_perm(hi_, lo_, 0x0c0c0100u + 0x0202u * ((at) & 3u));    \
-        (dst) = order_entry(table, code_, (uint32_t)a.n_groups, (uint32_t)a.n_order);                   \
-    } while (0)
-
-// Decode step c of the ring at LDS byte address `wrow` (128 one-byte columns + 8 spare
-// bytes): clear the half that becomes columns kend .. kend+63, then decode until every lane
-// has passed column kend = 64 (c + 1); lanes that are there already keep going while their
-// next codeword fits into the ring.  AFTER_WAIT runs right after the step's one wait for
-// global memory (a good place to issue loads that should stay in flight for a whole step).
-// A weight's ring byte is its two-bit field (2: +1, 6: -1) shifted left by BYTE_SHIFT.
-#define QMOE_RING_DECODE_STEP(c, AFTER_WAIT, BYTE_SHIFT)                                                          \
-    const int kc = (c) * kMmKc, kend = kc + kMmKc;                                                      \
-    _Pragma("unroll") for (int i_ = 0; i_ < kMmKc / 8; i_++)                                            \
-        ((lw_u64)(uintptr_t)(wrow + (uint32_t)((((c) + 1) & 1) * kMmKc)))[i_] = 0ull;                   \
-    do {                                                                                                \
-        /* Slide the window by one piece where its first half is used up (once per step as a */        \
-        /* rule; the loop comes back only for lanes that use up a whole window in one step). */        \
-        /* The other lanes fetch the piece they already wait for again, so that the load is */         \
-        /* unconditional and stays in flight until the next slide. */                                   \
-        {                                                                                               \
-            const bool s8_ = sub >= 8u;                                                                 \
-            sub -= s8_ ? 8u : 0u;                                                                       \
-            pp += s8_ ? pstr : (uintptr_t)0;                                                            \
-            const uint32_t f0_ = fut.x, f1_ = fut.y, f2_ = fut.z, f3_ = fut.w;                          \
-            c0 = s8_ ? n0 : c0; c1 = s8_ ? n1 : c1; c2 = s8_ ? n2 : c2; c3 = s8_ ? n3 : c3;             \
-            n0 = s8_ ? f0_ : n0; n1 = s8_ ? f1_ : n1; n2 = s8_ ? f2_ : n2; n3 = s8_ ? f3_ : n3;         \
-            fut = *(gp_u32x4)(pp + 2u * pstr < last ? pp + 2u * pstr : last);                           \
-        }                                                                                               \
-        AFTER_WAIT                                                                                      \
-        /* No branches inside the inner loop: a lane that sits out decodes an empty entry into */      \
-        /* the spare bytes after its ring.  The look-up of the next codeword is issued before */       \
-        /* the current one is applied. */                                                               \
-        uint32_t ent_next_;                                                                             \
-        QMOE_MM_ENTRY_AT(ent_next_, sub);                                                               \
-        while (__any(left != 0u && pos < kend && sub < 16u)) {                                          \
-            const bool go_ = left != 0u && pos <= kc + kMmAhead && sub < 16u;                           \
-            const uint32_t ent_ = go_ ? ent_next_ : 0u;                                                 \
-            left -= go_ ? 1u : 0u;                                                                      \
-            sub += go_ ? 1u : 0u;                                                                       \
-            QMOE_MM_ENTRY_AT(ent_next_, sub);                                                           \
-            const uint32_t base_ = go_ ? (uint32_t)pos : (uint32_t)kMmRing;                             \
-            const uint32_t mask_ = go_ ? (uint32_t)(kMmRing - 1) : 0xFFu;                               \
-            /* fields are right-aligned in device-order entries: an unused one (0) comes first */      \
-            /* and writes a zero at the run's first column, before any real weight */                   \
-            _Pragma("unroll") for (int z_ = 0; z_ < kRunMaxNonzeros; z_++) {                            \
-                const uint32_t f_ = (ent_ >> (8 + 8 * z_)) & 0xFFu;                                     \
-                const uint32_t col_ = (base_ + (f_ >> 3)) & mask_;                                      \
-                /* shift 5: 0, 0x40 (+2.0), 0xC0 (-2.0) */                                              \
-                *(lw_u8)(uintptr_t)(wrow + col_) = (unsigned char)((f_ & 6u) << (BYTE_SHIFT));          \
-            }                                                                                           \
-            pos += (int)((ent_ & 0xFFu) >> 3);                                                          \
-        }                                                                                               \
-    } while (__any(left != 0u && pos < kend))
+// The half of the ring that held step c becomes columns kc + 128 .. kc + 191: cleared after
+// the step's reads.
+__device__ __forceinline__ void ring_clear_half(const RingDecoder &d, int c)
+{
+#pragma unroll
+    for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(d.wrow + (uint32_t)((c & 1) * kMmKc)))[i] = 0ull;
+}
 
 // ---- the matrix-core product ----
 //
@@ -173,22 +242,9 @@ __device__ __forceinline__ void lds_barrier()
 // the eight wavefronts of a workgroup read the same lines, which the caches serve).  No
 // workgroup barrier inside an item.
 //
-// The decoder: a lane's codewords pass through a window of two 16-byte pieces in LDS (the
-// next piece is in flight in a register); the codeword three places ahead is read from the
-// window, the table entry two places ahead is looked up, while the current entry is applied.
-// All of it sits under the lane's own "go" predicate -- a lane goes when it has codewords left,
-// its next run fits the ring (it starts at most kMmAhead columns past the step's first column)
-// and the window holds the codeword three places ahead -- so lanes that sit out issue nothing.
-// Applying an entry is three one-byte stores: field z goes to ring column (column + position)
-// mod 128 with the value bits of the field shifted to the top of the byte (0x40: +2.0, 0xC0:
-// -2.0 as the high byte of bf16, 0 for an unused field, which comes first and so writes its
-// zero at the run's first column before any real weight of the same run).
-//
 // MB: blocks of 16 tokens in the tile (1, 2 or 4).  D[token][row] += X[token][k] * W^T[k][row]
 // with v_mfma_f32_16x16x32_bf16: operand lane l holds 8 consecutive k (group l / 16) of token
 // or row l % 16; accumulator v of lane l is token 4 * (l / 16) + v, row l % 16 of the block.
-constexpr int kMmWinBytes = 40;   // a lane's window: two 16-byte pieces, padded so that the 64 slots spread over the banks
-
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int MB, int EPI, int ASYM>
@@ -202,29 +258,8 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     const int r0 = blk * a.mm_rows_per_block;
     const int row = r0 + tid;
     const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
-    const RowStream rst = row_stream(M, row, row_live);
-    uint32_t left = rst.left;                  // codewords to go
-    uintptr_t pp = rst.pp;                     // first piece of the window
-    const uintptr_t last = rst.last, pstr = rst.pstride;
-    uint32_t ci = rst.sub;                     // index of the next codeword, counted from piece 0
-    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
-    const uint32_t slot = win + (uint32_t)(tid * kMmWinBytes);
-    auto piece_at = [&](uintptr_t at) -> u32x4 { return *(gp_u32x4)(at < last ? at : last); };
-    auto store_piece = [&](uint32_t half_bytes, const u32x4 &v) {
-        lw_u64 d = (lw_u64)(uintptr_t)(slot + half_bytes);
-        d[0] = (unsigned long long)v.x | ((unsigned long long)v.y << 32);
-        d[1] = (unsigned long long)v.z | ((unsigned long long)v.w << 32);
-    };
-    auto code_at = [&](uint32_t i) -> uint32_t { return (uint32_t)(*(lp_u16)(uintptr_t)(slot + 2u * (i & 15u))); };
-    {
-        const u32x4 p0 = piece_at(pp), p1 = piece_at(pp + pstr);
-        store_piece(0u, p0);
-        store_piece(16u, p1);
-    }
-    u32x4 fut = piece_at(pp + 2u * pstr);
-    uint32_t wbase = 0;   // index of the first codeword of the window's first piece (a multiple of 8)
-#pragma unroll
-    for (int i = 0; i < kMmRing / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+    RingDecoder dec;
+    ring_setup(dec, M, row, row_live, wt + (uint32_t)(tid * kMmWRowBytes), win + (uint32_t)(tid * kMmWinBytes));
 
     // ---- this lane's part of the activations: token 16 * mb + l16, columns 8 * lg .. 8 * lg + 7 of every 32
     uintptr_t xsrc[MB];
@@ -290,23 +325,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 
     __syncthreads();  // token ids and gates are in place (the epilogue reads them)
 
-    // The decoder's pipeline: entries of codewords ci and ci + 1, codes of ci + 1 and ci + 2.
-    // Nothing that was just read is used in the round that reads it (a select or a sign flip on
-    // a fresh value would make the wavefront wait for it on the spot): a round's two reads are
-    // issued first, unconditional, from addresses chosen so that a lane that sat out reads again
-    // what it already holds, and are used a round later; the entry of ci + 1 is kept as read,
-    // next to the sign flips of its code's two low bits.
-    auto entry_index = [&](uint32_t code) -> uint32_t {
-        return min(max(code >> 2, __builtin_elementwise_sub_sat(code, 3u * n_groups)), n_order - 1u);
-    };
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    uint32_t c1 = code_at(ci + 1u), c2 = code_at(ci + 2u);
-    uint32_t ent = order_entry(table, code_at(ci), n_groups, n_order);
-    uint32_t ent_n = table[entry_index(c1)], flips_n = order_flips(c1);
-    uint32_t pos8 = 0;  // 8 * (column where the next run starts)
-    // Nothing is in flight when the loop starts, so that the wait at the top of a round is for the two
-    // reads of the round before and not for the three stores issued after them.
-    asm volatile("" : "+v"(ent_n), "+v"(c1), "+v"(c2), "+v"(ent));
+    ring_prime(dec, table, n_groups, n_order);
 
     u32x4 xa[MB][2];
 #pragma unroll
@@ -316,62 +335,17 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
 
     for (int c = 0; c < nsteps; c++) {
         const int kc = c * kMmKc;
-        const uint32_t lim8 = 8u * (uint32_t)(kc + kMmAhead), end8 = 8u * (uint32_t)(kc + kMmKc);
-        // ---- decode until every lane has passed column kc + 64
+        // ---- decode until every lane has passed column kc + 64; the next step's activations are
+        // fetched right after the window's wait, a whole step ahead
         u32x4 xn[MB][2];
-        bool first = true;
-        do {
-            // Slide the window by one piece where its first piece is used up (once per step as a
-            // rule).  The other lanes fetch the piece they already wait for again, so that the
-            // load is unconditional and stays in flight until the next slide.
-            {
-                const bool s8 = ci - wbase >= 8u;
-                if (s8) store_piece(2u * (wbase & 8u), fut);
-                wbase += s8 ? 8u : 0u;
-                pp += s8 ? pstr : (uintptr_t)0;
-                fut = piece_at(pp + 2u * pstr);
-            }
-            if (first) {
-                // the next step's activations: fetched right after the window's wait, a whole step ahead
-                first = false;
-                int k_next = kc + kMmKc;
-                asm volatile("" : "+s"(k_next));
+        ring_decode_step<ASYM>(dec, table, n_groups, n_order, kc, [&]() {
+            int k_next = kc + kMmKc;
+            asm volatile("" : "+s"(k_next));
 #pragma unroll
-                for (int mb = 0; mb < MB; mb++)
+            for (int mb = 0; mb < MB; mb++)
 #pragma unroll
-                    for (int ks = 0; ks < 2; ks++) xn[mb][ks] = load_x(mb, k_next + 32 * ks);
-            }
-            // (a loop with its test at the end: with the test in front the compiler keeps two copies of the
-            // decoder's state and moves all of it from one to the other every round)
-            if (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u)) do {
-                const bool go = left != 0u && pos8 <= lim8 && ci - wbase <= 12u;
-                // The entry this round applies; a lane that sits out applies an empty one, which stores
-                // three zeros at the column where its next run starts: nothing was written there yet, and
-                // it is never a column of the step being completed (kMmAhead keeps a lane's position below
-                // kc + 128), so the loop body has no branch and the stores need not be waited for.
-                const uint32_t e0 = go ? ent : 0u;
-                // move on to codeword ci + go: its entry is the one read a round ago (go) or still e0,
-                // the code after it c2 (go) or still c1; this round's reads go out before anything else
-                const uint32_t csel = go ? c2 : c1;
-                ent = go ? (ent_n ^ flips_n) : ent;
-                ci += go ? 1u : 0u;
-                ent_n = table[entry_index(csel)];
-                flips_n = order_flips(csel);
-                c1 = csel;
-                c2 = code_at(ci + 2u);
-                __builtin_amdgcn_sched_barrier(0);  // the round's two reads go out before the rest of its work
-#pragma unroll
-                for (int z = 0; z < kRunMaxNonzeros; z++) {
-                    const uint32_t t = pos8 + ((e0 >> (8 + 8 * z)) & 0xFFu);  // 8 * column + the field's low three bits
-                    const uint32_t col = (t >> 3) & (uint32_t)(kMmRing - 1);
-                    // value bits of the field (2: +1, 6: -1): as they are (asymmetric grid: byte selectors), or
-                    // at the top of the byte (0x40 / 0xC0; the store keeps the low eight bits)
-                    *(lw_u8)(uintptr_t)(wrow + col) = (unsigned char)(ASYM ? (t & 6u) : (t << 5));
-                }
-                pos8 += e0 & 0xFFu;
-                left -= go ? 1u : 0u;
-            } while (__any(left != 0u && pos8 < end8 && ci - wbase <= 12u));
-        } while (__any(left != 0u && pos8 < end8));
+                for (int ks = 0; ks < 2; ks++) xn[mb][ks] = load_x(mb, k_next + 32 * ks);
+        });
         // the rows this wavefront multiplies are the ones its own lanes wrote
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -399,9 +373,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // this half of the ring becomes columns kc + 128 .. kc + 191: cleared after the reads above
-#pragma unroll
-        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)(wrow + (uint32_t)((c & 1) * kMmKc)))[i] = 0ull;
+        ring_clear_half(dec, c);
 #pragma unroll
         for (int mb = 0; mb < MB; mb++)
 #pragma unroll
@@ -509,12 +481,11 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
 // ---------------------------------------------------------------- decompression of whole matrices
 //
 // The codec without the product: dense ternary (int8) or scaled bf16 copies of compressed
-// matrices, for consumers that want a plain matrix (a library GEMM, a check).  Same ring
-// decoder as the matrix-core product: a workgroup of 512 lanes owns up to 512 rows, one lane
+// matrices, for consumers that want a plain matrix (a library GEMM, a check).  The ring
+// decoder of the matrix-core product: a workgroup of 512 lanes owns up to 512 rows, one lane
 // per row; after each 64-column step a wavefront writes out the 64 x 64 tile its own lanes
 // decoded, 8 rows per store instruction with 8 lanes covering a row's 64 columns, so that
 // the stores are whole 64- or 128-byte runs.  Wavefronts never wait for each other.
-
 
 // OUT 0: int8 in {-1, 0, +1}; 1: bf16(scale of the row) with the weight's sign, or 0;
 // 2: the row's bf16 grid point w_max or w_min, or 0 (asymmetric grid)
@@ -527,72 +498,104 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
     stage_words(table_w, a.order_table, a.n_order);
     __syncthreads();
     lp_u32 table = (lp_u32)table_w;
-    const uint32_t wt = (uint32_t)(uintptr_t)(lw_u8)(smem + table_bytes);
+    const uint32_t wt = (uint32_t)(uintptr_t)(lw_u8)(smem + table_bytes);               // [512][kMmWRowBytes] rings
+    const uint32_t win = wt + (uint32_t)(kMmThreads * kMmWRowBytes);                     // [512][kMmWinBytes] codeword windows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t wrow = wt + (uint32_t)(tid * kMmWRowBytes);
     const int seg = lane & 7, sub_row = lane >> 3;  // write-out role: columns 8*seg.., rows sub_row + 8*i
     const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
-    const long long total = (long long)a.n_mats * a.row_blocks;
+    const uint32_t n_groups = (uint32_t)a.n_groups, n_order = (uint32_t)a.n_order;
+
+    // Which matrices have a destination: one bit each, so that the workgroups share the matrices that
+    // are asked for evenly (dealt out over all matrices, a workgroup's share of those would be a matter of luck).
+    using lw_mask = __attribute__((address_space(3))) unsigned long long *;
+    lw_mask mask = (lw_mask)(uintptr_t)(win + (uint32_t)(kMmThreads * kMmWinBytes));  // [(n_mats + 63) / 64]
+    const int mask_words = (a.n_mats + 63) / 64;
+    for (int w = wave; w < mask_words; w += kMmThreads / 64) {
+        const int m = 64 * w + lane;
+        const unsigned long long bits = __ballot(m < a.n_mats && a.out[m] != nullptr);
+        if (lane == 0) mask[w] = bits;
+    }
+    __syncthreads();
+    long long n_wanted = 0;
+    for (int w = 0; w < mask_words; w++) n_wanted += __popcll(mask[w]);
+    const long long total = n_wanted * a.row_blocks;
 
     for (long long g = blockIdx.x; g < total; g += gridDim.x) {
-        const int m = (int)(g / a.row_blocks);
-        const int blk = (int)(g - (long long)m * a.row_blocks);
-        unsigned char *out = static_cast<unsigned char *>(a.out[m]);
-        if (!out) continue;
+        const int nth = (int)(g / a.row_blocks);  // which of the wanted matrices
+        const int blk = (int)(g - (long long)nth * a.row_blocks);
+        int m;
+        {
+            int w = 0, rem = nth;
+            for (;; w++) {
+                const int n = __popcll(mask[w]);
+                if (rem < n) break;
+                rem -= n;
+            }
+            unsigned long long bits = mask[w];
+            for (int i = 0; i < rem; i++) bits &= bits - 1ull;
+            // (the same in every lane; said so, the matrix descriptor is read into scalar registers)
+            m = __builtin_amdgcn_readfirstlane(64 * w + (int)__ffsll((long long)bits) - 1);
+        }
+        // (a pointer read from memory is a generic one to the compiler; stores through it would go out as
+        // generic-address stores, which count as LDS traffic too and make every wait of the decoder a full one)
+        const uintptr_t out = reinterpret_cast<uintptr_t>(a.out[m]);
         const qmoe_matrix M = a.mats[m];
         const int r0 = blk * a.rows_per_block;
         const int row = r0 + tid;
         const bool row_live = tid < a.rows_per_block && row < a.rows;
-        QMOE_RING_ROW_SETUP(M, row, row_live);
-#pragma unroll
-        for (int i = 0; i < kMmKc / 8; i++) ((lw_u64)(uintptr_t)wrow)[i] = 0ull;
+        RingDecoder dec;
+        ring_setup(dec, M, row, row_live, wt + (uint32_t)(tid * kMmWRowBytes), win + (uint32_t)(tid * kMmWinBytes));
 
-        // bf16 scale of the eight rows this lane writes out, in both halves of a register
+        // the eight rows this lane writes out: which of them exist, and their bf16 scale in both
+        // halves of a register (OUT 2: the (w_min, w_max) pair as stored, w_min in the low half)
+        bool r_ok[8];
         uint32_t s2[8];
-        if constexpr (OUT == 2) {
-            // the (w_min, w_max) pair as stored: w_min in the low half
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int rl = 64 * wave + sub_row + 8 * i;
-                s2[i] = 0u;
-                if (rl < a.rows_per_block && r0 + rl < a.rows && M.minmax_bf16) s2[i] = ((gp_u32)M.minmax_bf16)[r0 + rl];
+        for (int i = 0; i < 8; i++) {
+            const int rl = 64 * wave + sub_row + 8 * i;
+            r_ok[i] = rl < a.rows_per_block && r0 + rl < a.rows;
+            s2[i] = 0u;
+            if constexpr (OUT == 2) {
+                if (r_ok[i] && M.minmax_bf16) s2[i] = ((gp_u32)M.minmax_bf16)[r0 + rl];
             }
-        }
-        if constexpr (OUT == 1) {
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int rl = 64 * wave + sub_row + 8 * i;
+            if constexpr (OUT == 1) {
                 uint32_t b = 0;
-                if (rl < a.rows_per_block && r0 + rl < a.rows)
-                    b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[r0 + rl]));
+                if (r_ok[i]) b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[r0 + rl]));
                 s2[i] = b | (b << 16);
             }
         }
+        ring_prime(dec, table, n_groups, n_order);
 
         for (int c = 0; c < nsteps; c++) {
-            QMOE_RING_DECODE_STEP(c, {}, OUT == 2 ? 0 : 5);
+            const int kc = c * kMmKc;
+            ring_decode_step<OUT == 2>(dec, table, n_groups, n_order, kc, []() {});
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int k = kc + 8 * seg;
+            const bool k_ok = k + 8 <= a.cols;
+            // the eight reads first (every lane reads, from inside the workgroup's rings), then the stores
+            unsigned long long d[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 const int rl = 64 * wave + sub_row + 8 * i;
-                const int r = r0 + rl;
-                if (rl < a.rows_per_block && r < a.rows && k + 8 <= a.cols) {
-                    const unsigned long long d =
-                        *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes + (c & 1) * kMmKc + 8 * seg));
-                    const uint32_t w0 = (uint32_t)d, w1 = (uint32_t)(d >> 32);
+                d[i] = *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes + (c & 1) * kMmKc + 8 * seg));
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int r = r0 + 64 * wave + sub_row + 8 * i;
+                if (r_ok[i] && k_ok) {
+                    const uint32_t w0 = (uint32_t)d[i], w1 = (uint32_t)(d[i] >> 32);
                     const size_t at = (size_t)r * a.cols + k;
                     if constexpr (OUT == 0) {
                         // ring byte 0x40 -> 0x01, 0xC0 -> 0xFF, 0 -> 0
                         const uint32_t o0 = ((w0 >> 6) & 0x01010101u) | (((w0 >> 7) & 0x01010101u) * 0xFEu);
                         const uint32_t o1 = ((w1 >> 6) & 0x01010101u) | (((w1 >> 7) & 0x01010101u) * 0xFEu);
-                        *reinterpret_cast<unsigned long long *>(out + at) = (unsigned long long)o0 | ((unsigned long long)o1 << 32);
+                        *(gw_u64)(out + at) = (unsigned long long)o0 | ((unsigned long long)o1 << 32);
                     } else if constexpr (OUT == 2) {
                         const bf16x8 v = mm_expand_minmax(w0, w1, s2[i] << 16, s2[i] & 0xFFFF0000u);
                         u32x4 o;
                         __builtin_memcpy(&o, &v, 16);
-                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
+                        *(gw_u32x4)(out + 2 * at) = o;
                     } else {
                         u32x4 o;
 #pragma unroll
@@ -602,13 +605,14 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
                             const uint32_t present = ((e >> 14) & 0x00010001u) * 0xFFFFu;
                             o[h] = ((e & 0x80008000u) | s2[i]) & present;
                         }
-                        *reinterpret_cast<u32x4 *>(out + 2 * at) = o;
+                        *(gw_u32x4)(out + 2 * at) = o;
                     }
                 }
             }
-            // the next step clears this half of the ring: after these reads
+            // this half of the ring is cleared for the step after next: after the reads above
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            ring_clear_half(dec, c);
         }
     }
 }
@@ -621,9 +625,10 @@ size_t mm_lds_bytes(int n_order)
            (size_t)kMmThreads * kMmWinBytes + 2 * sizeof(int) * kMmTokens + 16;
 }
 
-size_t decompress_lds_bytes(int n_order)
+size_t decompress_lds_bytes(int n_order, int n_mats)
 {
-    return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes;
+    return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes +
+           (size_t)kMmThreads * kMmWinBytes + 8 * (((size_t)n_mats + 63) / 64);
 }
 
 void mm_rows(int rows, int *row_blocks, int *rows_per_block)

@@ -344,6 +344,30 @@ def test_decompress_whole_matrices_bit_exact(gpu, ddict, oracle_dict, d_model, d
                     assert np.array_equal(got.view(np.uint16), want.astype(np.uint16)), f"{which} expert {e}"
 
 
+def test_decompress_destinations_anywhere_in_the_address_space(gpu, ddict, oracle_dict):
+    """Destinations whose addresses have bit 31 set and clear (address arithmetic in 32-bit halves
+    must not sign-extend the low half): carved out of one 5 GiB allocation."""
+    w = synth.WORKLOADS["c2048_ragged256"].scaled(n_experts=4, d_model=72, d_ff=200, n_tokens=4)
+    layer = _build_layer(w, oracle_dict, gpu, order_of=ddict)
+    rows, cols = w.d_ff, w.d_model
+    pool = torch.empty(5 << 30, dtype=torch.int8, device=gpu)
+    base = pool.data_ptr()
+    offs = []
+    for want_high in (True, False, True, False):
+        off = 256 * len(offs) * 1024
+        while (((base + off) >> 31) & 1) != int(want_high):
+            off += 1 << 30
+        assert off + rows * cols <= pool.numel()
+        offs.append(off)
+    pool[: 1 << 20].fill_(77)
+    ptrs = torch.tensor([base + o for o in offs], dtype=torch.int64, device=gpu)
+    q.qmoe_decompress(ddict.handle, layer.desc_dev["wi"], 1, w.n_experts, rows, cols, 0, ptrs)
+    torch.cuda.synchronize()
+    for e, o in enumerate(offs):
+        got = pool[o: o + rows * cols].cpu().numpy().reshape(rows, cols)
+        assert np.array_equal(got, w.wi_ternary(e)), f"expert {e} at offset {o:#x}"
+
+
 @pytest.mark.parametrize("rows,cols,p0,seed", [(1, 2, 0.5, 1), (7, 58, 0.9, 2), (300, 136, 0.885, 3), (2080, 6144, 0.9, 4),
                                                (513, 770, 0.3, 5)])
 def test_encode_device_equals_the_oracle_stream(gpu, ddict, oracle_dict, rows, cols, p0, seed):
