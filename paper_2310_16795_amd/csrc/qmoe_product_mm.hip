@@ -171,11 +171,15 @@ __device__ __forceinline__ void ring_prime(RingDecoder &d, lp_u32 table, uint32_
 // reads are issued first, unconditional, from addresses chosen so that a lane that sat out
 // reads again what it already holds, and are used a round later; the entry of ci + 1 is kept
 // as read, next to the sign flips of its code's two low bits.
+//
+// `shift8` = 8 * (columns by which this lane's steps begin early, 0..63): the lane's step covers
+// columns kc - shift .. kc - shift + 63 (the decompression kernel lets every row's steps end on
+// line boundaries of the row's destination; the product passes 0).
 template <int ASYM, class AfterWait>
 __device__ __forceinline__ void ring_decode_step(RingDecoder &d, lp_u32 table, uint32_t n_groups, uint32_t n_order, int kc,
-                                                 AfterWait &&after_wait)
+                                                 uint32_t shift8, AfterWait &&after_wait)
 {
-    const uint32_t lim8 = 8u * (uint32_t)(kc + kMmAhead), end8 = 8u * (uint32_t)(kc + kMmKc);
+    const uint32_t lim8 = 8u * (uint32_t)(kc + kMmAhead) - shift8, end8 = 8u * (uint32_t)(kc + kMmKc) - shift8;
     bool first = true;
     do {
         // Slide the window by one piece where its first piece is used up (once per step as a
@@ -338,7 +342,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
         // ---- decode until every lane has passed column kc + 64; the next step's activations are
         // fetched right after the window's wait, a whole step ahead
         u32x4 xn[MB][2];
-        ring_decode_step<ASYM>(dec, table, n_groups, n_order, kc, [&]() {
+        ring_decode_step<ASYM>(dec, table, n_groups, n_order, kc, 0u, [&]() {
             int k_next = kc + kMmKc;
             asm volatile("" : "+s"(k_next));
 #pragma unroll
@@ -502,8 +506,14 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
     const uint32_t win = wt + (uint32_t)(kMmThreads * kMmWRowBytes);                     // [512][kMmWinBytes] codeword windows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seg = lane & 7, sub_row = lane >> 3;  // write-out role: columns 8*seg.., rows sub_row + 8*i
-    const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
     const uint32_t n_groups = (uint32_t)a.n_groups, n_order = (uint32_t)a.n_order;
+    // A row's 64-column steps begin early by as many columns as it takes for their ends to fall on
+    // 128-byte (bf16) or 64-byte (int8) boundaries of the row's destination: a matrix whose rows are no
+    // multiple of that long would otherwise have every run of every other row straddle two lines.
+    // (Destinations are 16-byte aligned and cols is a multiple of 8, so a shift is a multiple of 8 columns.)
+    constexpr int kBpe = OUT == 0 ? 1 : 2, kRunBytes = kMmKc * kBpe;
+    const bool shifted = ((size_t)a.cols * kBpe) % kRunBytes != 0;
+    const int nsteps = (a.cols + kMmKc - 1) / kMmKc + (shifted ? 1 : 0);
 
     // Which matrices have a destination: one bit each, so that the workgroups share the matrices that
     // are asked for evenly (dealt out over all matrices, a workgroup's share of those would be a matter of luck).
@@ -539,6 +549,11 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
         // (a pointer read from memory is a generic one to the compiler; stores through it would go out as
         // generic-address stores, which count as LDS traffic too and make every wait of the decoder a full one)
         const uintptr_t out = reinterpret_cast<uintptr_t>(a.out[m]);
+        // columns by which row r's steps begin early
+        auto row_shift = [&](int r) -> int {
+            const int lead = (int)((out + (uintptr_t)kBpe * (uintptr_t)r * (uintptr_t)a.cols) % kRunBytes);  // bytes past a boundary
+            return lead / kBpe;  // = (64 - columns up to the row's first boundary) mod 64
+        };
         const qmoe_matrix M = a.mats[m];
         const int r0 = blk * a.rows_per_block;
         const int row = r0 + tid;
@@ -550,40 +565,47 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
         // halves of a register (OUT 2: the (w_min, w_max) pair as stored, w_min in the low half)
         bool r_ok[8];
         uint32_t s2[8];
+        int sh[8];  // the shifts of those rows
+        const uint32_t shift8 = shifted && row_live ? 8u * (uint32_t)row_shift(row) : 0u;  // this lane's own row
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const int rl = 64 * wave + sub_row + 8 * i;
             r_ok[i] = rl < a.rows_per_block && r0 + rl < a.rows;
+            sh[i] = shifted && r_ok[i] ? row_shift(r0 + rl) : 0;
+            // (loads without a branch, from row r0 where there is no row: the eight are in flight together)
+            const int rr = r_ok[i] ? r0 + rl : min(r0, a.rows - 1);
             s2[i] = 0u;
             if constexpr (OUT == 2) {
-                if (r_ok[i] && M.minmax_bf16) s2[i] = ((gp_u32)M.minmax_bf16)[r0 + rl];
+                if (M.minmax_bf16) {
+                    const uint32_t pair = ((gp_u32)M.minmax_bf16)[rr];
+                    s2[i] = r_ok[i] ? pair : 0u;
+                }
             }
             if constexpr (OUT == 1) {
-                uint32_t b = 0;
-                if (r_ok[i]) b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[r0 + rl]));
-                s2[i] = b | (b << 16);
+                const uint32_t b = float_to_bf16_bits(half_bits_to_float(((gp_u16)M.scale_f16)[rr]));
+                s2[i] = r_ok[i] ? (b | (b << 16)) : 0u;
             }
         }
         ring_prime(dec, table, n_groups, n_order);
 
         for (int c = 0; c < nsteps; c++) {
             const int kc = c * kMmKc;
-            ring_decode_step<OUT == 2>(dec, table, n_groups, n_order, kc, []() {});
+            ring_decode_step<OUT == 2>(dec, table, n_groups, n_order, kc, shift8, []() {});
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            const int k = kc + 8 * seg;
-            const bool k_ok = k + 8 <= a.cols;
             // the eight reads first (every lane reads, from inside the workgroup's rings), then the stores
             unsigned long long d[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 const int rl = 64 * wave + sub_row + 8 * i;
-                d[i] = *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes + (c & 1) * kMmKc + 8 * seg));
+                const uint32_t ring_col = (uint32_t)(kc - sh[i] + 8 * seg) & (uint32_t)(kMmRing - 1);  // 8-aligned: no wrap inside
+                d[i] = *(lp_u64)(uintptr_t)(wt + (uint32_t)(rl * kMmWRowBytes) + ring_col);
             }
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 const int r = r0 + 64 * wave + sub_row + 8 * i;
-                if (r_ok[i] && k_ok) {
+                const int k = kc - sh[i] + 8 * seg;
+                if (r_ok[i] && k >= 0 && k + 8 <= a.cols) {
                     const uint32_t w0 = (uint32_t)d[i], w1 = (uint32_t)(d[i] >> 32);
                     const size_t at = (size_t)r * a.cols + k;
                     if constexpr (OUT == 0) {
@@ -609,10 +631,15 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
                     }
                 }
             }
-            // this half of the ring is cleared for the step after next: after the reads above
+            // the 64 columns of this lane's ring that held its step are cleared for the step after next:
+            // after the reads above
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            ring_clear_half(dec, c);
+#pragma unroll
+            for (int j = 0; j < kMmKc / 8; j++) {
+                const uint32_t ring_col = ((uint32_t)(8 * kc + 64 * j) - shift8) >> 3 & (uint32_t)(kMmRing - 1);
+                *(lw_u64)(uintptr_t)(dec.wrow + ring_col) = 0ull;
+            }
         }
     }
 }
