@@ -292,7 +292,7 @@ qmoe_status plan_mm(const qmoe_dict *d, int code_order, int d_model, int d_ff, i
     if (code_order != 1 || n_order == 0 || d->max_nonzeros > kRunMaxNonzeros || !fits || (d_model % 8) ||
         (d_ff % 8) || !x_aligned || tu.mfma_min_tokens < 0)
         return QMOE_OK;
-    // A tile is walked column step by column step by one workgroup per 512 rows: a long chain
+    // A tile is walked column step by column step by one wavefront per 64 rows: a long chain
     // that pays only when the scalar kernel would need several rounds of items per compute
     // unit anyway.  With few tokens in the call (measured: 512 tokens on 128 experts) the
     // scalar kernel finishes every expert in one round and the chain would be the critical path.
@@ -480,26 +480,26 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
     a.tb_max = tb;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // Many tokens: the matrix-core kernel decodes the matrix once per 64 tokens instead of once
-    // per 8.  One matrix has few row blocks of 512, so the blocks are made as small as they can
-    // be with all of them resident at once (every block still decodes only its own rows; a
-    // block's time is set by the length of a row, not by how many rows it has).
+    // per 8.  Its unit of work is 64 rows of a token tile, taken by one wavefront (a unit's time is
+    // set by the length of a row, not by how many units there are).
     {
         const Tuning &tu = tuning();
         const int n_order = (int)d->order_table.size();
         if (code_order == 1 && run && n_order > 0 && tu.mfma_min_tokens >= 0 && W->cols % 8 == 0 &&
             reinterpret_cast<uintptr_t>(x_bf16) % 16 == 0 && mm_lds_bytes(n_order) <= (size_t)di.max_lds) {
             const int tiles = (batch + kMmTokens - 1) / kMmTokens;
-            int rpb = 64;
-            while (rpb < kMmThreads && (long long)tiles * ((W->rows + rpb - 1) / rpb) > di.cus) rpb += 64;
-            const long long blocks = (long long)tiles * ((W->rows + rpb - 1) / rpb);
-            // Measured on this GPU (microseconds): a round of the matrix-core kernel takes about
-            // 8 + 0.0225 per column; the other kernel works through tiles of eight tokens at 0.62
-            // million weights per microsecond with one workgroup resident per compute unit (long
-            // rows: the tile's activations fill the LDS), 1.6 with four, 2.5-3 with eight.
+            const int waves = kMmThreads / 64;
+            const long long units = (long long)tiles * ((W->rows + 63) / 64);
+            const long long blocks = (units + waves - 1) / waves;  // workgroups with every wavefront busy
+            // Measured on this GPU (microseconds): a round of the matrix-core kernel (every wavefront of
+            // every compute unit with one unit of 64 tokens) takes about 8 + 0.0148 per column; the other
+            // kernel works through tiles of eight tokens at 1.3 million weights per microsecond with one
+            // workgroup resident per compute unit (long rows: the tile's activations fill the LDS) and
+            // about three times that with three or more.
             const double rounds = std::ceil((double)blocks / di.cus);
-            const double t_mm = rounds * (8.0 + 0.0225 * W->cols);
-            const int resident = (int)std::max<size_t>(1, std::min<size_t>(8, (size_t)di.max_lds / xs_bytes(8)));
-            const double rate = 0.62e6 * (1.0 + 0.55 * (resident - 1));
+            const double t_mm = rounds * (8.0 + 0.0148 * W->cols);
+            const int resident = (int)std::max<size_t>(1, std::min<size_t>(3, (size_t)di.max_lds / xs_bytes(8)));
+            const double rate = 1.3e6 * resident;
             const double t_rows = std::max(8.5, 4.0 + std::ceil(batch / 8.0) * (double)W->rows * W->cols / rate);
             const bool take = tu.mfma_min_tokens > 0 ? batch >= tu.mfma_min_tokens : t_mm < t_rows;
             if (take) {
@@ -507,8 +507,8 @@ qmoe_status qmoe_decode_matvec(const qmoe_dict *d, const qmoe_matrix *W, const u
                 a.epilogue = 0;
                 MmPlan mp;
                 mp.smem = mm_lds_bytes(n_order);
-                mp.grid = (int)std::min<long long>(blocks, di.cus);
-                return launch_product_mm(a, mp, s, rpb);
+                mp.grid = (int)std::min<long long>(units, di.cus);  // a unit per compute unit before a second per compute unit
+                return launch_product_mm(a, mp, s);
             }
         }
     }
@@ -731,6 +731,7 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
         // the hidden vectors of the crowded experts are kept in blocks of 16 tokens (see ProductArgs); only the two
         // matrix-core kernels touch those slots (needs whole 8-column groups on the hidden side: d_ff % 8 == 0)
         am.out_tiled = 1;
+        am.mm_in_step = 1;  // its activations come by token rows: the wavefronts of a workgroup read the same lines together
         if (phases & 8)
             if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
         am = a2;

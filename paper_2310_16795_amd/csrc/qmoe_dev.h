@@ -76,7 +76,8 @@ struct ProductArgs {
     const uint32_t *order_table;  // device-order table (n_order entries, the first n_groups are groups)
     int n_groups, n_order;
     int code_order;           // numbering of the streams (decode_dense only; the product picks its kernel)
-    int mm_row_blocks, mm_rows_per_block;  // matrix-core kernel: workgroups per matrix, rows each takes (<= 512)
+    int mm_row_blocks;  // matrix-core kernel: blocks of 64 rows per matrix (a wavefront's unit of work)
+    int mm_in_step;     // matrix-core kernel: a workgroup's wavefronts may take eight consecutive units at a time, together
     int minmax;               // rows on the grid {w_min, 0, w_max} (host side: which kernel to launch)
     // matrix-core kernel, layer calls: the hidden vectors of a tile are kept in blocks of 16 tokens,
     // [8-column group][token of the block][8 columns] (a partial last block: its own token count),
@@ -172,7 +173,7 @@ qmoe_status launch_product(const ProductArgs &a, const ProductPlan &p, bool run,
 qmoe_status launch_product_sym(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s);
 qmoe_status launch_product_asym(const ProductArgs &a, const ProductPlan &p, bool run, hipStream_t s);
 size_t mm_lds_bytes(int n_order);                                                                   // qmoe_product_mm.hip
-qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s, int rows_per_block = 0);
+qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s);
 void mm_rows(int rows, int *row_blocks, int *rows_per_block);
 qmoe_status launch_decompress(const DecompressArgs &a, int out_kind, bool minmax, int grid, size_t smem, hipStream_t s);
 size_t decompress_lds_bytes(int n_order, int n_mats);  // table, rings, windows, one bit per matrix

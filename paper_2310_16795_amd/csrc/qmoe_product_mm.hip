@@ -252,18 +252,29 @@ __device__ __forceinline__ void ring_clear_half(const RingDecoder &d, int c)
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int MB, int EPI, int ASYM>
-__device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int blk, int slot0, int ntok,
-                                        lp_u32 table, uint32_t wt, uint32_t win, lp_i32 tok_ids, lp_f32 gate_s)
+__device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix &M, int rblk, int slot0, int ntok,
+                                        lp_u32 table, uint32_t wt, uint32_t win)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    // ---- this lane's row and its codewords
-    const int r0 = blk * a.mm_rows_per_block;
-    const int row = r0 + tid;
-    const bool row_live = tid < a.mm_rows_per_block && row < a.rows;
+    // The second product writes to the tokens' own rows of the output, scaled by their gates.  Lane t asks
+    // for token t's row and gate now, among the other trips to memory of the set-up (two registers for the
+    // length of the item); the lanes swap them when the results are written.
+    int tok_own = 0;
+    float gate_own = 1.0f;
+    if constexpr (EPI == 0) {
+        const int t = min(lane, ntok - 1);
+        tok_own = a.perm ? a.perm[slot0 + t] : slot0 + t;
+    }
+
+    // ---- this lane's row (the wavefront's 64 rows are block `rblk` of the matrix) and its codewords
+    const int r0 = rblk * 64;
+    const int row = r0 + lane;
+    const bool row_live = row < a.rows;
     RingDecoder dec;
     ring_setup(dec, M, row, row_live, wt + (uint32_t)(tid * kMmWRowBytes), win + (uint32_t)(tid * kMmWinBytes));
+    if constexpr (EPI == 0) gate_own = a.gate ? a.gate[tok_own] : 1.0f;
 
     // ---- this lane's part of the activations: token 16 * mb + l16, columns 8 * lg .. 8 * lg + 7 of every 32
     uintptr_t xsrc[MB];
@@ -316,9 +327,9 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     if constexpr (ASYM) {
 #pragma unroll
         for (int nb = 0; nb < 4; nb++) {
-            const int rl = 64 * wave + 16 * nb + l16;
+            const int rl = 16 * nb + l16;
             uint32_t pair = 0u;  // a row past the end, or a matrix without a pair array, multiplies as zeros
-            if (rl < a.mm_rows_per_block && r0 + rl < a.rows && M.minmax_bf16) pair = ((gp_u32)M.minmax_bf16)[r0 + rl];
+            if (r0 + rl < a.rows && M.minmax_bf16) pair = ((gp_u32)M.minmax_bf16)[r0 + rl];
             g_hi[nb] = pair << 16;
             g_lo[nb] = pair & 0xFFFF0000u;
         }
@@ -326,8 +337,6 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     const uint32_t wfrag = wt + (uint32_t)((64 * wave + l16) * kMmWRowBytes + 8 * lg);
     const int nsteps = (a.cols + kMmKc - 1) / kMmKc;
     const uint32_t n_groups = (uint32_t)a.n_groups, n_order = (uint32_t)a.n_order;
-
-    __syncthreads();  // token ids and gates are in place (the epilogue reads them)
 
     ring_prime(dec, table, n_groups, n_order);
 
@@ -385,11 +394,23 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
     }
 
     // accumulator v of lane l: token 16 * mb + 4 * (l / 16) + v, row 16 * nb + l % 16 of the wavefront's 64
+    // (second product: output row and gate of each of the lane's tokens, from the lane that holds them)
+    int tok_of[MB][4];
+    float gate_of[MB][4];
+    if constexpr (EPI == 0) {
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+                const int t = 16 * mb + 4 * lg + v;  // < 64
+                tok_of[mb][v] = __shfl(tok_own, t, 64);
+                gate_of[mb][v] = __shfl(gate_own, t, 64);
+            }
+    }
 #pragma unroll
     for (int nb = 0; nb < 4; nb++) {
-        const int rl = 64 * wave + 16 * nb + l16;
-        const int r = r0 + rl;
-        if (rl < a.mm_rows_per_block && r < a.rows) {
+        const int r = r0 + 16 * nb + l16;
+        if (r < a.rows) {
             // symmetric grid: the weights were +-2; asymmetric: they were the grid points themselves
             const float scale = ASYM ? 1.0f : 0.5f * half_bits_to_float(((gp_u16)M.scale_f16)[r]);
 #pragma unroll
@@ -400,7 +421,7 @@ __device__ __forceinline__ void mm_item(const ProductArgs &a, const qmoe_matrix 
                     if (t < ntok) {
                         const float val = acc[mb][nb][v] * scale;
                         if constexpr (EPI == 0) {
-                            reinterpret_cast<float *>(a.out)[(size_t)tok_ids[t] * a.ld_out + r] = gate_s[t] * val;
+                            reinterpret_cast<float *>(a.out)[(size_t)tok_of[mb][v] * a.ld_out + r] = gate_of[mb][v] * val;
                         } else {
                             const float h = val > 0.0f ? val : 0.0f;
                             size_t at = (size_t)(slot0 + t) * a.ld_out + r;
@@ -425,32 +446,72 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
     uint32_t *table_w = reinterpret_cast<uint32_t *>(smem);
     unsigned char *wt = smem + table_bytes;                           // [512][kMmWRowBytes] rings
     unsigned char *win = wt + (size_t)kMmThreads * kMmWRowBytes;      // [512][kMmWinBytes] codeword windows
-    int *tok_ids = reinterpret_cast<int *>(win + (size_t)kMmThreads * kMmWinBytes);  // [64]
-    float *gate_s = reinterpret_cast<float *>(tok_ids + kMmTokens);   // [64]
-    int *next_item = reinterpret_cast<int *>(gate_s + kMmTokens);     // [1]
 
-    // A layer call brings a list of (expert, token tile) items and a device counter that hands
-    // them out; the single-matrix call has neither: its items are the tiles of 64 consecutive
-    // tokens of `single`, dealt out round robin.
+    // A unit of work is 64 rows of one (expert, token tile) item, and a wavefront takes it alone: after
+    // the table is staged the wavefronts of a workgroup share nothing and meet at no barrier, so one
+    // wavefront's set-up (a chain of trips to memory) runs under the others' arithmetic, a matrix
+    // whose rows are no multiple of 512 leaves no wavefront idle, and the units are small enough to
+    // pack well.  A layer call brings a list of items and a device counter that hands the units out;
+    // the single-matrix call has neither: its items are the tiles of 64 consecutive tokens of
+    // `single`, its units dealt out round robin.
     const bool listed = a.items != nullptr;
     const int n_items = listed ? min(*a.n_items_dev, a.max_items) : (a.batch + kMmTokens - 1) / kMmTokens;
     const int total = (int)min((long long)n_items * a.mm_row_blocks, 0x7FFFFFFFLL);
-    if (total <= 0 || (!listed && (int)blockIdx.x >= total)) return;
+    const int wave = (int)threadIdx.x >> 6, lane = (int)threadIdx.x & 63, waves = kMmThreads / 64;
+    // No more workgroups than fill all their wavefronts stay (a workgroup holds its compute unit's LDS whole,
+    // so one that runs half empty keeps the other kernels of a layer call off that compute unit); the
+    // single-matrix call, which is after latency, spreads its units over as many compute units as it can.
+    if (total <= 0 || (int)blockIdx.x >= (listed ? (total + waves - 1) / waves : total)) return;
+    int *next_base = reinterpret_cast<int *>(win + (size_t)kMmThreads * kMmWinBytes);  // [1], in-step hand-out only
+    int *tok_sums = next_base + 1;                                                      // [2]
+    if (threadIdx.x < 2) tok_sums[threadIdx.x] = 0;
     stage_words(table_w, a.order_table, a.n_order);
-
-    int g_static = (int)blockIdx.x;
-    for (;;) {
-        __syncthreads();  // everyone is done with the previous item
-        if (threadIdx.x == 0) {
-            const int g = listed ? atomicAdd(a.work_counter, 1) : g_static;
-            *next_item = g < total ? g : -1;
+    __syncthreads();
+    // In step or each wavefront for itself (see the loop)?  In step when most of the tokens sit in tiles of
+    // more than 32: those read 4-8 KB of activations per wavefront and step.
+    bool in_step = false;
+    if (listed && a.mm_in_step) {
+        int big = 0, all = 0;
+        for (int i = threadIdx.x; i < n_items; i += kMmThreads) {
+            const int n = max(0, min(a.items[i].ntok, kMmTokens));
+            all += n;
+            big += n > 32 ? n : 0;
         }
-        g_static += (int)gridDim.x;
+        if (all) {
+            atomicAdd(&tok_sums[0], all);
+            atomicAdd(&tok_sums[1], big);
+        }
         __syncthreads();
-        const int g = *next_item;
-        if (g < 0) break;
+        in_step = 2 * tok_sums[1] > tok_sums[0];
+    }
+
+    const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, win_addr = (uint32_t)(uintptr_t)(lw_u8)win;
+    // (round robin over the workgroups first, then over their wavefronts: few units spread over many compute units)
+    int g_static = wave * (int)gridDim.x + (int)blockIdx.x;
+    for (;;) {
+        int g = g_static;
+        if (in_step) {
+            // The wavefronts of a workgroup take eight consecutive units together and start them together:
+            // where the activations are not stored by token blocks (the first product of a layer) their
+            // operand loads touch a line per token, and eight wavefronts that ask for the same lines at the
+            // same time are served by one fetch.  (Measured both ways: a layer with few, crowded experts is
+            // 3 % faster in step, one with many experts of 8-32 tokens 7 % faster without.)
+            __syncthreads();
+            if (threadIdx.x == 0) *next_base = atomicAdd(a.work_counter, waves);
+            __syncthreads();
+            const int base = *next_base;
+            if (base >= total) break;
+            g = base + wave;
+            if (g >= total) continue;
+        } else if (listed) {
+            int got = 0;
+            if (lane == 0) got = atomicAdd(a.work_counter, 1);
+            g = __builtin_amdgcn_readfirstlane(got);
+        }
+        g_static += (int)gridDim.x * waves;
+        if (g >= total) break;
         const int idx = g / a.mm_row_blocks;
-        const int blk = g - idx * a.mm_row_blocks;
+        const int rblk = g - idx * a.mm_row_blocks;
         Item it;
         if (listed) {
             it = a.items[idx];
@@ -462,23 +523,13 @@ __global__ __launch_bounds__(kMmThreads) void k_product_mm(const ProductArgs a)
         const int expert = it.expert, slot0 = it.slot0;
         const int ntok = min(it.ntok, kMmTokens);
         if (expert < 0 || expert >= a.n_experts || ntok < 1) continue;
-        if (threadIdx.x < kMmTokens) {
-            const int t = threadIdx.x;
-            const int tok = t < ntok ? (a.perm ? a.perm[slot0 + t] : slot0 + t) : 0;
-            tok_ids[t] = tok;
-            gate_s[t] = (a.gate && t < ntok) ? a.gate[tok] : 1.0f;
-        }
         const qmoe_matrix M = a.mats ? a.mats[expert] : a.single;
-        const uint32_t wt_addr = (uint32_t)(uintptr_t)(lw_u8)wt, win_addr = (uint32_t)(uintptr_t)(lw_u8)win;
         if (ntok <= 16)
-            mm_item<1, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
-                                  (lp_f32)gate_s);
+            mm_item<1, EPI, ASYM>(a, M, rblk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr);
         else if (ntok <= 32)
-            mm_item<2, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
-                                  (lp_f32)gate_s);
+            mm_item<2, EPI, ASYM>(a, M, rblk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr);
         else
-            mm_item<4, EPI, ASYM>(a, M, blk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr, (lp_i32)tok_ids,
-                                  (lp_f32)gate_s);
+            mm_item<4, EPI, ASYM>(a, M, rblk, slot0, ntok, (lp_u32)table_w, wt_addr, win_addr);
     }
 }
 
@@ -649,7 +700,7 @@ __global__ __launch_bounds__(kMmThreads) void k_decompress(const DecompressArgs 
 size_t mm_lds_bytes(int n_order)
 {
     return (((size_t)n_order * 4 + 15) & ~(size_t)15) + (size_t)kMmThreads * kMmWRowBytes +
-           (size_t)kMmThreads * kMmWinBytes + 2 * sizeof(int) * kMmTokens + 16;
+           (size_t)kMmThreads * kMmWinBytes + 16;
 }
 
 size_t decompress_lds_bytes(int n_order, int n_mats)
@@ -666,16 +717,9 @@ void mm_rows(int rows, int *row_blocks, int *rows_per_block)
     *rows_per_block = std::min(kMmThreads, (per + 63) / 64 * 64);
 }
 
-// rows_per_block: 0 = as few workgroups per matrix as possible (a layer call has many
-// matrices); otherwise a multiple of 64 up to 512.
-qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s, int rows_per_block)
+qmoe_status launch_product_mm(ProductArgs a, const MmPlan &mp, hipStream_t s)
 {
-    if (rows_per_block > 0) {
-        a.mm_rows_per_block = rows_per_block;
-        a.mm_row_blocks = (a.rows + rows_per_block - 1) / rows_per_block;
-    } else {
-        mm_rows(a.rows, &a.mm_row_blocks, &a.mm_rows_per_block);
-    }
+    a.mm_row_blocks = (a.rows + 63) / 64;  // units of 64 rows, one wavefront each
     auto launch = [&](auto kernel) -> qmoe_status {
         const qmoe_status st = allow_lds(kernel, mp.smem);
         if (st != QMOE_OK) return st;
