@@ -358,7 +358,7 @@ size_t qmoe_moe_layer_workspace(int n_experts, int d_model, int d_ff, int n_toke
  * tokens and (device-order streams, widths divisible by 8, x 16-byte aligned) the
  * matrix-core kernel for crowded ones: an expert's matrix is decoded once per tile of up
  * to 64 tokens there, instead of once per 4.  When both kinds of experts are present the
- * two scalar kernels run on a second stream that forks from `stream` after the dispatch and
+ * two kernels of one kind run on a second stream that forks from `stream` after the dispatch and
  * joins it again before the call's work ends (two library-owned events per device), so that
  * later work on `stream` sees y complete as usual.  side_stream: that second stream, owned
  * by the caller like `stream` (default priority; it must not be `stream` itself); NULL = a

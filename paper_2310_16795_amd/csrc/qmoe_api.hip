@@ -636,7 +636,7 @@ qmoe_status qmoe_moe_dispatch(const qmoe_dict *d, int code_order, const int32_t 
 
 namespace {
 
-// side: 0 = every kernel on `stream`; 1 = the scalar kernels on `side_stream`, or on the
+// side: 0 = every kernel on `stream`; 1 = one of the two chains of kernels on `side_stream`, or on the
 // library's own second stream when that is NULL
 qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_matrix *wo,
                           int code_order, int n_experts, int d_model, int d_ff, const uint16_t *x_bf16,
@@ -680,17 +680,28 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
 
     // The experts with few tokens and the crowded ones are two independent chains of two
     // kernels (each second product reads only the hidden rows its own first product wrote).
-    // With both kinds present the scalar chain goes to a side stream that forks from
-    // `stream` after the dispatch and joins it again at the end, so the kernels fill each
-    // other's idle compute units; the caller sees the usual stream order.
+    // With both kinds present one chain goes to a side stream that forks from `stream` after
+    // the dispatch and joins it again at the end, so the kernels fill each other's idle compute
+    // units; the caller sees the usual stream order.  The chain that stays on `stream` starts
+    // first (a kernel behind an event starts several microseconds late) and its persistent
+    // workgroups take every compute unit; measured, the step is shorter when that is the SHORTER
+    // chain: the longer one then moves in as compute units come free and keeps them to the end,
+    // instead of leaving the short chain to run as a thin tail (c2048, where the crowded experts
+    // are the short chain: 0.966 against 0.985 ms; 256 experts with 1-32 tokens each, where they
+    // are the long one: 1.28 against 1.48 ms).  Limiting each chain to a share of the compute
+    // units in proportion to its work was worse than either (measured for shares from 1/4 to 7/8).
+    // The host cannot see the routing, so it goes by the average: with four or more tokens per
+    // expert most tokens sit in crowded experts.
     const bool overlap = side && mm && tuning().overlap >= 0 && (phases & 6) && (phases & 24);
-    hipStream_t s_scalar = s;
+    const bool mm_first = (long long)n_tokens < 4LL * n_experts;
+    hipStream_t s_mm = s, s_sc = s;
     SideStream ss;
     if (overlap) {
         if ((st = side_stream(static_cast<hipStream_t>(side_stream_arg), &ss)) != QMOE_OK) return st;
-        s_scalar = ss.stream;
+        if (mm_first) s_sc = ss.stream;
+        else s_mm = ss.stream;
         QMOE_HIP_TRY(hipEventRecord(ss.fork, s));
-        QMOE_HIP_TRY(hipStreamWaitEvent(s_scalar, ss.fork, 0));
+        QMOE_HIP_TRY(hipStreamWaitEvent(ss.stream, ss.fork, 0));
     }
     ProductArgs a{};
     fill_tables(d, &a, code_order);
@@ -722,7 +733,7 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
     a2.epilogue = 0;
     a2.rows = d_model;
     a2.cols = d_ff;
-    // crowded experts (matrix cores) on `stream`: their tiles are the long items
+    // crowded experts (matrix cores): their tiles are the long items
     if (mm) {
         ProductArgs am = a1;
         am.items = lp.items_mm;
@@ -733,14 +744,14 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
         am.out_tiled = 1;
         am.mm_in_step = 1;  // its activations come by token rows: the wavefronts of a workgroup read the same lines together
         if (phases & 8)
-            if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+            if ((st = launch_product_mm(am, mp, s_mm)) != QMOE_OK) return st;
         am = a2;
         am.items = lp.items_mm;
         am.n_items_dev = lp.counters + 7;
         am.work_counter = lp.counters + 9;
         am.x_tiled = 1;
         if (phases & 16)
-            if ((st = launch_product_mm(am, mp, s)) != QMOE_OK) return st;
+            if ((st = launch_product_mm(am, mp, s_mm)) != QMOE_OK) return st;
     }
     // experts with few tokens (scalar kernels)
     a1.items = lp.items_wi;
@@ -752,7 +763,7 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
     a1.stage_out = pwi.stage_out;
     a1.work_counter = lp.counters + 5;
     if (phases & 2)
-        if ((st = launch_product(a1, pwi, run, s_scalar)) != QMOE_OK) return st;
+        if ((st = launch_product(a1, pwi, run, s_sc)) != QMOE_OK) return st;
     a2.items = lp.items_wo;
     a2.n_items_dev = lp.counters + 4;
     a2.rows_per_item = pwo.rows_per_item;
@@ -762,9 +773,9 @@ qmoe_status layer_forward(const qmoe_dict *d, const qmoe_matrix *wi, const qmoe_
     a2.stage_out = pwo.stage_out && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     a2.work_counter = lp.counters + 6;
     if (phases & 4)
-        if ((st = launch_product(a2, pwo, run, s_scalar)) != QMOE_OK) return st;
+        if ((st = launch_product(a2, pwo, run, s_sc)) != QMOE_OK) return st;
     if (overlap) {
-        QMOE_HIP_TRY(hipEventRecord(ss.join, s_scalar));
+        QMOE_HIP_TRY(hipEventRecord(ss.join, ss.stream));
         QMOE_HIP_TRY(hipStreamWaitEvent(s, ss.join, 0));
     }
     return QMOE_OK;
