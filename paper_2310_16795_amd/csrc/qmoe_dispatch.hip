@@ -8,8 +8,24 @@ namespace {
 // ---------------------------------------------------------------- dispatch
 
 
-// Exclusive prefix sums of N ints per thread over the workgroup, all at once (three barriers).
-// `tmp` holds >= 17 * N ints.
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive adds (no trip
+// through the LDS crossbar): the row scan, then lane 15 of a row added to the whole next row, then
+// lane 31 to the upper half.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_add(int x)
+{
+    return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false);  // lanes without a source add 0
+}
+__device__ __forceinline__ int wave_inclusive_scan(int x)
+{
+    x = row_scan16(x);
+    x = dpp_add<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
+    x = dpp_add<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// Exclusive prefix sums of N ints per thread over the workgroup (up to 16 wavefronts), all at
+// once (three barriers).  `tmp` holds >= 17 * N ints: [value][wavefront], then the N totals.
 template <int N>
 __device__ __forceinline__ void block_exclusive_scan_n(const int (&v)[N], int *tmp, int (&excl)[N], int (&total)[N])
 {
@@ -17,40 +33,25 @@ __device__ __forceinline__ void block_exclusive_scan_n(const int (&v)[N], int *t
     int incl[N];
 #pragma unroll
     for (int k = 0; k < N; k++) {
-        incl[k] = v[k];
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl[k], d, 64);
-            if (lane >= d) incl[k] += up;
-        }
-        if (lane == 63) tmp[wave * N + k] = incl[k];
+        incl[k] = wave_inclusive_scan(v[k]);
+        if (lane == 63) tmp[k * 16 + wave] = incl[k];
     }
     __syncthreads();
     if (wave == 0) {
-        // lane l: value l % N of wavefront l / N, for up to 64 / N wavefronts a turn
-        for (int w0 = 0; w0 < nwaves; w0 += 64 / N) {
-            const int k = lane % N, w = w0 + lane / N;
-            const bool live = lane < (64 / N) * N && w < nwaves;
-            const int mine = live ? tmp[w * N + k] : 0;
-            int run = mine;  // inclusive over the wavefronts of this turn, same k: stride N lanes
-#pragma unroll
-            for (int d = N; d < 64; d <<= 1) {
-                const int up = __shfl_up(run, d, 64);
-                if (lane >= d) run += up;
-            }
-            const int carry = w0 ? tmp[16 * N + k] : 0;  // total of the turns before
-            if (live) tmp[w * N + k] = carry + run - mine;
-            __builtin_amdgcn_wave_barrier();
-            // the last live wavefront of the turn leaves the running total
-            const int last_w = min(nwaves, w0 + 64 / N) - 1;
-            if (live && w == last_w) tmp[16 * N + k] = carry + run;
-            __builtin_amdgcn_wave_barrier();
+        // a row of 16 lanes per value: lane w of the row holds wavefront w's sum; four values a turn
+        for (int k0 = 0; k0 < N; k0 += 4) {
+            const int k = k0 + (lane >> 4), w = lane & 15;
+            const bool live = k < N && w < nwaves;
+            const int mine = live ? tmp[k * 16 + w] : 0;
+            const int run = row_scan16(mine);
+            if (live) tmp[k * 16 + w] = run - mine;
+            if (k < N && w == 15) tmp[16 * N + k] = run;  // wavefronts that do not exist added 0
         }
     }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < N; k++) {
-        excl[k] = tmp[wave * N + k] + incl[k] - v[k];
+        excl[k] = tmp[k * 16 + wave] + incl[k] - v[k];
         total[k] = tmp[16 * N + k];
     }
     __syncthreads();
