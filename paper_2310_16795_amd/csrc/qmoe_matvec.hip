@@ -51,6 +51,12 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
         if (r >= a.rows) continue;
         const uint32_t kend = min(min(M.row_off[r + 1], M.n_codes), kMaxCodes);
         const uint32_t kbeg = min(M.row_off[r], kend);
+        if (kbeg >= kend) {
+            // a row without codewords (only a corrupt stream has one) decodes to zeros
+            if (l16 == 15)
+                for (int t = 0; t < ntok; t++) reinterpret_cast<float *>(a.out)[(size_t)(slot0 + t) * a.ld_out + r] = 0.0f;
+            continue;
+        }
         // y = scale * (signed sum) + mid * (sum under |weight|); mid = 0 on the symmetric grid
         float scale, mid = 0.0f;
         if constexpr (ASYM) {
@@ -67,11 +73,39 @@ __global__ __launch_bounds__(256) void k_matvec_rows(const ProductArgs a)
             float acc[NA];
 #pragma unroll
             for (int t = 0; t < NA; t++) acc[t] = 0.0f;
+            // A row's steps are a chain (the running column), but what a step needs from memory is not:
+            // the codewords are fetched two steps ahead and their table entries one step ahead, from
+            // addresses that always exist (a lane past the row's end reads the row's last codeword and
+            // drops it), so that only the first step of a row waits for its trips to memory in full.
             int incl = 0;
+            gp_u16 codes = (gp_u16)M.codes;
+            auto code_at = [&](uint32_t k) -> uint32_t { return (uint32_t)codes[min(k, kend - 1u)]; };
+            auto entry_of = [&](uint32_t code) -> Entry {
+                Entry e{0u, 0u};
+                if constexpr (RUN) {
+                    e.e0 = a.code_order ? order_entry((gp_u32)a.order_table, code, (uint32_t)a.n_groups, (uint32_t)a.n_order)
+                                        : ((gp_u32)a.run)[code];
+                } else {
+                    const unsigned long long w = ((gp_u64)a.words)[code];
+                    e.e0 = (uint32_t)w; e.e1 = (uint32_t)(w >> 32);
+                }
+                return e;
+            };
+            uint32_t c_next = code_at(kbeg + 16u + (uint32_t)l16);
+            Entry e_cur = entry_of(code_at(kbeg + (uint32_t)l16));
             for (uint32_t kb = kbeg; kb < kend; kb += 16) {
-                const Step s = decode_step<RUN>(a, M.codes, kb + l16, kend, l16, incl);
-                const Entry e{s.e0, s.e1};
-                accumulate<TBI, DICT, ASYM>(e, xs_addr, 8u * (uint32_t)s.start, acc);
+                const uint32_t c_after = code_at(kb + 32u + (uint32_t)l16);
+                const Entry e_next = entry_of(c_next);
+                Entry e = e_cur;
+                if (kb + (uint32_t)l16 >= kend) { e.e0 = 0u; e.e1 = 0u; }  // past the row's end: an empty run
+                const int len = RUN ? (int)((e.e0 & 0xFFu) >> 3) : 2 * (int)(e.e0 & 15u);
+                // previous step's total sits in lane 15 of the row; lane 0 takes it in
+                const int carry = __builtin_amdgcn_update_dpp(0, incl, kRowRor1, 0xf, 0xf, false);
+                incl = row_scan16(len + (l16 == 0 ? carry : 0));
+                const uint32_t start = min((uint32_t)(incl - len), (uint32_t)a.cols);  // also catches a wrapped index
+                accumulate<TBI, DICT, ASYM>(e, xs_addr, 8u * start, acc);
+                e_cur = e_next;
+                c_next = c_after;
             }
 #pragma unroll
             for (int t = 0; t < NA; t++) acc[t] = row_sum16_to_last(acc[t]);
