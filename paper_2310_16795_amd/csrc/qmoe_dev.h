@@ -101,7 +101,7 @@ struct DispatchArgs {
     int n_tokens, n_experts;
     int *tok_off;   // [E+1]
     int *perm;      // [T]
-    int *counters;  // [8]
+    int *counters;  // [kLayerCounters]
     Item *items_wi, *items_wo, *items_mm;
     int tb_wi, tb_wo;
     int mm_min;     // experts with at least this many tokens go to the matrix-core kernel (tiles of 64)

@@ -11,13 +11,13 @@ namespace {
 // An expert with many tokens is a dense contraction once its ternary weights are
 // in hand: y[token][row] = sum_k x[token][k] * W[row][k].  The scalar kernel
 // would decode the matrix again for every few tokens; this one decodes it once per
-// tile of up to 64 tokens.  A workgroup owns up to 512 rows (one lane per row) and
-// walks the columns 64 at a time.  Every lane keeps a ring of 128 one-byte columns
-// of its row in LDS and decodes its codewords into it sequentially, as far ahead as
-// the ring allows (so the lanes of a wavefront, whose codewords end at different
-// columns, seldom wait for each other); then each wavefront multiplies the 64
-// columns that are complete, for the 64 rows its own lanes decoded, with the
-// tokens' activations on the matrix cores, fp32 accumulators in registers.  The
+// tile of up to 64 tokens.  A wavefront owns 64 rows (one lane per row) and walks
+// the columns 64 at a time.  Every lane keeps a ring of 128 one-byte columns of its
+// row in LDS and decodes its codewords into it sequentially, as far ahead as the
+// ring allows (so the lanes of a wavefront, whose codewords end at different
+// columns, seldom wait for each other); then the wavefront multiplies the 64
+// columns that are complete, for the 64 rows its lanes decoded, with the tokens'
+// activations on the matrix cores, fp32 accumulators in registers.  The
 // ring holds the weights as the high byte of bf16 +-2.0 (0x40 / 0xC0, low byte
 // zero), expanded to bf16 by a byte permute when a fragment is read; the factor 2
 // is taken out again, exactly, when a row is written.
