@@ -571,7 +571,7 @@ qmoe_status qmoe_decompress(const qmoe_dict *d, const qmoe_matrix *mats, int cod
     a.n_groups = d->n_groups;
     a.n_order = (int)d->order_table.size();
     const size_t smem = decompress_lds_bytes(a.n_order, n_mats);
-    if (smem > (size_t)di.max_lds) return QMOE_E_LIMIT;  // (the paper's table leaves room for about 5000 matrices a call)
+    if (smem > (size_t)di.max_lds) return QMOE_E_LIMIT;  // (the paper's table leaves room for about 20000 matrices a call)
     // one workgroup per compute unit (its LDS is taken whole); the kernel deals the matrices that have a
     // destination out over them
     const long long total = (long long)n_mats * a.row_blocks;
