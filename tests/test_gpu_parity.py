@@ -1042,3 +1042,106 @@ def test_decode_matvec_in_a_hip_graph(gpu, ddict, oracle_dict):
     for y, x in ((y_few, x_few), (y_many, x_many)):
         y_ref, bound = oracle.matvec(tern, scale, x, with_bound=True)
         _check_product(y.cpu().numpy(), y_ref, bound, f"batch {x.shape[0]}")
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_layer_shapes(gpu, ddict, oracle_dict, seed):
+    """Seeded random layer calls inside the documented limits: expert counts, widths (multiples of 2, 8 and 64),
+    token counts on both sides of every tile size and of the call size that switches the matrix-core kernel on,
+    both numberings, both stream layouts, both grids, skewed routing, a token without an expert.  Outputs of up
+    to 24 tokens a case against the oracle; the same layer decompressed (when its format allows) bit for bit,
+    destinations at different 16-byte offsets, nothing written outside them."""
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        E = int(rng.choice([1, 2, 5, 12, 33, 130]))
+        mult = int(rng.choice([2, 8, 8, 8, 64]))
+        big = rng.integers(0, 8) == 0
+        d_model = mult * int(rng.integers(max(1, 40 // mult), (2200 if big else 600) // mult))
+        d_ff = mult * int(rng.integers(max(1, 40 // mult), (3300 if big else 900) // mult))
+        T = int(rng.choice([1, 2, 3, 8, 17, 64, 65, 70, 129, 300, 1024, 1030, 1300, 2100]))
+        order = int(rng.integers(0, 2))
+        lanes = bool(order and rng.integers(0, 2))
+        minmax = bool(rng.integers(0, 3) == 0)
+        skew = bool(rng.integers(0, 2))
+        label = f"seed {seed} case {case}: E={E} d_model={d_model} d_ff={d_ff} T={T} order={order} lanes={lanes} minmax={minmax}"
+        print(label, flush=True)
+        w = synth.WORKLOADS["switch_base128"].scaled(n_experts=E, d_model=d_model, d_ff=d_ff, n_tokens=T)
+        idx, x = w.expert_idx(), w.tokens()
+        if skew and E > 1:
+            idx[: T // 2] = int(rng.integers(0, E))
+        if T > 5:
+            idx[int(rng.integers(0, T))] = -1 if rng.integers(0, 2) else E + 3
+        if lanes and min(q.qmoe_plan_lanes(ddict.handle, d_ff, d_model, E, T),
+                         q.qmoe_plan_lanes(ddict.handle, d_model, d_ff, E, T)) <= 0:
+            lanes = False
+        layer = _build_layer(w, oracle_dict, gpu, order_of=ddict if order else None, minmax=minmax,
+                             lanes_for_tokens=T if lanes else 0)
+        gate = rng.uniform(0.2, 1.0, idx.size)
+        y, wsout = _run_layer(layer, ddict, x, idx, gpu, gate)
+        valid = [t for t in range(T) if 0 <= idx[t] < E]
+        pick = valid if len(valid) <= 24 else [int(v) for v in rng.choice(valid, 24, replace=False)]
+        _check_layer(w, idx, x, y, wsout, pick, gate, asym=minmax)
+        for t in range(T):
+            if not 0 <= idx[t] < E:
+                assert np.all(y[t] == 0.0), f"{label}: dropped token {t} not zeroed"
+        if not (order and not minmax and d_model % 8 == 0 and d_ff % 8 == 0 and E <= 33 and d_model * d_ff <= 600000):
+            continue
+        for which, rows, cols in (("wi", d_ff, d_model), ("wo", d_model, d_ff)):
+            kind = int(rng.integers(0, 2))
+            skip = int(rng.integers(0, E + 1))  # E: none skipped
+            span = rows * cols + 256
+            pool = torch.full((E * span,), 77, dtype=torch.int8 if kind == 0 else torch.int16, device=gpu)
+            offs = [e * span + 8 * int(rng.integers(0, 8)) * (2 if kind == 0 else 1) for e in range(E)]
+            ptrs = torch.tensor([0 if e == skip else pool.data_ptr() + offs[e] * pool.element_size() for e in range(E)],
+                                dtype=torch.int64, device=gpu)
+            q.qmoe_decompress(ddict.handle, layer.desc_dev[which], 1, E, rows, cols, kind, ptrs)
+            torch.cuda.synchronize()
+            host = pool.cpu().numpy()
+            outside = np.ones(host.size, dtype=bool)
+            for e in range(E):
+                if e == skip:
+                    continue
+                got = host[offs[e]: offs[e] + rows * cols].reshape(rows, cols)
+                outside[offs[e]: offs[e] + rows * cols] = False
+                tern = w.wi_ternary(e) if which == "wi" else w.wo_ternary(e)
+                if kind == 0:
+                    assert np.array_equal(got, tern), f"{label}: {which} expert {e}"
+                else:
+                    sb = _bf16_bits_of_f16(w.wi_scale(e) if which == "wi" else w.wo_scale(e))[:, None].astype(np.uint16)
+                    want = np.where(tern == 0, np.uint16(0), np.where(tern > 0, sb, sb | np.uint16(0x8000)))
+                    assert np.array_equal(got.view(np.uint16), want.astype(np.uint16)), f"{label}: {which} expert {e}"
+            assert (host[outside] == 77).all(), f"{label}: {which} written outside the destinations"
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_single_matrix_shapes(gpu, ddict, oracle_dict, seed):
+    """Seeded random single-matrix calls: 1..2200 rows, 2..6200 columns, zero fractions from 0 to 1, batches on
+    both sides of the tile sizes and of the switch to the matrix-core kernel, both numberings, both grids: the
+    product against the oracle and the decoded matrix bit for bit."""
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        mult = int(rng.choice([2, 8, 8, 64]))
+        big = rng.integers(0, 6) == 0
+        rows = int(rng.integers(1, 2200 if big else 400))
+        cols = mult * int(rng.integers(1, (6200 if big else 900) // mult))
+        p0 = float(rng.choice([0.0, 0.5, 0.8, 0.885, 0.9, 0.97, 1.0]))
+        batch = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 33, 64, 65, 200, 513]))
+        order = int(rng.integers(0, 2))
+        minmax = bool(rng.integers(0, 3) == 0)
+        label = f"seed {seed} case {case}: {rows}x{cols} p0={p0} batch={batch} order={order} minmax={minmax}"
+        print(label, flush=True)
+        s = 1000 * seed + case
+        tern = synth.ternary(s, rows, cols, p0)
+        scale = None if minmax else synth.uniform_f16(s + 1, (rows,), 0.01, 0.1)
+        pairs = synth.minmax_bf16(s + 2, rows, 0.01, 0.1) if minmax else None
+        M = _upload(oracle_dict, tern, scale, gpu, order_of=ddict if order else None, minmax=pairs)
+        x = synth.normal_bf16(s + 3, (batch, cols))
+        y = torch.full((batch, rows), float("nan"), dtype=torch.float32, device=gpu)
+        q.qmoe_decode_matvec(ddict.handle, M.desc, _to_dev16(x, gpu), y)
+        torch.cuda.synchronize()
+        y_ref, bound = oracle.matvec(tern, scale, x, with_bound=True, minmax_bf16=pairs)
+        _check_product(y.cpu().numpy(), y_ref, bound, label)
+        out = torch.full((rows, cols), 7, dtype=torch.int8, device=gpu)
+        q.qmoe_decode_dense(ddict.handle, M.desc, out, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), tern), label
